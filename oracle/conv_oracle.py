@@ -1,0 +1,156 @@
+"""ctypes front end of oracle/conv_oracle.c.  TEST INFRASTRUCTURE ONLY.
+
+Every function takes float32 numpy arrays in NCHW / KCRS order (the exact values
+the GPU path is given: fp32, or bf16 widened to fp32) and returns float64
+results computed by the plain loop nests in conv_oracle.c.  Nothing in the
+product package imports this module, and this module imports nothing from it.
+
+The operations are the convolution layer's forward pass and its two
+derivatives (MXNet paper, Section 2.1 for forward/backward of a symbol and
+Section 3.1 for the hand-written "big" layer operators); the paper prints no
+formula, so conv_oracle.c's header states the definition used.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libconv_oracle.so")
+_lib = None
+
+_I = ctypes.c_int
+_LL = ctypes.c_longlong
+_FP = ctypes.POINTER(ctypes.c_float)
+_DP = ctypes.POINTER(ctypes.c_double)
+_LP = ctypes.POINTER(ctypes.c_longlong)
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from oracle.build_oracle import build
+        build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    nine = [_I] * 9
+    lib.orc_out_dim.argtypes = [_I, _I, _I, _I]
+    lib.orc_out_dim.restype = _I
+    for name in ("orc_conv2d_fwd", "orc_conv2d_bwd_data", "orc_conv2d_bwd_weight"):
+        f = getattr(lib, name)
+        f.argtypes = nine + [_FP, _FP, _DP]
+        f.restype = None
+    for name in ("orc_conv2d_fwd_at", "orc_conv2d_bwd_data_at", "orc_conv2d_bwd_weight_at"):
+        f = getattr(lib, name)
+        f.argtypes = nine + [_FP, _FP, _LL, _LP, _DP, _DP]
+        f.restype = None
+    lib.orc_num_threads.argtypes = []
+    lib.orc_num_threads.restype = _I
+    _lib = lib
+    return lib
+
+
+def _f32(a, shape):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.shape != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {a.shape}")
+    return a
+
+
+def _fp(a):
+    return a.ctypes.data_as(_FP)
+
+
+def _dp(a):
+    return a.ctypes.data_as(_DP)
+
+
+def out_dim(size, filt, stride, pad):
+    return int(_load().orc_out_dim(size, filt, stride, pad))
+
+
+def num_threads():
+    return int(_load().orc_num_threads())
+
+
+def _check(N, C, H, W, K, R, S, stride, pad):
+    if min(N, C, H, W, K, R, S, stride) <= 0 or pad < 0 or H + 2 * pad < R or W + 2 * pad < S:
+        raise ValueError("invalid convolution shape")
+
+
+def conv2d_fwd(x, w, stride, pad):
+    """y[N,K,P,Q] (float64) from x[N,C,H,W], w[K,C,R,S]."""
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert C2 == C
+    _check(N, C, H, W, K, R, S, stride, pad)
+    x = _f32(x, (N, C, H, W)); w = _f32(w, (K, C, R, S))
+    P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    y = np.empty((N, K, P, Q), dtype=np.float64)
+    _load().orc_conv2d_fwd(N, C, H, W, K, R, S, stride, pad, _fp(x), _fp(w), _dp(y))
+    return y
+
+
+def conv2d_bwd_data(dy, w, x_shape, stride, pad):
+    """dx[N,C,H,W] (float64) from dy[N,K,P,Q], w[K,C,R,S]."""
+    N, C, H, W = x_shape
+    K, C2, R, S = w.shape
+    assert C2 == C
+    _check(N, C, H, W, K, R, S, stride, pad)
+    P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    dy = _f32(dy, (N, K, P, Q)); w = _f32(w, (K, C, R, S))
+    dx = np.empty((N, C, H, W), dtype=np.float64)
+    _load().orc_conv2d_bwd_data(N, C, H, W, K, R, S, stride, pad, _fp(dy), _fp(w), _dp(dx))
+    return dx
+
+
+def conv2d_bwd_weight(x, dy, w_shape, stride, pad):
+    """dw[K,C,R,S] (float64) from x[N,C,H,W], dy[N,K,P,Q]."""
+    N, C, H, W = x.shape
+    K, C2, R, S = w_shape
+    assert C2 == C
+    _check(N, C, H, W, K, R, S, stride, pad)
+    P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    x = _f32(x, (N, C, H, W)); dy = _f32(dy, (N, K, P, Q))
+    dw = np.empty((K, C, R, S), dtype=np.float64)
+    _load().orc_conv2d_bwd_weight(N, C, H, W, K, R, S, stride, pad, _fp(x), _fp(dy), _dp(dw))
+    return dw
+
+
+def _at(name, dims, a, b, idx):
+    idx = np.ascontiguousarray(idx, dtype=np.int64).ravel()
+    val = np.empty(idx.size, dtype=np.float64)
+    den = np.empty(idx.size, dtype=np.float64)
+    getattr(_load(), name)(*dims, _fp(a), _fp(b), idx.size,
+                           idx.ctypes.data_as(_LP), _dp(val), _dp(den))
+    return val, den
+
+
+def conv2d_fwd_at(x, w, stride, pad, idx):
+    """(value, D) of y at flat NKPQ indices idx; D = sum |x||w| over the same taps."""
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    _check(N, C, H, W, K, R, S, stride, pad)
+    x = _f32(x, (N, C, H, W)); w = _f32(w, (K, C, R, S))
+    return _at("orc_conv2d_fwd_at", (N, C, H, W, K, R, S, stride, pad), x, w, idx)
+
+
+def conv2d_bwd_data_at(dy, w, x_shape, stride, pad, idx):
+    """(value, D) of dx at flat NCHW indices idx; D = sum |dy||w|."""
+    N, C, H, W = x_shape
+    K, _, R, S = w.shape
+    _check(N, C, H, W, K, R, S, stride, pad)
+    P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    dy = _f32(dy, (N, K, P, Q)); w = _f32(w, (K, C, R, S))
+    return _at("orc_conv2d_bwd_data_at", (N, C, H, W, K, R, S, stride, pad), dy, w, idx)
+
+
+def conv2d_bwd_weight_at(x, dy, w_shape, stride, pad, idx):
+    """(value, D) of dw at flat KCRS indices idx; D = sum |dy||x|."""
+    N, C, H, W = x.shape
+    K, _, R, S = w_shape
+    _check(N, C, H, W, K, R, S, stride, pad)
+    P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    x = _f32(x, (N, C, H, W)); dy = _f32(dy, (N, K, P, Q))
+    return _at("orc_conv2d_bwd_weight_at", (N, C, H, W, K, R, S, stride, pad), x, dy, idx)
