@@ -1,0 +1,130 @@
+/*
+ * mxc.h -- C ABI of the MI355X (gfx950) conv2d library.
+ *
+ * The three compute calls are the convolution layer of the MXNet paper: the
+ * hand-optimised "big" operator of Section 3.1 (Graph Optimization), whose
+ * forward and backward evaluation Section 2.1 describes and whose kernels
+ * Section 4 ("Raw performance") reports as taking most of the run time of the
+ * CNN benchmarks.  The paper prints no formula; the definitions below are the
+ * ones this library implements.
+ *
+ * Notation.  x[N,C,H,W] input, w[K,C,R,S] filter, y/dy[N,K,P,Q] output and its
+ * gradient, with
+ *     P = floor((H + 2*pad - R)/stride) + 1,  Q = floor((W + 2*pad - S)/stride) + 1.
+ * One stride and one pad serve both axes; dilation 1, groups 1, no bias;
+ * cross-correlation (no filter flip); x outside the image reads as 0.
+ *
+ * Common rules for every call.
+ *   - All data pointers are DEVICE pointers on the current HIP device, 16-byte
+ *     aligned, owned by the caller; the library allocates no device memory,
+ *     never synchronises and never changes the current device.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  Calls return as soon as the launches are queued.
+ *   - `dtype` is the element type of x, w, y, dy, dx: MXC_F32, or MXC_BF16
+ *     (bf16 storage, fp32 accumulation, results rounded to nearest-even).
+ *     dw is ALWAYS fp32, for both dtypes.
+ *   - `layout` says how the caller's tensors are stored:
+ *       MXC_NCHW: x[N][C][H][W], w/dw[K][C][R][S], y/dy[N][K][P][Q]
+ *       MXC_NHWC: x[N][H][W][C], w/dw[K][R][S][C], y/dy[N][P][Q][K]
+ *     all dense.  Kernels work in NHWC/KRSC; NCHW tensors are converted through
+ *     the workspace.
+ *   - Outputs are fully overwritten (no accumulation into them).
+ *   - `workspace` is scratch memory of at least the size reported by
+ *     mxc_conv2d_workspace_bytes for the same arguments (may be NULL when that
+ *     size is 0).  Its contents are undefined afterwards.  Two calls that share
+ *     a workspace must be ordered on one stream.
+ *   - Return value: MXC_OK or an error code; on error nothing was launched.
+ *     No call throws, aborts or exits.  Shapes are checked before pointers.
+ */
+#ifndef MXC_H
+#define MXC_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MXC_OK = 0,
+    MXC_ERR_NULL = 1,        /* a required pointer is NULL                         */
+    MXC_ERR_SHAPE = 2,       /* non-positive dim/stride, negative pad, empty output */
+    MXC_ERR_UNSUPPORTED = 3, /* unknown dtype / layout / pass                       */
+    MXC_ERR_WORKSPACE = 4,   /* workspace missing or smaller than required          */
+    MXC_ERR_ALIGN = 5,       /* a pointer is not 16-byte aligned                    */
+    MXC_ERR_LAUNCH = 6       /* the HIP runtime rejected a kernel launch            */
+};
+
+enum { MXC_F32 = 0, MXC_BF16 = 1 };
+enum { MXC_NCHW = 0, MXC_NHWC = 1 };
+enum { MXC_FWD = 0, MXC_BWD_DATA = 1, MXC_BWD_WEIGHT = 2 };
+
+/*
+ * Forward (the layer's "forward" evaluation, paper Section 2.1):
+ *   y[n,k,p,q] = sum_{c,r,s} x[n,c,p*stride-pad+r,q*stride-pad+s] * w[k,c,r,s]
+ * x, w: inputs; y: output (N*K*P*Q elements of `dtype`).
+ */
+int mxc_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                   int dtype, int layout,
+                   const void *x, const void *w, void *y,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward w.r.t. the input (derivative of forward in x; paper Section 2.1,
+ * "backward"):
+ *   dx[n,c,h,v] = sum over (k,r,s) such that p=(h+pad-r)/stride and
+ *                 q=(v+pad-s)/stride are integers inside the output,
+ *                 of dy[n,k,p,q] * w[k,c,r,s].
+ * Every element of dx is written; positions no filter tap reaches get 0.
+ * dy, w: inputs; dx: output (N*C*H*W elements of `dtype`).
+ */
+int mxc_conv2d_bwd_data(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                        int dtype, int layout,
+                        const void *dy, const void *w, void *dx,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward w.r.t. the filter (derivative of forward in w; the gradient that the
+ * paper's update step w -= eta*g of Section 2.2 consumes):
+ *   dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x[n,c,p*stride-pad+r,q*stride-pad+s]
+ * x, dy: inputs of `dtype`; dw: output, K*C*R*S fp32 values in the filter order
+ * of `layout`.  The reduction is split across workgroups and summed in a fixed
+ * order: results are bit-identical from run to run.
+ */
+int mxc_conv2d_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                          int dtype, int layout,
+                          const void *x, const void *dy, void *dw,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Workspace size in bytes that `pass` (MXC_FWD / MXC_BWD_DATA / MXC_BWD_WEIGHT)
+ * needs for these arguments, written to *out_bytes (a HOST pointer).  Touches
+ * no GPU state.
+ */
+int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R, int S,
+                               int stride, int pad, int dtype, int layout, size_t *out_bytes);
+
+/*
+ * Layout conversion of a dense 4-D tensor between [n][c][h][w] and [n][h][w][c]
+ * (the conversion a network does once at entry and exit when activations stay
+ * NHWC between layers).  Also converts filters KCRS <-> KRSC with n=K, h=R, w=S.
+ * src and dst are device pointers and must not overlap.  src_layout ==
+ * dst_layout is a plain copy.
+ */
+int mxc_layout_convert(int n, int c, int h, int w, int dtype, int src_layout, int dst_layout,
+                       const void *src, void *dst, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code (host memory, never freed). */
+const char *mxc_status_string(int status);
+
+/* Name of the kernel variant the calling thread's last successful compute call
+ * chose (for logs and the bench); "" before any call.  Host memory, thread-local. */
+const char *mxc_last_variant(void);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int mxc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MXC_H */

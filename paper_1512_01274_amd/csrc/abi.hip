@@ -1,0 +1,231 @@
+// C ABI entry points: argument validation, workspace carving, layout handling
+// and kernel selection.  See include/mxc.h for the contract of every call.
+#include <string.h>
+
+#include "mxc_internal.h"
+
+namespace mxc {
+
+namespace {
+
+thread_local char g_variant[128] = "";
+
+void set_variant(const char *pass, const char *name)
+{
+    snprintf(g_variant, sizeof(g_variant), "%s:%s", pass, name);
+}
+
+// Sequential carve-out of the caller's workspace.  The same code path runs in
+// "dry" mode (base == nullptr, nothing launched) to answer the size query, so
+// the reported size is by construction what a real call consumes.
+struct Carver {
+    char *base;
+    size_t used = 0;
+    explicit Carver(void *b) : base((char *)b) {}
+    void *take(size_t bytes)
+    {
+        const size_t off = used;
+        used += align_up(bytes, 256);
+        return base ? base + off : nullptr;
+    }
+};
+
+int validate_shape(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                   ConvShape *out)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+        return MXC_ERR_SHAPE;
+    if ((long long)H + 2LL * pad < R || (long long)W + 2LL * pad < S) return MXC_ERR_SHAPE;
+    if (dtype != MXC_F32 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
+    if (layout != MXC_NCHW && layout != MXC_NHWC) return MXC_ERR_UNSUPPORTED;
+    ConvShape s{N, C, H, W, K, R, S, stride, pad, (H + 2 * pad - R) / stride + 1, (W + 2 * pad - S) / stride + 1};
+    // Per-tensor element counts must stay below 2^40 (kernels index with 64 bits; this only
+    // guards the size arithmetic) and the filter below 2^31 elements.
+    const long double lim = 1099511627776.0L;
+    if ((long double)N * C * H * W >= lim || (long double)N * K * s.P * s.Q >= lim ||
+        (long double)K * C * R * S >= 2147483648.0L)
+        return MXC_ERR_SHAPE;
+    *out = s;
+    return MXC_OK;
+}
+
+bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+// ---- passes in the working layout (NHWC / KRSC) --------------------------------
+// dry == true: only account workspace.
+
+int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *y, Carver &ws, hipStream_t st, bool dry)
+{
+    (void)ws;
+    if (dry) return MXC_OK;
+    set_variant("fwd", "direct");
+    return direct_fwd(s, dtype, x, w, y, st);
+}
+
+int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, Carver &ws, hipStream_t st,
+                  bool dry)
+{
+    (void)ws;
+    if (dry) return MXC_OK;
+    set_variant("bwd_data", "direct");
+    return direct_bwd_data(s, dtype, dy, w, dx, st);
+}
+
+int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw, Carver &ws, hipStream_t st,
+                    bool dry)
+{
+    const int splits = direct_bwd_weight_splits(s);
+    float *partial = (float *)ws.take((size_t)splits * s.K * s.R * s.S * s.C * sizeof(float));
+    if (dry) return MXC_OK;
+    set_variant("bwd_weight", "direct_splitk");
+    return direct_bwd_weight(s, dtype, x, dy, dw, partial, splits, st);
+}
+
+// ---- one driver per pass: handles the caller's layout ---------------------------
+
+#define MXC_TRY(expr)                 \
+    do {                              \
+        const int rc_ = (expr);       \
+        if (rc_ != MXC_OK) return rc_; \
+    } while (0)
+
+int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a, const void *b, void *out, Carver &ws,
+             hipStream_t st, bool dry)
+{
+    const int eb = (int)elem_size(dtype);
+    const size_t nx = (size_t)s.N * s.C * s.H * s.W, nw = (size_t)s.K * s.C * s.R * s.S,
+                 ny = (size_t)s.N * s.K * s.P * s.Q;
+    if (layout == MXC_NHWC) {
+        switch (pass) {
+        case MXC_FWD: return fwd_nhwc(s, dtype, a, b, out, ws, st, dry);
+        case MXC_BWD_DATA: return bwd_data_nhwc(s, dtype, a, b, out, ws, st, dry);
+        default: return bwd_weight_nhwc(s, dtype, a, b, (float *)out, ws, st, dry);
+        }
+    }
+    // NCHW at the boundary: convert operands into the workspace, compute, convert the result back.
+    if (pass == MXC_FWD) {
+        void *x2 = ws.take(nx * eb), *w2 = ws.take(nw * eb), *y2 = ws.take(ny * eb);
+        if (!dry) {
+            MXC_TRY(launch_transpose(a, x2, s.N, s.C, s.H * s.W, eb, st));
+            MXC_TRY(launch_transpose(b, w2, s.K, s.C, s.R * s.S, eb, st));
+        }
+        MXC_TRY(fwd_nhwc(s, dtype, x2, w2, y2, ws, st, dry));
+        if (!dry) MXC_TRY(launch_transpose(y2, out, s.N, s.P * s.Q, s.K, eb, st));
+        return MXC_OK;
+    }
+    if (pass == MXC_BWD_DATA) {
+        void *dy2 = ws.take(ny * eb), *w2 = ws.take(nw * eb), *dx2 = ws.take(nx * eb);
+        if (!dry) {
+            MXC_TRY(launch_transpose(a, dy2, s.N, s.K, s.P * s.Q, eb, st));
+            MXC_TRY(launch_transpose(b, w2, s.K, s.C, s.R * s.S, eb, st));
+        }
+        MXC_TRY(bwd_data_nhwc(s, dtype, dy2, w2, dx2, ws, st, dry));
+        if (!dry) MXC_TRY(launch_transpose(dx2, out, s.N, s.H * s.W, s.C, eb, st));
+        return MXC_OK;
+    }
+    void *x2 = ws.take(nx * eb), *dy2 = ws.take(ny * eb);
+    float *dw2 = (float *)ws.take(nw * sizeof(float));
+    if (!dry) {
+        MXC_TRY(launch_transpose(a, x2, s.N, s.C, s.H * s.W, eb, st));
+        MXC_TRY(launch_transpose(b, dy2, s.N, s.K, s.P * s.Q, eb, st));
+    }
+    MXC_TRY(bwd_weight_nhwc(s, dtype, x2, dy2, dw2, ws, st, dry));
+    if (!dry) MXC_TRY(launch_transpose(dw2, out, s.K, s.R * s.S, s.C, 4, st));
+    return MXC_OK;
+}
+
+int entry(int pass, int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+          const void *a, const void *b, void *out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (!a || !b || !out) return MXC_ERR_NULL;
+    if (misaligned(a) || misaligned(b) || misaligned(out) || misaligned(workspace)) return MXC_ERR_ALIGN;
+    Carver need(nullptr);
+    MXC_TRY(run_pass(pass, s, dtype, layout, nullptr, nullptr, nullptr, need, nullptr, true));
+    if (need.used > 0 && (!workspace || workspace_bytes < need.used)) return MXC_ERR_WORKSPACE;
+    Carver ws(workspace);
+    return run_pass(pass, s, dtype, layout, a, b, out, ws, (hipStream_t)hip_stream, false);
+}
+
+}  // namespace
+}  // namespace mxc
+
+using namespace mxc;
+
+extern "C" {
+
+int mxc_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                   const void *x, const void *w, void *y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return entry(MXC_FWD, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, w, y, workspace, workspace_bytes,
+                 hip_stream);
+}
+
+int mxc_conv2d_bwd_data(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                        const void *dy, const void *w, void *dx, void *workspace, size_t workspace_bytes,
+                        void *hip_stream)
+{
+    return entry(MXC_BWD_DATA, N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, dx, workspace, workspace_bytes,
+                 hip_stream);
+}
+
+int mxc_conv2d_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                          const void *x, const void *dy, void *dw, void *workspace, size_t workspace_bytes,
+                          void *hip_stream)
+{
+    return entry(MXC_BWD_WEIGHT, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, workspace, workspace_bytes,
+                 hip_stream);
+}
+
+int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               int dtype, int layout, size_t *out_bytes)
+{
+    if (!out_bytes) return MXC_ERR_NULL;
+    if (pass != MXC_FWD && pass != MXC_BWD_DATA && pass != MXC_BWD_WEIGHT) return MXC_ERR_UNSUPPORTED;
+    ConvShape s;
+    const int rc = validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s);
+    if (rc != MXC_OK) return rc;
+    Carver need(nullptr);
+    const int rc2 = run_pass(pass, s, dtype, layout, nullptr, nullptr, nullptr, need, nullptr, true);
+    if (rc2 != MXC_OK) return rc2;
+    *out_bytes = need.used;
+    return MXC_OK;
+}
+
+int mxc_layout_convert(int n, int c, int h, int w, int dtype, int src_layout, int dst_layout, const void *src,
+                       void *dst, void *hip_stream)
+{
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return MXC_ERR_SHAPE;
+    if ((long double)n * c * h * w >= 1099511627776.0L || (long long)h * w > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+    if (dtype != MXC_F32 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
+    if ((src_layout != MXC_NCHW && src_layout != MXC_NHWC) || (dst_layout != MXC_NCHW && dst_layout != MXC_NHWC))
+        return MXC_ERR_UNSUPPORTED;
+    if (!src || !dst) return MXC_ERR_NULL;
+    if (misaligned(src) || misaligned(dst)) return MXC_ERR_ALIGN;
+    const int eb = (int)elem_size(dtype);
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (src_layout == dst_layout) return launch_copy(src, dst, (size_t)n * c * h * w * eb, st);
+    if (src_layout == MXC_NCHW) return launch_transpose(src, dst, n, c, h * w, eb, st);
+    return launch_transpose(src, dst, n, h * w, c, eb, st);
+}
+
+const char *mxc_status_string(int status)
+{
+    switch (status) {
+    case MXC_OK: return "ok";
+    case MXC_ERR_NULL: return "a required pointer is NULL";
+    case MXC_ERR_SHAPE: return "invalid shape: non-positive dimension or stride, negative pad, or empty output";
+    case MXC_ERR_UNSUPPORTED: return "unsupported dtype, layout or pass";
+    case MXC_ERR_WORKSPACE: return "workspace missing or too small (see mxc_conv2d_workspace_bytes)";
+    case MXC_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
+    case MXC_ERR_LAUNCH: return "the HIP runtime rejected a kernel launch";
+    default: return "unknown status";
+    }
+}
+
+const char *mxc_last_variant(void) { return g_variant; }
+
+int mxc_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+// Layout conversion kernels: batched 2-D transposes through LDS.
+//
+// NCHW -> NHWC of an activation tensor is, per image, the transpose of a
+// [C][H*W] matrix; KCRS -> KRSC of a filter bank is the same with [C][R*S].
+// Pure data movement: 1 read + 1 write of every element, HBM-bound.
+#include "mxc_internal.h"
+
+namespace mxc {
+
+namespace {
+
+constexpr int TILE = 64;
+
+// One 64x64 tile per workgroup of 256 threads.  Reads are contiguous along
+// `cols`, writes contiguous along `rows`; the +1 pad keeps the column reads of
+// the LDS tile off a single bank.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_tile_kernel(const T *__restrict__ src, T *__restrict__ dst,
+                                                             int rows, int cols)
+{
+    __shared__ T tile[TILE][TILE + 1];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int c0 = blockIdx.x * TILE, r0 = blockIdx.y * TILE;
+    const size_t base = (size_t)blockIdx.z * rows * cols;
+#pragma unroll
+    for (int i = 0; i < TILE; i += 4) {
+        const int r = r0 + ty + i, c = c0 + tx;
+        if (r < rows && c < cols) tile[ty + i][tx] = src[base + (size_t)r * cols + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TILE; i += 4) {
+        const int c = c0 + ty + i, r = r0 + tx;
+        if (r < rows && c < cols) dst[base + (size_t)c * rows + r] = tile[tx][ty + i];
+    }
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16,
+                                                   const unsigned char *__restrict__ tail_src,
+                                                   unsigned char *__restrict__ tail_dst, int tail)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    if (blockIdx.x == 0 && (int)threadIdx.x < tail) tail_dst[threadIdx.x] = tail_src[threadIdx.x];
+}
+
+}  // namespace
+
+int launch_transpose(const void *src, void *dst, int batch, int rows, int cols, int elem_bytes, hipStream_t stream)
+{
+    if (batch <= 0 || rows <= 0 || cols <= 0) return MXC_ERR_SHAPE;
+    const unsigned gx = (unsigned)((cols + TILE - 1) / TILE), gy = (unsigned)((rows + TILE - 1) / TILE);
+    if (gy > 65535u || (unsigned)batch > 65535u) return MXC_ERR_SHAPE;
+    dim3 grid(gx, gy, (unsigned)batch), block(256);
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(transpose_tile_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t *)src,
+                           (uint16_t *)dst, rows, cols);
+    else if (elem_bytes == 4)
+        hipLaunchKernelGGL(transpose_tile_kernel<uint32_t>, grid, block, 0, stream, (const uint32_t *)src,
+                           (uint32_t *)dst, rows, cols);
+    else
+        return MXC_ERR_UNSUPPORTED;
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
+int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream)
+{
+    if (bytes == 0) return MXC_OK;
+    const size_t n16 = bytes / 16;
+    const int tail = (int)(bytes % 16);
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4 *)src, (uint4 *)dst, n16,
+                       (const unsigned char *)src + n16 * 16, (unsigned char *)dst + n16 * 16, tail);
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
+}  // namespace mxc

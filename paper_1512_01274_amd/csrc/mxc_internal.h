@@ -1,0 +1,51 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mxc.h"
+
+namespace mxc {
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+// One convolution problem in the library's working layout: activations NHWC,
+// filters KRSC.  P and Q are derived by the ABI layer.
+struct ConvShape {
+    int N, C, H, W, K, R, S, stride, pad, P, Q;
+};
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// Round-to-nearest-even; inputs are finite in this library's use.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_f32(const float *p) { return *p; }
+__device__ __forceinline__ float load_f32(const bf16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void store_f32(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_f32(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline size_t elem_size(int dtype) { return dtype == MXC_BF16 ? 2 : 4; }
+
+// ---- layout.hip ------------------------------------------------------------
+// Batched 2-D transpose: src[b][rows][cols] -> dst[b][cols][rows], element size 2 or 4 bytes.
+int launch_transpose(const void *src, void *dst, int batch, int rows, int cols, int elem_bytes,
+                     hipStream_t stream);
+int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
+
+// ---- direct.hip: one-thread-per-output kernels, any shape, NHWC/KRSC --------
+int direct_fwd(const ConvShape &s, int dtype, const void *x, const void *w, void *y, hipStream_t st);
+int direct_bwd_data(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, hipStream_t st);
+// partial: fp32 scratch of direct_bwd_weight_splits(s) * K*R*S*C floats
+int direct_bwd_weight_splits(const ConvShape &s);
+int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw,
+                      float *partial, int splits, hipStream_t st);
+
+}  // namespace mxc

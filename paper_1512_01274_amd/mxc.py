@@ -1,0 +1,125 @@
+"""ctypes binding over libmxc.so: argument marshalling only.
+
+Function names and argument order mirror include/mxc.h.  Tensors are torch
+tensors on the GPU (torch is used for device memory and streams, nothing else);
+every step of the computation runs in the library's HIP kernels.  There is no
+CPU or PyTorch fallback: if the library cannot be loaded, importing this module
+raises.
+"""
+import ctypes
+import os
+
+import torch
+
+MXC_OK = 0
+MXC_ERR_NULL, MXC_ERR_SHAPE, MXC_ERR_UNSUPPORTED, MXC_ERR_WORKSPACE, MXC_ERR_ALIGN, MXC_ERR_LAUNCH = 1, 2, 3, 4, 5, 6
+MXC_F32, MXC_BF16 = 0, 1
+MXC_NCHW, MXC_NHWC = 0, 1
+MXC_FWD, MXC_BWD_DATA, MXC_BWD_WEIGHT = 0, 1, 2
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmxc.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1512_01274_amd.build`")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_I, _VP, _SZ = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+for _name in ("mxc_conv2d_fwd", "mxc_conv2d_bwd_data", "mxc_conv2d_bwd_weight"):
+    _f = getattr(_lib, _name)
+    _f.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP, _SZ, _VP]
+    _f.restype = _I
+_lib.mxc_conv2d_workspace_bytes.argtypes = [_I] * 12 + [ctypes.POINTER(_SZ)]
+_lib.mxc_conv2d_workspace_bytes.restype = _I
+_lib.mxc_layout_convert.argtypes = [_I] * 7 + [_VP, _VP, _VP]
+_lib.mxc_layout_convert.restype = _I
+_lib.mxc_status_string.argtypes = [_I]
+_lib.mxc_status_string.restype = ctypes.c_char_p
+_lib.mxc_last_variant.argtypes = []
+_lib.mxc_last_variant.restype = ctypes.c_char_p
+_lib.mxc_version.argtypes = []
+_lib.mxc_version.restype = _I
+
+
+class MxcError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__(f"mxc status {status}: {mxc_status_string(status)}")
+
+
+def mxc_status_string(status: int) -> str:
+    return _lib.mxc_status_string(status).decode()
+
+
+def mxc_last_variant() -> str:
+    return _lib.mxc_last_variant().decode()
+
+
+def mxc_version() -> int:
+    return _lib.mxc_version()
+
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return MXC_F32
+    if t == torch.bfloat16:
+        return MXC_BF16
+    raise TypeError(f"unsupported dtype {t}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous GPU tensors")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def mxc_conv2d_workspace_bytes(op, N, C, H, W, K, R, S, stride, pad, dtype, layout) -> int:
+    out = _SZ(0)
+    rc = _lib.mxc_conv2d_workspace_bytes(op, N, C, H, W, K, R, S, stride, pad, dtype, layout, ctypes.byref(out))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+    return int(out.value)
+
+
+def _call(fn, dims, dtype, layout, a, b, out, workspace, stream):
+    ws_ptr = _ptr(workspace) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = fn(*dims, dtype, layout, _ptr(a), _ptr(b), _ptr(out), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_conv2d_fwd(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, w, y, workspace=None, stream=None):
+    _call(_lib.mxc_conv2d_fwd, (N, C, H, W, K, R, S, stride, pad), dtype, layout, x, w, y, workspace, stream)
+
+
+def mxc_conv2d_bwd_data(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, dx, workspace=None, stream=None):
+    _call(_lib.mxc_conv2d_bwd_data, (N, C, H, W, K, R, S, stride, pad), dtype, layout, dy, w, dx, workspace, stream)
+
+
+def mxc_conv2d_bwd_weight(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, workspace=None, stream=None):
+    _call(_lib.mxc_conv2d_bwd_weight, (N, C, H, W, K, R, S, stride, pad), dtype, layout, x, dy, dw, workspace, stream)
+
+
+def mxc_layout_convert(n, c, h, w, dtype, src_layout, dst_layout, src, dst, stream=None):
+    rc = _lib.mxc_layout_convert(n, c, h, w, dtype, src_layout, dst_layout, _ptr(src), _ptr(dst), _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def raw():
+    """The ctypes library handle (tests of the error paths pass raw pointers)."""
+    return _lib
+
+
+def alloc_workspace(nbytes: int, device="cuda"):
+    """A torch byte tensor of at least nbytes (None when nbytes == 0)."""
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)

@@ -1,0 +1,191 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element,
+on the same seeded inputs.  Metric and tolerances: max |gpu - oracle| / D with
+D = sum |a||b| over that output's taps; <= 1e-5 (fp32), <= 1e-2 (bf16); plus a much
+tighter per-element bound derived from the arithmetic (fp32 accumulation + one bf16
+rounding of the result), so that a dropped or misplaced tap cannot hide inside the
+loose budget.  Where D == 0 (no tap reaches the element) the result must be exactly 0.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_1512_01274_amd import inputs as gen
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mxc():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1512_01274_amd import mxc as m
+    return m
+
+
+def check_all_passes(mxc, oracle, dims, dtype, layout, x, w, dy, passes=("fwd", "bwd_data", "bwd_weight")):
+    N, C, H, W, K, R, S, st, pad = dims
+    run = util.Runner(mxc, dims, dtype, layout)
+    ax, aw, ady = np.abs(x), np.abs(w), np.abs(dy)
+    out_bf16 = dtype == "bf16"
+    report = {}
+    if "fwd" in passes:
+        ref, den = oracle.conv2d_fwd(x, w, st, pad), oracle.conv2d_fwd(ax, aw, st, pad)
+        got = run.fwd(x, w)
+        report["fwd"] = (got, ref, den, out_bf16)
+    if "bwd_data" in passes:
+        ref, den = oracle.conv2d_bwd_data(dy, w, x.shape, st, pad), oracle.conv2d_bwd_data(ady, aw, x.shape, st, pad)
+        got = run.bwd_data(dy, w)
+        report["bwd_data"] = (got, ref, den, out_bf16)
+    if "bwd_weight" in passes:
+        ref, den = oracle.conv2d_bwd_weight(x, dy, w.shape, st, pad), oracle.conv2d_bwd_weight(ax, ady, w.shape, st, pad)
+        got = run.bwd_weight(x, dy)
+        report["bwd_weight"] = (got, ref, den, False)
+    for name, (got, ref, den, ob) in report.items():
+        assert got.shape == ref.shape, name
+        err = util.metric(got, ref, den)
+        assert err <= util.TOL[dtype], f"{name} {dims} {dtype} {layout}: err {err:.3e} variant {mxc.mxc_last_variant()}"
+        excess = np.abs(got - ref) - util.tight_bound(ref, den, dtype, ob)
+        worst = np.unravel_index(np.argmax(excess), excess.shape)
+        assert excess.max() <= 0, (f"{name} {dims} {dtype} {layout}: tight bound exceeded at {worst}: "
+                                   f"gpu {got[worst]!r} oracle {ref[worst]!r} D {den[worst]!r}")
+
+
+# ---- config 1 (fp32 single layer), in full, both layouts -----------------------
+
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+def test_config1_full(mxc, oracle, layout):
+    cfg = gen.CONFIGS[0]
+    L, t = gen.layer_inputs(cfg, 0)
+    check_all_passes(mxc, oracle, L.dims(), "f32", layout, t["x"], t["w"], t["dy"])
+
+
+# ---- shape sweep: ragged tiles, strides, pads, floor remainders ----------------
+
+SWEEP = [
+    # N, C, H, W, K, R, S, stride, pad
+    (1, 1, 1, 1, 1, 1, 1, 1, 0),        # smallest problem
+    (2, 3, 9, 7, 5, 3, 3, 1, 1),        # H != W, odd C and K
+    (1, 8, 12, 12, 16, 3, 3, 2, 1),
+    (3, 16, 10, 11, 24, 1, 1, 1, 0),    # 1x1
+    (2, 24, 9, 9, 40, 1, 1, 2, 0),      # 1x1 stride 2: three quarters of dx is zero fill
+    (2, 5, 13, 13, 7, 5, 5, 1, 2),
+    (1, 3, 35, 35, 8, 11, 11, 4, 2),    # first-layer style, (H+2pad-R) % stride != 0
+    (2, 40, 7, 7, 72, 3, 3, 1, 1),      # small spatial, several channel chunks
+    (1, 16, 8, 8, 16, 3, 3, 3, 0),      # stride 3, remainder rows never read
+    (1, 4, 6, 6, 4, 2, 2, 1, 1),        # even filter
+    (2, 8, 5, 5, 8, 3, 3, 1, 2),        # pad == R-1
+    (1, 8, 4, 4, 8, 1, 1, 1, 1),        # pad > R-1 (1x1 with padding)
+    (1, 136, 6, 5, 264, 3, 3, 1, 1),    # C, K beyond one tile with ragged tails
+    (5, 32, 17, 17, 48, 3, 3, 2, 0),
+    (1, 8, 40, 3, 8, 3, 3, 1, 1),       # tall and narrow
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+@pytest.mark.parametrize("dims", SWEEP)
+def test_sweep(mxc, oracle, dims, dtype, layout):
+    x, w, dy = gen.random_case(hash(dims) & 0xFFFF, *dims, dtype=dtype, dist="uniform")
+    check_all_passes(mxc, oracle, dims, dtype, layout, x, w, dy)
+
+
+# ---- the bf16 networks at reduced batch: every layer, full tensors --------------
+
+@pytest.mark.parametrize("cfg_idx", [1, 2, 3, 4])
+def test_network_layers_reduced_batch(mxc, oracle, cfg_idx):
+    cfg = gen.CONFIGS[cfg_idx]
+    for li in range(len(cfg.layers)):
+        L, t = gen.layer_inputs(cfg, li, batch=2)
+        big = L.H >= 112
+        if big:  # keep the oracle's full pass to seconds: one image for the 224/112 layers
+            L, t = gen.layer_inputs(cfg, li, batch=1)
+        check_all_passes(mxc, oracle, L.dims(), cfg.dtype, "nhwc", t["x"], t["w"], t["dy"])
+
+
+# ---- determinism: bitwise equal results from run to run ------------------------
+
+@pytest.mark.parametrize("dims,dtype", [((4, 32, 14, 14, 64, 3, 3, 1, 1), "bf16"), ((2, 16, 16, 16, 32, 3, 3, 1, 1), "f32"),
+                                        ((3, 24, 9, 9, 40, 1, 1, 2, 0), "bf16")])
+def test_bitwise_determinism(mxc, dims, dtype):
+    x, w, dy = gen.random_case(5, *dims, dtype=dtype, dist="normal")
+    run = util.Runner(mxc, dims, dtype, "nhwc")
+    for fn, args in ((run.fwd, (x, w)), (run.bwd_data, (dy, w)), (run.bwd_weight, (x, dy))):
+        a = fn(*args, return_tensor=True)
+        b = fn(*args, return_tensor=True)
+        av = a.view(torch.int16) if a.dtype == torch.bfloat16 else a.view(torch.int32)
+        bv = b.view(torch.int16) if b.dtype == torch.bfloat16 else b.view(torch.int32)
+        assert torch.equal(av, bv)
+
+
+# ---- nothing outside the output is written --------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_canaries_around_outputs(mxc, dtype):
+    dims = (2, 24, 9, 10, 40, 3, 3, 2, 1)
+    N, C, H, W, K, R, S, st, pad = dims
+    P, Q = (H + 2 * pad - R) // st + 1, (W + 2 * pad - S) // st + 1
+    x, w, dy = gen.random_case(6, *dims, dtype=dtype, dist="uniform")
+    dt = mxc.MXC_BF16 if dtype == "bf16" else mxc.MXC_F32
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dx_, dw_, ddy_ = (util.to_device(util.nchw_to_nhwc(a), dtype) for a in (x, w, dy))
+    GUARD = 1024
+    for op, fn, a, b, n_out, odt in (
+            (mxc.MXC_FWD, mxc.mxc_conv2d_fwd, dx_, dw_, N * K * P * Q, td),
+            (mxc.MXC_BWD_DATA, mxc.mxc_conv2d_bwd_data, ddy_, dw_, N * C * H * W, td),
+            (mxc.MXC_BWD_WEIGHT, mxc.mxc_conv2d_bwd_weight, dx_, ddy_, K * C * R * S, torch.float32)):
+        n_pad = (n_out + 7) // 8 * 8          # keeps the output view 16-byte aligned
+        buf = torch.full((GUARD + n_pad + GUARD,), 7.0, dtype=odt, device="cuda")
+        out = buf[GUARD:GUARD + n_out]
+        ws = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *dims, dt, mxc.MXC_NHWC))
+        fn(*dims, dt, mxc.MXC_NHWC, a, b, out, ws)
+        torch.cuda.synchronize()
+        assert (buf[:GUARD] == 7.0).all() and (buf[GUARD + n_out:] == 7.0).all()
+
+
+# ---- layout conversion: exact permutation, both directions, both element sizes --
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 5, 7), (3, 64, 8, 8), (2, 65, 9, 15), (1, 200, 3, 3), (2, 16, 70, 66)])
+def test_layout_convert(mxc, shape, dtype):
+    n, c, h, w = shape
+    g = np.random.Generator(np.random.Philox(key=3))
+    a = g.standard_normal(shape).astype(np.float32)
+    if dtype == "bf16":
+        a = gen.round_to_bf16(a)
+    dt = mxc.MXC_BF16 if dtype == "bf16" else mxc.MXC_F32
+    src = util.to_device(a, dtype)
+    dst = torch.empty_like(src)
+    mxc.mxc_layout_convert(n, c, h, w, dt, mxc.MXC_NCHW, mxc.MXC_NHWC, src, dst)
+    np.testing.assert_array_equal(util.to_host_f64(dst).reshape(n, h, w, c), util.nchw_to_nhwc(a).astype(np.float64))
+    back = torch.empty_like(src)
+    mxc.mxc_layout_convert(n, c, h, w, dt, mxc.MXC_NHWC, mxc.MXC_NCHW, dst, back)
+    np.testing.assert_array_equal(util.to_host_f64(back).reshape(shape), a.astype(np.float64))
+    same = torch.empty_like(src)
+    mxc.mxc_layout_convert(n, c, h, w, dt, mxc.MXC_NCHW, mxc.MXC_NCHW, src, same)
+    assert torch.equal(same.view(torch.uint8), src.view(torch.uint8))
+
+
+# ---- error paths on a live GPU: bad arguments launch nothing --------------------
+
+def test_error_codes_on_gpu(mxc):
+    dims = (2, 8, 6, 6, 8, 3, 3, 1, 1)
+    x = torch.zeros(2 * 8 * 6 * 6, device="cuda")
+    w = torch.zeros(8 * 8 * 3 * 3, device="cuda")
+    y = torch.full((2 * 8 * 6 * 6,), 5.0, device="cuda")
+    need = mxc.mxc_conv2d_workspace_bytes(mxc.MXC_FWD, *dims, mxc.MXC_F32, mxc.MXC_NCHW)
+    assert need > 0
+    with pytest.raises(mxc.MxcError) as e:
+        mxc.mxc_conv2d_fwd(*dims, mxc.MXC_F32, mxc.MXC_NCHW, x, w, y, None)
+    assert e.value.status == mxc.MXC_ERR_WORKSPACE
+    small = mxc.alloc_workspace(need - 256)
+    with pytest.raises(mxc.MxcError) as e:
+        mxc.mxc_conv2d_fwd(*dims, mxc.MXC_F32, mxc.MXC_NCHW, x, w, y, small)
+    assert e.value.status == mxc.MXC_ERR_WORKSPACE
+    with pytest.raises(mxc.MxcError) as e:
+        mxc.mxc_conv2d_fwd(*dims, mxc.MXC_F32, mxc.MXC_NHWC, x[1:], w, y, None)
+    assert e.value.status == mxc.MXC_ERR_ALIGN
+    with pytest.raises(mxc.MxcError) as e:
+        mxc.mxc_conv2d_fwd(2, 8, 6, 6, 8, 9, 9, 1, 1, mxc.MXC_F32, mxc.MXC_NHWC, x, w, y, None)
+    assert e.value.status == mxc.MXC_ERR_SHAPE
+    torch.cuda.synchronize()
+    assert (y == 5.0).all()
