@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv2d hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of a synthetic CNN layer
+stack: the network input is converted NCHW -> NHWC once (layout kernel), then every
+layer runs forward, backward-data and backward-weight (with its split reduction)
+through the C ABI with activations resident in NHWC and filters in KRSC.  Inputs are
+generated from a seed on the host and are resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job TFLOP/s (2*N*K*P*Q*C*R*S flops per pass, three passes
+per layer), the roofline figures of the dominant kernel measured with HIP events, and
+the CPU oracle timed on a bounded sample of the same workload (reported baseline only).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet_b128] [--all]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+PEAK_F32_TFLOPS = 157.3       # fp32 vector / matrix, published
+PEAK_HBM_GBS = 8000.0         # HBM3E, published
+
+
+def algorithmic_bytes(L, op, esize):
+    """Bytes a pass must move: each operand read once, the result written once.  Strided
+    forward/backward-weight count only the input pixels some tap touches; dw is fp32."""
+    touched_h = len({p * L.stride - L.pad + r for p in range(L.P) for r in range(L.R)} & set(range(L.H)))
+    touched_w = len({q * L.stride - L.pad + s for q in range(L.Q) for s in range(L.S)} & set(range(L.W)))
+    x_touched = L.N * L.C * touched_h * touched_w
+    x_all, w, y = L.N * L.C * L.H * L.W, L.K * L.C * L.R * L.S, L.N * L.K * L.P * L.Q
+    if op == "fwd":
+        return esize * (x_touched + w + y)
+    if op == "bwd_data":
+        return esize * (y + w + x_all)
+    return esize * (x_touched + y) + 4 * w
+
+
+class LayerState:
+    """Device tensors of one layer, NHWC/KRSC resident, plus workspaces."""
+
+    def __init__(self, mxc, torch, cfg, li, gen):
+        L, t = gen.layer_inputs(cfg, li)
+        self.L = L
+        self.dims = L.dims()
+        self.dt = mxc.MXC_BF16 if cfg.dtype == "bf16" else mxc.MXC_F32
+        td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        dev = lambda a: gen.to_device(a, cfg.dtype)
+        x_nchw = dev(t["x"])
+        self.x_nchw = x_nchw if li == 0 else None            # only the network input is converted in the step
+        self.x = x_nchw.view(L.N, L.C, L.H, L.W).permute(0, 2, 3, 1).contiguous().view(-1)
+        self.w = dev(t["w"]).view(L.K, L.C, L.R, L.S).permute(0, 2, 3, 1).contiguous().view(-1)
+        self.dy = dev(t["dy"]).view(L.N, L.K, L.P, L.Q).permute(0, 2, 3, 1).contiguous().view(-1)
+        del t
+        self.y = torch.empty(L.N * L.K * L.P * L.Q, dtype=td, device="cuda")
+        self.dx = torch.empty(L.N * L.C * L.H * L.W, dtype=td, device="cuda")
+        self.dw = torch.empty(L.K * L.C * L.R * L.S, dtype=torch.float32, device="cuda")
+        self.ws = {}
+        for op in (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT):
+            self.ws[op] = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *self.dims, self.dt, mxc.MXC_NHWC))
+
+
+class Network:
+    def __init__(self, mxc, torch, gen, cfg):
+        self.mxc, self.torch, self.cfg = mxc, torch, cfg
+        self.layers = [LayerState(mxc, torch, cfg, li, gen) for li in range(len(cfg.layers))]
+        self.flops_per_step = 3 * sum(s.L.flops_per_pass for s in self.layers)
+        self.esize = 2 if cfg.dtype == "bf16" else 4
+
+    def calls(self):
+        """(label, op, layer, thunk) for every ABI call of one step, in order."""
+        m = self.mxc
+        out = []
+        s0 = self.layers[0]
+        L0 = s0.L
+        out.append(("layout", "layout", s0, lambda: m.mxc_layout_convert(
+            L0.N, L0.C, L0.H, L0.W, s0.dt, m.MXC_NCHW, m.MXC_NHWC, s0.x_nchw, s0.x)))
+        for s in self.layers:
+            out.append((s.L.name, "fwd", s, lambda s=s: m.mxc_conv2d_fwd(
+                *s.dims, s.dt, m.MXC_NHWC, s.x, s.w, s.y, s.ws[m.MXC_FWD])))
+            out.append((s.L.name, "bwd_data", s, lambda s=s: m.mxc_conv2d_bwd_data(
+                *s.dims, s.dt, m.MXC_NHWC, s.dy, s.w, s.dx, s.ws[m.MXC_BWD_DATA])))
+            out.append((s.L.name, "bwd_weight", s, lambda s=s: m.mxc_conv2d_bwd_weight(
+                *s.dims, s.dt, m.MXC_NHWC, s.x, s.dy, s.dw, s.ws[m.MXC_BWD_WEIGHT])))
+        return out
+
+    def step(self):
+        for _, _, _, fn in self.calls():
+            fn()
+
+
+def time_steps(torch, net, steps, warmup):
+    calls = [c[3] for c in net.calls()]
+    for _ in range(warmup):
+        for fn in calls:
+            fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for fn in calls:
+            fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def time_calls(torch, net, steps):
+    """Per-call durations (ms, mean over `steps`) with HIP events on the stream the kernels run on
+    (torch's current stream), over the same sequence of calls as the timed region."""
+    mxc = net.mxc
+    calls = net.calls()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
+          for _ in range(steps)]
+    variants = []
+    for i in range(steps):
+        for j, (_, op, _, fn) in enumerate(calls):
+            ev[i][j][0].record()
+            fn()
+            ev[i][j][1].record()
+            if i == 0:
+                variants.append(mxc.mxc_last_variant() if op != "layout" else "layout:transpose")
+    torch.cuda.synchronize()
+    out = []
+    for j, (name, op, s, _) in enumerate(calls):
+        ms = sum(ev[i][j][0].elapsed_time(ev[i][j][1]) for i in range(steps)) / steps
+        out.append({"layer": name, "op": op, "variant": variants[j], "ms": ms, "state": s})
+    return out
+
+
+def roofline_of(per_call, net):
+    """Roofline entry of the kernel variant that takes the most time in a step."""
+    by_variant = {}
+    for c in per_call:
+        by_variant.setdefault(c["variant"], []).append(c)
+    dominant = max(by_variant, key=lambda v: sum(c["ms"] for c in by_variant[v]))
+    group = by_variant[dominant]
+    t = sum(c["ms"] for c in group) * 1e-3
+    flops = sum(c["state"].L.flops_per_pass for c in group if c["op"] != "layout")
+    nbytes = sum(algorithmic_bytes(c["state"].L, c["op"], net.esize) for c in group if c["op"] != "layout")
+    peak_tf = PEAK_BF16_TFLOPS if net.cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    t_mfma, t_hbm = flops / (peak_tf * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+    if t_mfma >= t_hbm:
+        bound = "mfma" if net.cfg.dtype == "bf16" or "mfma" in dominant else "alu"
+        ach = flops / t / 1e12
+        r = {"bound": bound, "achieved": round(ach, 2), "peak": peak_tf, "unit": "TFLOP/s", "frac": round(ach / peak_tf, 4)}
+    else:
+        ach = nbytes / t / 1e9
+        r = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": round(ach / PEAK_HBM_GBS, 4)}
+    r["kernel"] = dominant
+    r["launches_per_step"] = len(group)
+    r["avg_launch_ms"] = round(t * 1e3 / len(group), 4)
+    r["traffic"] = load_traffic(net.cfg.name, dominant)
+    return r
+
+
+def load_traffic(workload, variant):
+    """HBM bytes per launch from the committed rocprofv3 counter summaries, if one covers this kernel."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(variant)
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(gen, cfg, sample_batch):
+    """The oracle, as it stands, on the host cores: all layers, three passes, at a reduced batch."""
+    from oracle import conv_oracle as orc
+    flops, t = 0, 0.0
+    for li in range(len(cfg.layers)):
+        L, a = gen.layer_inputs(cfg, li, batch=min(sample_batch, cfg.layers[li].N))
+        t0 = time.perf_counter()
+        orc.conv2d_fwd(a["x"], a["w"], L.stride, L.pad)
+        orc.conv2d_bwd_data(a["dy"], a["w"], a["x"].shape, L.stride, L.pad)
+        orc.conv2d_bwd_weight(a["x"], a["dy"], a["w"].shape, L.stride, L.pad)
+        t += time.perf_counter() - t0
+        flops += 3 * L.flops_per_pass
+    return {"value": round(flops / t / 1e12, 6), "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{cfg.name} all {len(cfg.layers)} layers, 3 passes, batch {sample_batch} of "
+                      f"{cfg.layers[0].N} (cost is linear in batch); {t:.1f} s of fp64 7-loop oracle"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="alexnet_b128")
+    ap.add_argument("--all", action="store_true", help="also time the other layer stacks (extra 'networks' field)")
+    ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by contract (one MI355X, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1512_01274_amd import inputs as gen
+    from paper_1512_01274_amd import mxc
+    torch.cuda.set_device(0)
+
+    def run_one(cfg, steps, warmup):
+        net = Network(mxc, torch, gen, cfg)
+        sec = time_steps(torch, net, steps, warmup)
+        per_call = time_calls(torch, net, steps)
+        return net, sec, per_call
+
+    cfg = gen.config_by_name(args.workload)
+    net, sec, per_call = run_one(cfg, args.steps, args.warmup)
+    value = net.flops_per_step / sec / 1e12
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    result = {
+        "metric": "conv2d fwd+bwd TFLOP/s per network on 1 MI355X", "value": round(value, 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": len(cfg.layers), "batch": cfg.layers[0].N, "layout": "nhwc-resident",
+                   "step": "layout(NCHW->NHWC of network input) + per layer fwd, bwd_data, bwd_weight"},
+        "frac_of_mfma_peak": round(value / peak, 4),
+        "roofline": roofline_of(per_call, net),
+    }
+    if args.per_layer:
+        for c in per_call:
+            L = c["state"].L
+            if c["op"] == "layout":
+                nbytes = 2 * L.N * L.C * L.H * L.W * net.esize
+                print(f"{c['layer']:>24} {c['op']:>10} {c['ms']*1e3:9.1f} us {nbytes/c['ms']/1e6:8.0f} GB/s  {c['variant']}",
+                      file=sys.stderr)
+                continue
+            tf = L.flops_per_pass / c["ms"] / 1e9
+            gbs = algorithmic_bytes(L, c["op"], net.esize) / c["ms"] / 1e6
+            print(f"{c['layer']:>24} {c['op']:>10} {c['ms']*1e3:9.1f} us {tf:8.1f} TFLOP/s {gbs:8.0f} GB/s  {c['variant']}",
+                  file=sys.stderr)
+    del net
+    torch.cuda.empty_cache()
+    if args.all:
+        nets = {}
+        for other in gen.CONFIGS:
+            if other.name == cfg.name:
+                continue
+            n2, s2, pc2 = run_one(other, max(3, args.steps // 4), 2)
+            pk = PEAK_BF16_TFLOPS if other.dtype == "bf16" else PEAK_F32_TFLOPS
+            nbytes = sum(algorithmic_bytes(c["state"].L, c["op"], n2.esize) for c in pc2 if c["op"] != "layout")
+            nets[other.name] = {"tflops": round(n2.flops_per_step / s2 / 1e12, 3), "ms_per_step": round(s2 * 1e3, 4),
+                                "frac_of_mfma_peak": round(n2.flops_per_step / s2 / 1e12 / pk, 4),
+                                "algorithmic_GBps": round(nbytes / s2 / 1e9, 1)}
+            del n2, pc2
+            torch.cuda.empty_cache()
+        result["networks"] = nets
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(gen, cfg, args.cpu_sample_batch)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -188,3 +188,23 @@ def random_case(seed: int, N, C, H, W, K, R, S, stride, pad, dtype="f32", dist="
     if dtype == "bf16":
         arrs = [round_to_bf16(a) for a in arrs]
     return arrs
+
+
+# ---- host <-> device plumbing (torch is used for device memory only) ---------
+
+def to_device(a_f32: np.ndarray, dtype: str):
+    """float32 numpy (already bf16-exact when dtype == "bf16") -> contiguous GPU tensor of that dtype."""
+    import torch
+    if dtype == "bf16":
+        bits = f32_to_bf16_bits(a_f32).view(np.int16)
+        return torch.from_numpy(bits).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a_f32, dtype=np.float32)).cuda()
+
+
+def to_host_f64(t) -> np.ndarray:
+    """GPU tensor (fp32 or bf16) -> float64 numpy, exactly."""
+    import torch
+    if t.dtype == torch.bfloat16:
+        bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return bf16_bits_to_f32(bits).astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)

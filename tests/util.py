@@ -10,19 +10,8 @@ from paper_1512_01274_amd import inputs as gen
 TOL = {"f32": 1e-5, "bf16": 1e-2}
 
 
-def to_device(a_f32: np.ndarray, dtype: str) -> torch.Tensor:
-    """float32 numpy (already bf16-exact for dtype bf16) -> contiguous GPU tensor of that dtype."""
-    if dtype == "bf16":
-        bits = gen.f32_to_bf16_bits(a_f32).view(np.int16)
-        return torch.from_numpy(bits).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(a_f32, dtype=np.float32)).cuda()
-
-
-def to_host_f64(t: torch.Tensor) -> np.ndarray:
-    if t.dtype == torch.bfloat16:
-        bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
-        return gen.bf16_bits_to_f32(bits).astype(np.float64)
-    return t.cpu().numpy().astype(np.float64)
+to_device = gen.to_device
+to_host_f64 = gen.to_host_f64
 
 
 def nchw_to_nhwc(a: np.ndarray) -> np.ndarray:
