@@ -58,6 +58,12 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
 {
     (void)ws;
     if (dry) return MXC_OK;
+    if (dtype == MXC_BF16 && igemm_fwd_supported(s)) {
+        const char *v = "";
+        const int rc = igemm_fwd(s, x, w, y, st, &v);
+        set_variant("fwd", v);
+        return rc;
+    }
     set_variant("fwd", "direct");
     return direct_fwd(s, dtype, x, w, y, st);
 }
@@ -65,7 +71,14 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
 int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, Carver &ws, hipStream_t st,
                   bool dry)
 {
-    (void)ws;
+    if (dtype == MXC_BF16 && igemm_bwd_data_supported(s)) {
+        void *wt = ws.take(igemm_bwd_data_workspace(s));
+        if (dry) return MXC_OK;
+        const char *v = "";
+        const int rc = igemm_bwd_data(s, dy, w, dx, wt, st, &v);
+        set_variant("bwd_data", v);
+        return rc;
+    }
     if (dry) return MXC_OK;
     set_variant("bwd_data", "direct");
     return direct_bwd_data(s, dtype, dy, w, dx, st);

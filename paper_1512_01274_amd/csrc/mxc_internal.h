@@ -48,4 +48,12 @@ int direct_bwd_weight_splits(const ConvShape &s);
 int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw,
                       float *partial, int splits, hipStream_t st);
 
+// ---- igemm.hip: bf16 MFMA implicit GEMM (NHWC/KRSC) ---------------------------
+bool igemm_fwd_supported(const ConvShape &s);
+int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant);
+bool igemm_bwd_data_supported(const ConvShape &s);
+size_t igemm_bwd_data_workspace(const ConvShape &s);   // bytes for the re-packed filter
+int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
+                   const char **variant);
+
 }  // namespace mxc
