@@ -87,6 +87,14 @@ int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, 
 int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw, Carver &ws, hipStream_t st,
                     bool dry)
 {
+    if (dtype == MXC_BF16 && wgrad_supported(s)) {
+        float *partial = (float *)ws.take(wgrad_workspace(s));
+        if (dry) return MXC_OK;
+        const char *v = "";
+        const int rc = wgrad(s, x, dy, dw, partial, st, &v);
+        set_variant("bwd_weight", v);
+        return rc;
+    }
     const int splits = direct_bwd_weight_splits(s);
     float *partial = (float *)ws.take((size_t)splits * s.K * s.R * s.S * s.C * sizeof(float));
     if (dry) return MXC_OK;

@@ -56,4 +56,10 @@ size_t igemm_bwd_data_workspace(const ConvShape &s);   // bytes for the re-packe
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
                    const char **variant);
 
+// ---- wgrad.hip: bf16 MFMA backward-weight with split reduction ------------------
+bool wgrad_supported(const ConvShape &s);
+size_t wgrad_workspace(const ConvShape &s);            // bytes of fp32 partial tiles
+int wgrad(const ConvShape &s, const void *x, const void *dy, float *dw, float *partial, hipStream_t st,
+          const char **variant);
+
 }  // namespace mxc
