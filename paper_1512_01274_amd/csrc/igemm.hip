@@ -24,8 +24,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 64;           // reduction elements per LDS stage
-constexpr int CHUNKS = BK / 8;   // 16-byte chunks per tile row
+constexpr int BK = 64;           // reduction elements per LDS stage (one 128-byte tile row)
 
 struct IgemmParams {
     const bf16_t *in;    // activations [N][Hi][Wi][Ci]
@@ -37,24 +36,41 @@ struct IgemmParams {
     int Mh, Mw;          // output grid of this launch (per image)
     int in_mul, in_off_h, in_off_w;     // input coordinate of tap 0: a*in_mul + in_off
     int Ho, Wo, out_mul, out_off_h, out_off_w;  // output coordinate: a*out_mul + out_off
+    int linear_out;      // output pixel index == m (forward, and stride-1 backward-data)
+    int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
     int m_tiles, n_tiles;
 };
 
-__device__ __forceinline__ uint4 ldg16(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+// 16 bytes of zeros in global memory: the source of every tile chunk that lies in the padding,
+// beyond the tensor or beyond the reduction length (direct-to-LDS loads cannot be predicated to
+// write zeros, so such lanes are pointed here instead).
+__device__ const uint4 g_zero_chunk[1] = {};
+
+typedef __attribute__((address_space(3))) void *lds_vptr;
+typedef const __attribute__((address_space(1))) void *glb_vptr;
+
+// One wave-wide direct global->LDS transfer: lane l's 16 bytes land at lds_base + 16*l.
+__device__ __forceinline__ void load16_to_lds(const bf16_t *src, bf16_t *lds_base_uniform)
+{
+    __builtin_amdgcn_global_load_lds((glb_vptr)src, (lds_vptr)lds_base_uniform, 16, 0, 0);
+}
+
+// Tile rows are 128 bytes (8 chunks).  Chunk c of row r is stored at chunk position c ^ swz(r):
+// any 16 consecutive rows at one logical chunk then cover all 64 LDS banks exactly once.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
 template <int BM, int BN, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p)
 {
-    constexpr int NT = 64 * WR * WC;
+    constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC;     // wave tile
     constexpr int MI = WM / 32, NI = WN / 32;     // 32x32 MFMA blocks per wave
-    constexpr int A_LD = BM * CHUNKS / NT;        // 16-byte loads per thread per stage
-    constexpr int B_LD = BN * CHUNKS / NT;
-    static_assert(BM * CHUNKS % NT == 0 && BN * CHUNKS % NT == 0, "tile/threads mismatch");
-    static_assert(NT % CHUNKS == 0, "chunk column must be fixed per thread");
+    constexpr int A_LD = BM / 8 / NW;             // wave-wide loads (8 tile rows each) per wave per stage
+    constexpr int B_LD = BN / 8 / NW;
+    static_assert(NW % 2 == 0 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
 
-    __shared__ __attribute__((aligned(16))) bf16_t lds_a[2][BM * BK];
-    __shared__ __attribute__((aligned(16))) bf16_t lds_b[2][BN * BK];
+    __shared__ __attribute__((aligned(1024))) bf16_t lds_a[2][BM * BK];
+    __shared__ __attribute__((aligned(1024))) bf16_t lds_b[2][BN * BK];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -65,82 +81,67 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
     // in one L2.
     const int total = p.m_tiles * p.n_tiles;
     const int per_xcd = (total + 7) / 8;
-    int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= total) return;
     const int m0 = (logical / p.n_tiles) * BM, n0 = (logical % p.n_tiles) * BN;
 
-    const long long M = (long long)p.N * p.Mh * p.Mw;
     const int T = p.TR * p.TS;
     const int Kd = T * p.Ci;
     const int KT = (Kd + BK - 1) / BK;
 
-    // ---- per-thread load bookkeeping ------------------------------------------------------
-    const int ld_col = tid % CHUNKS;          // chunk column (fixed), rows tid/CHUNKS + i*(NT/CHUNKS)
-    const int ld_row0 = tid / CHUNKS;
-    constexpr int ROW_STEP = NT / CHUNKS;
+    // ---- load bookkeeping --------------------------------------------------------------------
+    // Wave-wide load number i (of BM/8 for A) fills tile rows 8i..8i+7: lane l -> row 8i + l/8,
+    // chunk position l%8.  This wave issues i = wave, wave+NW, ...; NW is even, so swz(row) and
+    // with it the logical chunk (the reduction offset) a lane fetches is the same for all of them.
+    const int ld_sub = lane >> 3;                                    // row within the 8-row group
+    const int ld_chunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);   // logical chunk fetched
 
-    long long a_base[A_LD];   // element offset of (n, base_h, base_w, 0); meaningless when !a_ok
-    int a_h[A_LD], a_w[A_LD];
-    bool a_ok[A_LD];
+    int a_off[A_LD];     // element offset of (n, base_h, base_w, 0) / 8   (may be negative)
+    int a_hw[A_LD];      // base_h in the low 16 bits, base_w in the high 16 (both signed); row invalid: h = -32768
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        const long long m = (long long)m0 + ld_row0 + i * ROW_STEP;
-        a_ok[i] = m < M;
-        const long long mm = a_ok[i] ? m : 0;
-        const int b = (int)(mm % p.Mw);
-        const long long t2 = mm / p.Mw;
-        const int a = (int)(t2 % p.Mh);
-        const int n = (int)(t2 / p.Mh);
-        a_h[i] = a * p.in_mul + p.in_off_h;
-        a_w[i] = b * p.in_mul + p.in_off_w;
-        a_base[i] = (((long long)n * p.Hi + a_h[i]) * p.Wi + a_w[i]) * p.Ci;
+        const int m = m0 + 8 * (wave + NW * i) + ld_sub;
+        if (m < p.M) {
+            const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
+            const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
+            const int h = (int)a * p.in_mul + p.in_off_h, w = (int)b * p.in_mul + p.in_off_w;
+            a_off[i] = (int)((((long long)n * p.Hi + h) * p.Wi + w) * (p.Ci >> 3));
+            a_hw[i] = (h & 0xFFFF) | (w << 16);
+        } else {
+            a_off[i] = 0;
+            a_hw[i] = 0x8000;   // h = -32768: never inside the image
+        }
     }
-    long long b_base[B_LD];
-    bool b_ok[B_LD];
-#pragma unroll
-    for (int i = 0; i < B_LD; ++i) {
-        const int co = n0 + ld_row0 + i * ROW_STEP;
-        b_ok[i] = co < p.Co;
-        b_base[i] = (long long)(b_ok[i] ? co : 0) * Kd;
-    }
-    // reduction position of this thread's chunk column: kd = kt*BK + ld_col*8 = tap*Ci + ci
-    int kd = ld_col * 8;
-    int ci = kd % p.Ci, tap = kd / p.Ci;
-    int tr = p.TS > 0 ? tap / p.TS : 0, ts = p.TS > 0 ? tap % p.TS : 0;
+    // reduction position of this lane's chunk: kd = kt*BK + ld_chunk*8 = tap*Ci + ci
+    int kd = ld_chunk * 8;
+    int ci = kd % p.Ci;
+    const int tap0 = kd / p.Ci;
+    int tr = p.TS > 0 ? tap0 / p.TS : 0, ts = p.TS > 0 ? tap0 % p.TS : 0;
+    const bf16_t *zero = reinterpret_cast<const bf16_t *>(g_zero_chunk);
+    const int b_row0 = n0 + 8 * wave + ld_sub;    // filter row of load 0; load i: + 8*NW*i
 
-    uint4 ra[A_LD], rb[B_LD];
-
-    auto load_global = [&]() {
+    auto issue_loads = [&](int buf) {
         const bool k_ok = kd < Kd;
         const int dh = tr * p.tstep, dv = ts * p.tstep;
-        const long long tap_off = ((long long)dh * p.Wi + dv) * p.Ci + ci;
+        const int tap_off = ((dh * p.Wi + dv) * p.Ci + ci) >> 3;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
-            const bool ok = a_ok[i] && k_ok && (unsigned)(a_h[i] + dh) < (unsigned)p.Hi &&
-                            (unsigned)(a_w[i] + dv) < (unsigned)p.Wi;
-            ra[i] = ok ? ldg16(p.in + a_base[i] + tap_off) : make_uint4(0, 0, 0, 0);
+            const int h = (int)(short)(a_hw[i] & 0xFFFF) + dh, w = (a_hw[i] >> 16) + dv;
+            const bool ok = k_ok && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi;
+            const bf16_t *src = ok ? p.in + ((long long)(a_off[i] + tap_off) << 3) : zero;
+            load16_to_lds(src, &lds_a[buf][(wave + NW * i) * 8 * BK]);
         }
 #pragma unroll
-        for (int i = 0; i < B_LD; ++i) rb[i] = (b_ok[i] && k_ok) ? ldg16(p.wm + b_base[i] + kd) : make_uint4(0, 0, 0, 0);
-        // advance to the next stage
+        for (int i = 0; i < B_LD; ++i) {
+            const int co = b_row0 + 8 * NW * i;
+            const bf16_t *src = (k_ok && co < p.Co) ? p.wm + ((long long)co * Kd + kd) : zero;
+            load16_to_lds(src, &lds_b[buf][(wave + NW * i) * 8 * BK]);
+        }
         kd += BK;
         ci += BK;
         while (ci >= p.Ci) {
             ci -= p.Ci;
             if (++ts == p.TS) { ts = 0; ++tr; }
-        }
-    };
-
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i) {
-            const int row = ld_row0 + i * ROW_STEP;
-            *reinterpret_cast<uint4 *>(&lds_a[buf][row * BK + ((ld_col ^ (row & 7)) << 3)]) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) {
-            const int row = ld_row0 + i * ROW_STEP;
-            *reinterpret_cast<uint4 *>(&lds_b[buf][row * BK + ((ld_col ^ (row & 7)) << 3)]) = rb[i];
         }
     };
 
@@ -152,38 +153,34 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int frag_row = lane & 31, frag_kg = lane >> 5;   // operand row and 8-element k group of this lane
+    // operand fetch: lane -> tile row (lane%32) of a 32-row block, 8-element group lane/32 of a 16-wide k step
+    const int frag_row = lane & 31, frag_kg = lane >> 5;
+    const int frag_swz = swz(frag_row);            // block bases are multiples of 32 rows: swz(row) == swz(frag_row)
 
-    if (KT > 0) {
-        load_global();
-        store_lds(0);
-    }
+    if (KT > 0) issue_loads(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < KT) load_global();
+        if (kt + 1 < KT) issue_loads(buf ^ 1);
+        const bf16_t *ta = &lds_a[buf][(wave_m + frag_row) * BK];
+        const bf16_t *tb = &lds_b[buf][(wave_n + frag_row) * BK];
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 fa[MI], fb[NI];
-            const int chunk = ks * 2 + frag_kg;
+            const int pos = ((ks * 2 + frag_kg) ^ frag_swz) << 3;
 #pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                const int row = wave_m + i * 32 + frag_row;
-                fa[i] = *reinterpret_cast<const bf16x8 *>(&lds_a[buf][row * BK + ((chunk ^ (row & 7)) << 3)]);
-            }
+            for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8 *>(ta + i * 32 * BK + pos);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int row = wave_n + j * 32 + frag_row;
-                fb[j] = *reinterpret_cast<const bf16x8 *>(&lds_b[buf][row * BK + ((chunk ^ (row & 7)) << 3)]);
-            }
+            for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const bf16x8 *>(tb + j * 32 * BK + pos);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < KT) store_lds(buf ^ 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
 
@@ -193,13 +190,14 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const long long m = (long long)m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
-            if (m >= M) continue;
-            const int b = (int)(m % p.Mw);
-            const long long t2 = m / p.Mw;
-            const int a = (int)(t2 % p.Mh);
-            const int n = (int)(t2 / p.Mh);
-            const long long pix = ((long long)n * p.Ho + (a * p.out_mul + p.out_off_h)) * p.Wo + (b * p.out_mul + p.out_off_w);
+            const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
+            if (m >= p.M) continue;
+            long long pix = m;
+            if (!p.linear_out) {
+                const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
+                const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
+                pix = ((long long)n * p.Ho + ((int)a * p.out_mul + p.out_off_h)) * p.Wo + ((int)b * p.out_mul + p.out_off_w);
+            }
             bf16_t *orow = p.out + pix * p.Co;
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
@@ -217,11 +215,20 @@ int launch(IgemmParams p, hipStream_t st)
     const long long mt = (M + BM - 1) / BM;
     p.n_tiles = (p.Co + BN - 1) / BN;
     if (mt * p.n_tiles > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
+    p.M = (int)M;
     p.m_tiles = (int)mt;
+    p.linear_out = (p.out_mul == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
     const int total = p.m_tiles * p.n_tiles;
     const int grid = ((total + 7) / 8) * 8;
     hipLaunchKernelGGL((igemm_kernel<BM, BN, WR, WC>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
+// The kernel addresses activations with 32-bit offsets in units of 8 elements and packs tile-row
+// coordinates into 16 bits.
+bool igemm_dims_ok(long long in_elems, long long M, int Hi, int Wi, int span)
+{
+    return in_elems / 8 < 0x7FFFFFFFll && M < 0x7FFFFFFFll && Hi + span < 32000 && Wi + span < 32000;
 }
 
 // Re-pack the filter for backward-data.  For the residue class (ph, pw) of (h+pad, v+pad) mod
@@ -257,7 +264,11 @@ __global__ __launch_bounds__(256) void repack_bwd_data_filter_kernel(const bf16_
 
 }  // namespace
 
-bool igemm_fwd_supported(const ConvShape &s) { return s.C % 8 == 0; }
+bool igemm_fwd_supported(const ConvShape &s)
+{
+    return s.C % 8 == 0 && igemm_dims_ok((long long)s.N * s.H * s.W * s.C, (long long)s.N * s.P * s.Q, s.H, s.W,
+                                         s.pad + s.R + s.S + s.stride);
+}
 
 int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant)
 {
@@ -272,7 +283,11 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
     return launch<128, 128, 2, 2>(p, st);
 }
 
-bool igemm_bwd_data_supported(const ConvShape &s) { return s.K % 8 == 0 && s.stride <= 4; }
+bool igemm_bwd_data_supported(const ConvShape &s)
+{
+    return s.K % 8 == 0 && s.stride <= 4 &&
+           igemm_dims_ok((long long)s.N * s.P * s.Q * s.K, (long long)s.N * s.H * s.W, s.P, s.Q, s.pad + s.R + s.S + s.stride);
+}
 
 size_t igemm_bwd_data_workspace(const ConvShape &s) { return (size_t)s.K * s.R * s.S * s.C * sizeof(bf16_t); }
 
