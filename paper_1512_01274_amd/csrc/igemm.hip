@@ -11,10 +11,16 @@
 //   backward-data:  In = dy, Wm = per-phase re-packed filter [C][taps*K], one launch per residue
 //                   class of (h+pad, v+pad) mod stride, tap step -1, strided output addressing.
 //
-// Tiling: a workgroup of 4 waves owns a BM x BN output tile; the reduction advances in steps of
-// BK = 64 through a double-buffered LDS tile pair (A: BM x 64, B: BN x 64, 16-byte chunks XOR
-// swizzled by row so that ds_read_b128 operand fetches are bank-conflict free).  Each wave
-// accumulates a (BM/WR) x (BN/WC) sub-tile with v_mfma_f32_32x32x16_bf16 in fp32.
+// Tiling: a workgroup of 4 or 8 waves owns a BM x BN output tile; each wave accumulates a
+// (BM/WR) x (BN/WC) sub-tile with v_mfma_f32_32x32x16_bf16 in fp32.  The reduction advances in
+// steps of BKT (32 or 64) through a ring of NS LDS stages that are filled by direct global->LDS
+// loads issued NS stages ahead of their use; 16-byte chunks are XOR-swizzled by row so that the
+// ds_read_b128 operand fetches are bank-conflict free.
+#include <stdlib.h>
+#include <string.h>
+
+#include <type_traits>
+
 #include "mxc_internal.h"
 
 namespace mxc {
@@ -24,7 +30,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 64;           // reduction elements per LDS stage (one 128-byte tile row)
+constexpr int MAX_TAPS = 127;   // tap table capacity (11x11 = 121 fits)
 
 struct IgemmParams {
     const bf16_t *in;    // activations [N][Hi][Wi][Ci]
@@ -39,41 +45,77 @@ struct IgemmParams {
     int linear_out;      // output pixel index == m (forward, and stride-1 backward-data)
     int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
     int m_tiles, n_tiles;
+    unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
 };
 
-// 16 bytes of zeros in global memory: the source of every tile chunk that lies in the padding,
-// beyond the tensor or beyond the reduction length (direct-to-LDS loads cannot be predicated to
-// write zeros, so such lanes are pointed here instead).
-__device__ const uint4 g_zero_chunk[1] = {};
-
 typedef __attribute__((address_space(3))) void *lds_vptr;
-typedef const __attribute__((address_space(1))) void *glb_vptr;
+typedef short s16x2 __attribute__((ext_vector_type(2)));
 
-// One wave-wide direct global->LDS transfer: lane l's 16 bytes land at lds_base + 16*l.
-__device__ __forceinline__ void load16_to_lds(const bf16_t *src, bf16_t *lds_base_uniform)
+constexpr unsigned OOB = 0x80000000u;   // a buffer offset no operand reaches: the load returns zeros
+
+// One wave-wide direct global->LDS transfer through a buffer descriptor: lane l's 16 bytes land at
+// lds_base + 16*l.  Lanes whose byte offset is outside the buffer (OOB) deposit zeros, which is how
+// padding, ragged tile edges and the tail of the reduction are filled.
+__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off, bf16_t *lds_base_uniform)
 {
-    __builtin_amdgcn_global_load_lds((glb_vptr)src, (lds_vptr)lds_base_uniform, 16, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_vptr)lds_base_uniform, 16, byte_off, 0, 0, 0);
 }
 
-// Tile rows are 128 bytes (8 chunks).  Chunk c of row r is stored at chunk position c ^ swz(r):
-// any 16 consecutive rows at one logical chunk then cover all 64 LDS banks exactly once.
-__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void pin() { __builtin_amdgcn_sched_barrier(0); }   // nothing is scheduled across
 
-template <int BM, int BN, int WR, int WC>
+template <int I> using IC = std::integral_constant<int, I>;
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) { (f(IC<I>{}), ...); }
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// BM x BN output tile, BKT reduction elements per stage, NS stages, WR x WC waves.
+template <int BM, int BN, int BKT, int NS, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p)
 {
-    constexpr int NW = WR * WC;
+    constexpr int NW = WR * WC, NT = 64 * NW;
     constexpr int WM = BM / WR, WN = BN / WC;     // wave tile
     constexpr int MI = WM / 32, NI = WN / 32;     // 32x32 MFMA blocks per wave
-    constexpr int A_LD = BM / 8 / NW;             // wave-wide loads (8 tile rows each) per wave per stage
-    constexpr int B_LD = BN / 8 / NW;
-    static_assert(NW % 2 == 0 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
+    constexpr int NMF = MI * NI;                  // MFMAs per k-step
+    constexpr int CH = BKT / 8;                   // 16-byte chunks per tile row
+    constexpr int RPL = 64 / CH;                  // tile rows filled by one wave-wide load
+    constexpr int RB = 256 / (BKT * 2);           // tile rows per 256-byte span of LDS banks
+    constexpr int A_LD = BM / RPL / NW;           // wave-wide loads per wave per stage
+    constexpr int B_LD = BN / RPL / NW;
+    constexpr int L = A_LD + B_LD;
+    constexpr int KS = BKT / 16;                  // MFMA k-steps per stage
+    static_assert(BKT == 32 || BKT == 64, "BKT");
+    static_assert(NS >= 2 && NS <= 4, "NS");
+    static_assert(NW % 2 == 0 && BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "tile/wave mismatch");
+    static_assert(L * (NS - 1) < 64, "vmcnt range");
+    static_assert(KS % 2 == 0, "fragment ping-pong assumes an even number of k-steps");
 
-    __shared__ __attribute__((aligned(1024))) bf16_t lds_a[2][BM * BK];
-    __shared__ __attribute__((aligned(1024))) bf16_t lds_b[2][BN * BK];
+    // Every stage is its own LDS object (not one array indexed by the stage): the compiler can then
+    // see that the direct loads filling one stage never alias the operand reads of another and does
+    // not serialise them.
+    constexpr int SZA = BM * BKT, SZB = BN * BKT;
+    __shared__ __attribute__((aligned(1024))) bf16_t sa0[SZA];
+    __shared__ __attribute__((aligned(1024))) bf16_t sa1[SZA];
+    __shared__ __attribute__((aligned(1024))) bf16_t sa2[NS > 2 ? SZA : 8];
+    __shared__ __attribute__((aligned(1024))) bf16_t sa3[NS > 3 ? SZA : 8];
+    __shared__ __attribute__((aligned(1024))) bf16_t sb0[SZB];
+    __shared__ __attribute__((aligned(1024))) bf16_t sb1[SZB];
+    __shared__ __attribute__((aligned(1024))) bf16_t sb2[NS > 2 ? SZB : 8];
+    __shared__ __attribute__((aligned(1024))) bf16_t sb3[NS > 3 ? SZB : 8];
+    // per tap: .x = byte offset of the tap relative to tap 0, .y = (dh, dv) packed as two int16
+    __shared__ int2 tap_tab[MAX_TAPS + 1];
+    auto stage_a = [&](auto s) -> bf16_t * {
+        constexpr int S = decltype(s)::value;
+        if constexpr (S == 0) return sa0; else if constexpr (S == 1) return sa1; else if constexpr (S == 2) return sa2; else return sa3;
+    };
+    auto stage_b = [&](auto s) -> bf16_t * {
+        constexpr int S = decltype(s)::value;
+        if constexpr (S == 0) return sb0; else if constexpr (S == 1) return sb1; else if constexpr (S == 2) return sb2; else return sb3;
+    };
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps LDS targets in SGPRs
     const int wave_m = (wave / WC) * WM, wave_n = (wave % WC) * WN;
 
     // Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs; give each
@@ -87,62 +129,97 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
 
     const int T = p.TR * p.TS;
     const int Kd = T * p.Ci;
-    const int KT = (Kd + BK - 1) / BK;
+    const int KT = (Kd + BKT - 1) / BKT;
+
+    // ---- tap table -------------------------------------------------------------------------------
+    // Entry T is a sentinel whose row offset lies far outside any image: every chunk past the end
+    // of the reduction fails the bounds test and is filled with zeros.
+    for (int t = tid; t <= T; t += NT) {
+        int2 e;
+        if (t < T) {
+            const int dh = (t / p.TS) * p.tstep, dv = (t % p.TS) * p.tstep;
+            e.x = ((dh * p.Wi + dv) * p.Ci) * 2;
+            e.y = (dh & 0xFFFF) | (dv << 16);
+        } else {
+            e.x = 0;
+            e.y = (-16384) & 0xFFFF;
+        }
+        tap_tab[t] = e;
+    }
 
     // ---- load bookkeeping --------------------------------------------------------------------
-    // Wave-wide load number i (of BM/8 for A) fills tile rows 8i..8i+7: lane l -> row 8i + l/8,
-    // chunk position l%8.  This wave issues i = wave, wave+NW, ...; NW is even, so swz(row) and
-    // with it the logical chunk (the reduction offset) a lane fetches is the same for all of them.
-    const int ld_sub = lane >> 3;                                    // row within the 8-row group
-    const int ld_chunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);   // logical chunk fetched
+    // Wave-wide load number i fills tile rows RPL*i .. RPL*i+RPL-1: lane l -> row RPL*i + l/CH, chunk
+    // position l%CH.  Chunk c of row r lives at position c ^ ((r/RB) % CH), which spreads any 16
+    // consecutive rows of one logical chunk over all 64 banks.  This wave issues loads wave, wave+NW,
+    // ...; (RPL/RB)*NW is a multiple of CH, so the logical chunk (= reduction offset) a lane fetches is
+    // the same for all of them.
+    const int ld_sub = lane / CH;
+    const int ld_chunk = (lane % CH) ^ (((RPL / RB) * wave + ld_sub / RB) % CH);
 
-    int a_off[A_LD];     // element offset of (n, base_h, base_w, 0) / 8   (may be negative)
-    int a_hw[A_LD];      // base_h in the low 16 bits, base_w in the high 16 (both signed); row invalid: h = -32768
+    const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_wm = __builtin_amdgcn_make_buffer_rsrc((void *)p.wm, 0, (int)p.wm_bytes, 0x00020000);
+
+    int a_off[A_LD];     // byte offset of (n, base_h, base_w, 0) in `in` (may be negative)
+    int a_hw[A_LD];      // base_h (low 16 bits) and base_w (high 16), signed; invalid row: h = -16384
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        const int m = m0 + 8 * (wave + NW * i) + ld_sub;
+        const int m = m0 + RPL * (wave + NW * i) + ld_sub;
         if (m < p.M) {
             const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
             const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
             const int h = (int)a * p.in_mul + p.in_off_h, w = (int)b * p.in_mul + p.in_off_w;
-            a_off[i] = (int)((((long long)n * p.Hi + h) * p.Wi + w) * (p.Ci >> 3));
+            a_off[i] = (int)((((long long)n * p.Hi + h) * p.Wi + w) * p.Ci * 2);
             a_hw[i] = (h & 0xFFFF) | (w << 16);
         } else {
             a_off[i] = 0;
-            a_hw[i] = 0x8000;   // h = -32768: never inside the image
+            a_hw[i] = (-16384) & 0xFFFF;
         }
     }
-    // reduction position of this lane's chunk: kd = kt*BK + ld_chunk*8 = tap*Ci + ci
-    int kd = ld_chunk * 8;
-    int ci = kd % p.Ci;
-    const int tap0 = kd / p.Ci;
-    int tr = p.TS > 0 ? tap0 / p.TS : 0, ts = p.TS > 0 ? tap0 % p.TS : 0;
-    const bf16_t *zero = reinterpret_cast<const bf16_t *>(g_zero_chunk);
-    const int b_row0 = n0 + 8 * wave + ld_sub;    // filter row of load 0; load i: + 8*NW*i
+    unsigned b_off[B_LD];   // byte offset of the filter row, OOB for rows past Co
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int co = n0 + RPL * (wave + NW * i) + ld_sub;
+        b_off[i] = co < p.Co ? (unsigned)co * (unsigned)Kd * 2u : OOB;
+    }
+    // Reduction position of this lane's chunk: kd = stage*BKT + ld_chunk*8 = tap*Ci + ci, kept as
+    // (tap, ci) and advanced without branches: BKT = kq*Ci + kr.
+    const int kq = BKT / p.Ci, kr2 = (BKT % p.Ci) * 2, Ci2 = p.Ci * 2, Kd2 = Kd * 2;
+    int kd2 = ld_chunk * 16;                       // byte offset within a filter row
+    int ci2 = (ld_chunk * 8 % p.Ci) * 2, tap = ld_chunk * 8 / p.Ci;
+    const int lim_hw = ((p.Hi - 1) & 0xFFFF) | ((p.Wi - 1) << 16);
 
-    auto issue_loads = [&](int buf) {
-        const bool k_ok = kd < Kd;
-        const int dh = tr * p.tstep, dv = ts * p.tstep;
-        const int tap_off = ((dh * p.Wi + dv) * p.Ci + ci) >> 3;
+    unsigned va[A_LD], vb[B_LD];   // byte offsets of the next stage's loads
+
+    // address generation for the next stage, split in A_LD + 2 small tasks so that it can be spread
+    // between MFMAs
+    int2 tap_e;
+    auto addr_task = [&](auto t) {
+        constexpr int Tk = decltype(t)::value;
+        if constexpr (Tk == 0) {
+            tap_e = tap_tab[tap < T ? tap : T];
+        } else if constexpr (Tk <= A_LD) {
+            constexpr int i = Tk - 1;
+            const s16x2 hw = __builtin_bit_cast(s16x2, a_hw[i]) + __builtin_bit_cast(s16x2, tap_e.y);
+            const s16x2 d = __builtin_bit_cast(s16x2, lim_hw) - hw;
+            const int bad = (__builtin_bit_cast(int, hw) | __builtin_bit_cast(int, d)) & (int)0x80008000;
+            va[i] = bad == 0 ? (unsigned)(a_off[i] + tap_e.x + ci2) : OOB;
+        } else {
+            const bool k_ok = kd2 < Kd2;
 #pragma unroll
-        for (int i = 0; i < A_LD; ++i) {
-            const int h = (int)(short)(a_hw[i] & 0xFFFF) + dh, w = (a_hw[i] >> 16) + dv;
-            const bool ok = k_ok && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi;
-            const bf16_t *src = ok ? p.in + ((long long)(a_off[i] + tap_off) << 3) : zero;
-            load16_to_lds(src, &lds_a[buf][(wave + NW * i) * 8 * BK]);
+            for (int i = 0; i < B_LD; ++i) vb[i] = k_ok ? b_off[i] + (unsigned)kd2 : OOB;
+            // advance (tap, ci) and kd by one stage
+            kd2 += BKT * 2;
+            ci2 += kr2;
+            const int carry = ci2 >= Ci2 ? 1 : 0;
+            ci2 -= carry ? Ci2 : 0;
+            tap += kq + carry;
         }
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) {
-            const int co = b_row0 + 8 * NW * i;
-            const bf16_t *src = (k_ok && co < p.Co) ? p.wm + ((long long)co * Kd + kd) : zero;
-            load16_to_lds(src, &lds_b[buf][(wave + NW * i) * 8 * BK]);
-        }
-        kd += BK;
-        ci += BK;
-        while (ci >= p.Ci) {
-            ci -= p.Ci;
-            if (++ts == p.TS) { ts = 0; ++tr; }
-        }
+    };
+    constexpr int N_ADDR = A_LD + 2;
+    auto load_task = [&](auto t, bf16_t *dst_a, bf16_t *dst_b) {
+        constexpr int Tk = decltype(t)::value;
+        if constexpr (Tk < A_LD) load16_to_lds(rs_in, va[Tk], dst_a + (wave + NW * Tk) * RPL * BKT);
+        else load16_to_lds(rs_wm, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * RPL * BKT);
     };
 
     f32x16 acc[MI][NI];
@@ -153,36 +230,87 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // operand fetch: lane -> tile row (lane%32) of a 32-row block, 8-element group lane/32 of a 16-wide k step
+    // operand fetch: lane -> tile row lane%32 of a 32-row block, 8-element group lane/32 of a 16-wide k-step
     const int frag_row = lane & 31, frag_kg = lane >> 5;
-    const int frag_swz = swz(frag_row);            // block bases are multiples of 32 rows: swz(row) == swz(frag_row)
+    const int frag_swz = (frag_row / RB) % CH;     // block bases are multiples of 32 rows
+    const int a_lane = (wave_m + frag_row) * BKT, b_lane = (wave_n + frag_row) * BKT;
 
-    if (KT > 0) issue_loads(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    struct Frags { bf16x8 a[MI], b[NI]; };
+    auto read_task = [&](auto t, Frags &f, const bf16_t *src_a, const bf16_t *src_b, int ks) {
+        constexpr int Tk = decltype(t)::value;
+        const int pos = ((ks * 2 + frag_kg) ^ frag_swz) << 3;
+        if constexpr (Tk < MI) f.a[Tk] = *reinterpret_cast<const bf16x8 *>(src_a + a_lane + Tk * 32 * BKT + pos);
+        else f.b[Tk - MI] = *reinterpret_cast<const bf16x8 *>(src_b + b_lane + (Tk - MI) * 32 * BKT + pos);
+    };
+    constexpr int N_READ = MI + NI;
+
+    // NMF MFMAs of one k-step with `NTASK` side tasks spread between them (program order is pinned:
+    // the matrix pipe executes one MFMA while the wave issues the side work behind it)
+    auto mfma_with = [&](const Frags &f, auto ntask, auto &&task) {
+        constexpr int NTASK = decltype(ntask)::value;
+        static_for<NMF>([&](auto s) {
+            constexpr int S = decltype(s)::value;
+            acc[S / NI][S % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[S / NI], f.b[S % NI], acc[S / NI][S % NI], 0, 0, 0);
+            static_for<NTASK>([&](auto t) {
+                constexpr int Tk = decltype(t)::value;
+                if constexpr (Tk * NMF / NTASK == S) task(t);
+            });
+            pin();
+        });
+    };
+
+    // ---- pipeline ------------------------------------------------------------------------------
+    // Stage s lives in ring slot s % NS.  While stage kt is being multiplied, stages kt+1..kt+NS-1
+    // are landing.  Per stage: k-steps 0..KS-2 fetch the next k-step's operands, and the one before
+    // last also computes the addresses of the refill; then this wave's loads of stage kt+1 are
+    // awaited (all but the (NS-2)*L youngest), one barrier publishes stage kt+1 and frees slot
+    // kt % NS, and the last k-step's MFMAs run interleaved with the refill loads (stage kt+NS) and the
+    // first operand fetch of stage kt+1 - the matrix pipe has work across the barrier.
+    Frags f0, f1;
+    __syncthreads();   // tap table visible
+    static_for<NS>([&](auto s) {
+        static_for<N_ADDR>([&](auto t) { addr_task(t); });
+        static_for<L>([&](auto t) { load_task(t, stage_a(s), stage_b(s)); });
+    });
+    wait_vmcnt<L * (NS - 1)>();
     __syncthreads();
+    static_for<N_READ>([&](auto t) { read_task(t, f0, sa0, sb0, 0); });
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) issue_loads(buf ^ 1);
-        const bf16_t *ta = &lds_a[buf][(wave_m + frag_row) * BK];
-        const bf16_t *tb = &lds_b[buf][(wave_n + frag_row) * BK];
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[MI], fb[NI];
-            const int pos = ((ks * 2 + frag_kg) ^ frag_swz) << 3;
-#pragma unroll
-            for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8 *>(ta + i * 32 * BK + pos);
-#pragma unroll
-            for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const bf16x8 *>(tb + j * 32 * BK + pos);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    auto run_stage = [&](auto s) {
+        constexpr int S = decltype(s)::value;
+        constexpr int S1 = (S + 1) % NS;
+        bf16_t *ca = stage_a(s), *cb = stage_b(s);
+        static_for<KS - 1>([&](auto k) {
+            constexpr int ks = decltype(k)::value;
+            Frags &cur = (ks & 1) ? f1 : f0;
+            Frags &nxt = (ks & 1) ? f0 : f1;
+            if constexpr (ks == KS - 2) {
+                mfma_with(cur, IC<N_READ + N_ADDR>{}, [&](auto t) {
+                    constexpr int Tk = decltype(t)::value;
+                    if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<Tk - N_READ>{});
+                });
+            } else {
+                mfma_with(cur, IC<N_READ>{}, [&](auto t) { read_task(t, nxt, ca, cb, ks + 1); });
+            }
+        });
+        // the last k-step's operands are in f1; all reads of this slot must have returned before it is refilled
+        wait_lgkmcnt0();
+        wait_vmcnt<L * (NS - 2)>();
         __syncthreads();
+        mfma_with(f1, IC<L + N_READ>{}, [&](auto t) {
+            constexpr int Tk = decltype(t)::value;
+            if constexpr (Tk < L) load_task(t, ca, cb);
+            else read_task(IC<Tk - L>{}, f0, stage_a(IC<S1>{}), stage_b(IC<S1>{}), 0);
+        });
+    };
+
+    for (int kt = 0; kt < KT; kt += NS) {
+        run_stage(IC<0>{});
+        if (kt + 1 < KT) run_stage(IC<1>{});
+        if constexpr (NS > 2) if (kt + 2 < KT) run_stage(IC<2>{});
+        if constexpr (NS > 3) if (kt + 3 < KT) run_stage(IC<3>{});
     }
+    wait_vmcnt<0>();   // drain the zero-fill loads of the stages past the end before the tile's LDS is abandoned
 
     // ---- epilogue: fp32 -> bf16 (RNE), scatter to the output pixels -------------------------
     // accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
@@ -208,7 +336,7 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
     }
 }
 
-template <int BM, int BN, int WR, int WC>
+template <int BM, int BN, int BKT, int NS, int WR, int WC>
 int launch(IgemmParams p, hipStream_t st)
 {
     const long long M = (long long)p.N * p.Mh * p.Mw;
@@ -217,18 +345,59 @@ int launch(IgemmParams p, hipStream_t st)
     if (mt * p.n_tiles > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
     p.M = (int)M;
     p.m_tiles = (int)mt;
+    p.in_bytes = (unsigned)((long long)p.N * p.Hi * p.Wi * p.Ci * 2);
+    p.wm_bytes = (unsigned)((long long)p.Co * p.TR * p.TS * p.Ci * 2);
     p.linear_out = (p.out_mul == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
     const int total = p.m_tiles * p.n_tiles;
     const int grid = ((total + 7) / 8) * 8;
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, WR, WC>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
+    hipLaunchKernelGGL((igemm_kernel<BM, BN, BKT, NS, WR, WC>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
 
-// The kernel addresses activations with 32-bit offsets in units of 8 elements and packs tile-row
-// coordinates into 16 bits.
-bool igemm_dims_ok(long long in_elems, long long M, int Hi, int Wi, int span)
+struct TileChoice { int bm, bn; const char *name; };
+const TileChoice kTiles[] = {
+    {128, 128, "igemm_128x128_k64s2_w4"}, {256, 256, "igemm_256x256_k32s4_w8"}, {256, 128, "igemm_256x128_k64s3_w8"},
+    {256, 128, "igemm_256x128_k32s4_w4"}, {128, 128, "igemm_128x128_k64s4_w4"}, {128, 128, "igemm_128x128_k32s4_w4"},
+    {128, 64, "igemm_128x64_k64s2_w4"}, {256, 64, "igemm_256x64_k64s3_w4"}, {128, 32, "igemm_128x32_k64s2_w4"},
+    {256, 32, "igemm_256x32_k64s3_w4"}, {256, 256, "igemm_256x256_k64s2_w8"}, {256, 256, "igemm_256x256_k32s3_w8"},
+};
+
+int launch_choice(int idx, const IgemmParams &p, hipStream_t st)
 {
-    return in_elems / 8 < 0x7FFFFFFFll && M < 0x7FFFFFFFll && Hi + span < 32000 && Wi + span < 32000;
+    switch (idx) {
+    case 0: return launch<128, 128, 64, 2, 2, 2>(p, st);
+    case 1: return launch<256, 256, 32, 4, 2, 4>(p, st);
+    case 2: return launch<256, 128, 64, 3, 4, 2>(p, st);
+    case 3: return launch<256, 128, 32, 4, 2, 2>(p, st);
+    case 4: return launch<128, 128, 64, 4, 2, 2>(p, st);
+    case 5: return launch<128, 128, 32, 4, 2, 2>(p, st);
+    case 6: return launch<128, 64, 64, 2, 2, 2>(p, st);
+    case 7: return launch<256, 64, 64, 3, 4, 1>(p, st);
+    case 8: return launch<128, 32, 64, 2, 4, 1>(p, st);
+    case 9: return launch<256, 32, 64, 3, 4, 1>(p, st);
+    case 10: return launch<256, 256, 64, 2, 2, 4>(p, st);
+    default: return launch<256, 256, 32, 3, 2, 4>(p, st);
+    }
+}
+
+// Tile choice.  MXC_FORCE_VARIANT=<name> (tuning sweeps only) overrides the heuristic.
+int choose_tile(long long M, int Co, int Kd)
+{
+    (void)M; (void)Kd;
+    if (const char *f = getenv("MXC_FORCE_VARIANT"))
+        for (int i = 0; i < (int)(sizeof(kTiles) / sizeof(kTiles[0])); ++i)
+            if (!strcmp(f, kTiles[i].name)) return i;
+    if (Co <= 32) return 8;
+    if (Co <= 64) return 6;
+    return 0;
+}
+
+// The kernel addresses both operands with signed 32-bit byte offsets, packs tile-row coordinates
+// into 16 bits and holds at most MAX_TAPS filter taps in its tap table.
+bool igemm_dims_ok(long long in_elems, long long wm_elems, long long M, int Hi, int Wi, int span, int taps)
+{
+    return in_elems * 2 < 0x7FFF0000ll && wm_elems * 2 < 0x7FFF0000ll && M < 0x7FFFFFFFll && Hi + span <= 8192 &&
+           Wi + span <= 8192 && taps <= MAX_TAPS;
 }
 
 // Re-pack the filter for backward-data.  For the residue class (ph, pw) of (h+pad, v+pad) mod
@@ -266,8 +435,8 @@ __global__ __launch_bounds__(256) void repack_bwd_data_filter_kernel(const bf16_
 
 bool igemm_fwd_supported(const ConvShape &s)
 {
-    return s.C % 8 == 0 && igemm_dims_ok((long long)s.N * s.H * s.W * s.C, (long long)s.N * s.P * s.Q, s.H, s.W,
-                                         s.pad + s.R + s.S + s.stride);
+    return s.C % 8 == 0 && igemm_dims_ok((long long)s.N * s.H * s.W * s.C, (long long)s.K * s.R * s.S * s.C,
+                                         (long long)s.N * s.P * s.Q, s.H, s.W, s.pad + s.R + s.S + s.stride, s.R * s.S);
 }
 
 int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant)
@@ -279,14 +448,16 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
     p.Mh = s.P; p.Mw = s.Q;
     p.in_mul = s.stride; p.in_off_h = -s.pad; p.in_off_w = -s.pad;
     p.Ho = s.P; p.Wo = s.Q; p.out_mul = 1; p.out_off_h = 0; p.out_off_w = 0;
-    *variant = "igemm_128x128";
-    return launch<128, 128, 2, 2>(p, st);
+    const int tc = choose_tile((long long)s.N * s.P * s.Q, s.K, s.R * s.S * s.C);
+    *variant = kTiles[tc].name;
+    return launch_choice(tc, p, st);
 }
 
 bool igemm_bwd_data_supported(const ConvShape &s)
 {
     return s.K % 8 == 0 && s.stride <= 4 &&
-           igemm_dims_ok((long long)s.N * s.P * s.Q * s.K, (long long)s.N * s.H * s.W, s.P, s.Q, s.pad + s.R + s.S + s.stride);
+           igemm_dims_ok((long long)s.N * s.P * s.Q * s.K, (long long)s.K * s.R * s.S * s.C, (long long)s.N * s.H * s.W, s.P,
+                         s.Q, s.pad + s.R + s.S + s.stride, s.R * s.S);
 }
 
 size_t igemm_bwd_data_workspace(const ConvShape &s) { return (size_t)s.K * s.R * s.S * s.C * sizeof(bf16_t); }
@@ -299,6 +470,7 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
                        (const bf16_t *)w, (bf16_t *)wt, s.K, s.C, s.R, s.S, s.stride);
     if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
     size_t wt_off = 0;
+    int tc = 0;
     for (int ph = 0; ph < s.stride; ++ph) {
         for (int pw = 0; pw < s.stride; ++pw) {
             const int TR = ph < s.R ? (s.R - ph + s.stride - 1) / s.stride : 0;
@@ -318,11 +490,12 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
             p.Ho = s.H; p.Wo = s.W; p.out_mul = s.stride; p.out_off_h = h_first; p.out_off_w = v_first;
             wt_off += (size_t)s.C * TR * TS * s.K;
             if (Mh <= 0 || Mw <= 0) continue;
-            const int rc = launch<128, 128, 2, 2>(p, st);
+            tc = choose_tile((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
+            const int rc = launch_choice(tc, p, st);
             if (rc != MXC_OK) return rc;
         }
     }
-    *variant = "igemm_128x128";
+    *variant = kTiles[tc].name;
     return MXC_OK;
 }
 
