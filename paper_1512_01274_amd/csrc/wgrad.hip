@@ -8,9 +8,18 @@
 // ds_read_b64_tr_b16: within 16 lanes, lane j addresses 4 channels of pixel j/4 and receives
 // the 4 pixels of channel j.
 //
+// Pipeline: a ring of NS LDS stages of BP pixels each, filled by direct global->LDS buffer loads
+// (out-of-range lanes deposit zeros: padding, ragged edges, the tail of a split) issued NS stages
+// ahead; address generation and operand fetches are interleaved between the MFMAs.
+//
 // Split reduction: workgroup (tile, z) reduces pixels [z*span, (z+1)*span) into an fp32 partial
-// tile; a second kernel adds the partials of every tile in ascending z (fixed order, so results
+// tile; a second kernel adds the partials of every element in ascending z (fixed order, so results
 // are bit-identical from run to run; no float atomics).
+#include <stdlib.h>
+#include <string.h>
+
+#include <type_traits>
+
 #include "mxc_internal.h"
 
 namespace mxc {
@@ -21,154 +30,263 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
+typedef __attribute__((address_space(3))) void *lds_vptr;
+typedef short s16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 128;   // k channels per tile
-constexpr int BN = 128;   // filter columns (tap, c) per tile
-constexpr int BP = 64;    // pixels per LDS stage
-constexpr int NT = 256;
-constexpr int ROW_CHUNKS = 16;            // 16-byte chunks per tile row (128 channels)
-constexpr int ROWS_PER_PASS = NT / ROW_CHUNKS;   // 16
-constexpr int LD = BP / ROWS_PER_PASS;           // 4 rows per thread per stage
+constexpr unsigned OOB = 0x80000000u;   // a buffer offset no operand reaches: the load returns zeros
 
 struct WgradParams {
     const bf16_t *x;    // [N][H][W][C]
     const bf16_t *dy;   // [N][P][Q][K]
     float *partial;     // [splits][K][R*S*C]
     int N, C, H, W, K, R, S, stride, pad, P, Q;
-    int k_tiles, n_tiles, splits;
-    long long span;     // pixels per split (multiple of BP)
-    // decomposition of a BP-pixel advance: BP = dq + Q*(dp + P*dn)
-    int dq, dp, dn;
+    int n_tiles, splits;
+    int span;           // pixels per split (multiple of the stage size)
+    int M;              // N*P*Q
+    int dq, dp, dn;     // decomposition of a one-stage pixel advance: BP = dq + Q*(dp + P*dn)
+    unsigned x_bytes, dy_bytes;
 };
 
-// physical position of 16-byte chunk `chunk` of tile row `row`
-__device__ __forceinline__ int swz(int row, int chunk) { return row * (ROW_CHUNKS * 8) + ((chunk ^ ((row & 3) << 2)) << 3); }
-
-__global__ __launch_bounds__(NT) void wgrad_kernel(const WgradParams p)
+__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off, bf16_t *lds_base_uniform)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t lds_a[2][BP * BM];   // dy tile  [pixel][k]
-    __shared__ __attribute__((aligned(16))) bf16_t lds_b[2][BP * BN];   // x tile   [pixel][col]
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_vptr)lds_base_uniform, 16, byte_off, 0, 0, 0);
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void pin() { __builtin_amdgcn_sched_barrier(0); }
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wave_m = (wave >> 1) * 64, wave_n = (wave & 1) * 64;
+template <int I> using IC = std::integral_constant<int, I>;
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) { (f(IC<I>{}), ...); }
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// XOR applied to the chunk index of tile row `row` (RC chunks of 16 bytes per row) so that the four
+// pixel rows touched by one transposing read fall into different banks.
+template <int RC> __device__ __forceinline__ int row_swz(int row)
+{
+    if constexpr (RC >= 16) return (row & 3) << 2;
+    else if constexpr (RC == 8) return ((row >> 1) & 1) << 2;
+    else return 0;
+}
+
+// BMT k-channels x BNT filter columns per tile, BP pixels per stage, NS stages, WR x WC waves.
+template <int BMT, int BNT, int BP, int NS, int WR, int WC>
+__global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p)
+{
+    constexpr int NW = WR * WC;
+    constexpr int WM = BMT / WR, WN = BNT / WC;
+    constexpr int MI = WM / 32, NI = WN / 32, NMF = MI * NI;
+    constexpr int RCA = BMT / 8, RCB = BNT / 8;           // 16-byte chunks per tile row
+    constexpr int RPLA = 64 / RCA, RPLB = 64 / RCB;       // pixel rows per wave-wide load
+    constexpr int A_LD = BP / RPLA / NW, B_LD = BP / RPLB / NW;
+    constexpr int L = A_LD + B_LD;
+    constexpr int KS = BP / 16;
+    static_assert(NS >= 2 && NS <= 4 && KS % 2 == 0 && NW % 2 == 0, "config");
+    static_assert(BP % (RPLA * NW) == 0 && BP % (RPLB * NW) == 0 && RCA <= 32 && RCB <= 32 && RCA >= 4 && RCB >= 4, "tile/wave mismatch");
+    static_assert(L * (NS - 1) < 64, "vmcnt range");
+
+    constexpr int SZA = BP * BMT, SZB = BP * BNT;
+    __shared__ __attribute__((aligned(1024))) bf16_t sa0[SZA];
+    __shared__ __attribute__((aligned(1024))) bf16_t sa1[SZA];
+    __shared__ __attribute__((aligned(1024))) bf16_t sa2[NS > 2 ? SZA : 8];
+    __shared__ __attribute__((aligned(1024))) bf16_t sa3[NS > 3 ? SZA : 8];
+    __shared__ __attribute__((aligned(1024))) bf16_t sb0[SZB];
+    __shared__ __attribute__((aligned(1024))) bf16_t sb1[SZB];
+    __shared__ __attribute__((aligned(1024))) bf16_t sb2[NS > 2 ? SZB : 8];
+    __shared__ __attribute__((aligned(1024))) bf16_t sb3[NS > 3 ? SZB : 8];
+    auto stage_a = [&](auto s) -> bf16_t * {
+        constexpr int S = decltype(s)::value;
+        if constexpr (S == 0) return sa0; else if constexpr (S == 1) return sa1; else if constexpr (S == 2) return sa2; else return sa3;
+    };
+    auto stage_b = [&](auto s) -> bf16_t * {
+        constexpr int S = decltype(s)::value;
+        if constexpr (S == 0) return sb0; else if constexpr (S == 1) return sb1; else if constexpr (S == 2) return sb2; else return sb3;
+    };
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = (wave / WC) * WM, wave_n = (wave % WC) * WN;
     const int tile = blockIdx.x, z = blockIdx.y;
-    const int k0 = (tile / p.n_tiles) * BM, n0 = (tile % p.n_tiles) * BN;
+    const int k0 = (tile / p.n_tiles) * BMT, n0 = (tile % p.n_tiles) * BNT;
     const int RSC = p.R * p.S * p.C;
-    const long long M = (long long)p.N * p.P * p.Q;
-    const long long m_begin = (long long)z * p.span;
-    long long m_end = m_begin + p.span;
-    if (m_end > M) m_end = M;
-    const int KT = m_end > m_begin ? (int)((m_end - m_begin + BP - 1) / BP) : 0;
+    const int m_begin = z * p.span;
+    const int m_end = min(m_begin + p.span, p.M);
+    const int KT = m_end > m_begin ? (m_end - m_begin + BP - 1) / BP : 0;
 
-    // ---- load bookkeeping: this thread owns chunk column ld_col of rows ld_row0 + 16*i ----
-    const int ld_col = tid % ROW_CHUNKS, ld_row0 = tid / ROW_CHUNKS;
-    const int kch = k0 + ld_col * 8;                 // dy channel of the chunk
-    const bool a_col_ok = kch < p.K;
-    const int col = n0 + ld_col * 8;                 // filter column of the chunk
-    const bool b_col_ok = col < RSC;
-    const int tap = b_col_ok ? col / p.C : 0, cc = b_col_ok ? col % p.C : 0;
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (int)p.dy_bytes, 0x00020000);
+
+    // ---- A side (dy): lane -> pixel row RPLA*i + lane/RCA of the stage, k-channel chunk fixed -------
+    const int la_sub = lane / RCA;
+    const int la_chunk = (lane % RCA) ^ row_swz<RCA>(RPLA * wave + la_sub);   // RPLA*NW*j never changes the swizzle
+    const int kch = k0 + la_chunk * 8;
+    int a_m[A_LD];                       // pixel index of this lane's row in the current stage
+    unsigned a_col = kch < p.K ? (unsigned)kch * 2u : OOB;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) a_m[i] = m_begin + RPLA * (wave + NW * i) + la_sub;
+
+    // ---- B side (x gather): filter column chunk fixed per lane -> fixed tap (r,s) and channel ------
+    const int lb_sub = lane / RCB;
+    const int lb_chunk = (lane % RCB) ^ row_swz<RCB>(RPLB * wave + lb_sub);
+    const int col = n0 + lb_chunk * 8;
+    const bool col_ok = col < RSC;
+    const int tap = col_ok ? col / p.C : 0, cc = col_ok ? col % p.C : 0;
     const int fr = tap / p.S, fs = tap % p.S;
-
-    int pn[LD], pp[LD], pq[LD];
+    const int tap_off = col_ok ? ((fr * p.W + fs) * p.C + cc) * 2 : 0;     // bytes, relative to the window origin
+    // window origin (p*stride-pad, q*stride-pad) of each row, its byte offset, and (n,p,q) to advance it
+    int b_n[B_LD], b_p[B_LD], b_q[B_LD], b_m[B_LD];
 #pragma unroll
-    for (int i = 0; i < LD; ++i) {
-        const long long m = m_begin + ld_row0 + i * ROWS_PER_PASS;
-        pq[i] = (int)(m % p.Q);
-        const long long t = m / p.Q;
-        pp[i] = (int)(t % p.P);
-        pn[i] = (int)(t / p.P);
+    for (int i = 0; i < B_LD; ++i) {
+        const int m = m_begin + RPLB * (wave + NW * i) + lb_sub;
+        b_m[i] = m;
+        b_q[i] = (int)((unsigned)m % (unsigned)p.Q);
+        const unsigned t = (unsigned)m / (unsigned)p.Q;
+        b_p[i] = (int)(t % (unsigned)p.P);
+        b_n[i] = (int)(t / (unsigned)p.P);
     }
-    long long m_row = m_begin + ld_row0;   // pixel index of row i is m_row + 16*i
+    const int lim_hw = ((p.H - 1) & 0xFFFF) | ((p.W - 1) << 16);
+    const int tap_hw = ((fr - p.pad) & 0xFFFF) | ((fs - p.pad) << 16);
 
-    uint4 ra[LD], rb[LD];
-    auto load_global = [&]() {
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const long long m = m_row + i * ROWS_PER_PASS;
-            const bool row_ok = m < m_end;
-            ra[i] = (row_ok && a_col_ok) ? *reinterpret_cast<const uint4 *>(p.dy + m * p.K + kch) : make_uint4(0, 0, 0, 0);
-            const int h = pp[i] * p.stride - p.pad + fr, v = pq[i] * p.stride - p.pad + fs;
-            const bool ok = row_ok && b_col_ok && (unsigned)h < (unsigned)p.H && (unsigned)v < (unsigned)p.W;
-            rb[i] = ok ? *reinterpret_cast<const uint4 *>(p.x + (((long long)pn[i] * p.H + h) * p.W + v) * p.C + cc)
-                       : make_uint4(0, 0, 0, 0);
-            // advance this row by BP pixels
-            int q = pq[i] + p.dq;
-            const int cq = q >= p.Q;
+    unsigned va[A_LD], vb[B_LD];
+    // address tasks: 0..A_LD-1 = dy rows, A_LD..A_LD+B_LD-1 = x rows (each also advances its row by one stage)
+    auto addr_task = [&](auto t) {
+        constexpr int Tk = decltype(t)::value;
+        if constexpr (Tk < A_LD) {
+            va[Tk] = a_m[Tk] < m_end ? (unsigned)a_m[Tk] * (unsigned)(p.K * 2) + a_col : OOB;
+            a_m[Tk] += BP;
+        } else {
+            constexpr int i = Tk - A_LD;
+            const int h0 = b_p[i] * p.stride, w0 = b_q[i] * p.stride;
+            const s16x2 hw = __builtin_bit_cast(s16x2, (h0 & 0xFFFF) | (w0 << 16)) + __builtin_bit_cast(s16x2, tap_hw);
+            const s16x2 d = __builtin_bit_cast(s16x2, lim_hw) - hw;
+            const int bad = (__builtin_bit_cast(int, hw) | __builtin_bit_cast(int, d)) & (int)0x80008000;
+            const int org = ((b_n[i] * p.H + h0 - p.pad) * p.W + (w0 - p.pad)) * (p.C * 2);
+            vb[i] = (bad == 0 && b_m[i] < m_end && col_ok) ? (unsigned)(org + tap_off) : OOB;
+            // advance by BP pixels
+            b_m[i] += BP;
+            int q = b_q[i] + p.dq;
+            const int cq = q >= p.Q ? 1 : 0;
             q -= cq ? p.Q : 0;
-            int pr = pp[i] + p.dp + cq;
-            const int cp = pr >= p.P;
+            int pr = b_p[i] + p.dp + cq;
+            const int cp = pr >= p.P ? 1 : 0;
             pr -= cp ? p.P : 0;
-            pq[i] = q; pp[i] = pr; pn[i] += p.dn + cp;
+            b_q[i] = q; b_p[i] = pr; b_n[i] += p.dn + cp;
         }
-        m_row += BP;
     };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int row = ld_row0 + i * ROWS_PER_PASS;
-            *reinterpret_cast<uint4 *>(&lds_a[buf][swz(row, ld_col)]) = ra[i];
-            *reinterpret_cast<uint4 *>(&lds_b[buf][swz(row, ld_col)]) = rb[i];
-        }
+    auto load_task = [&](auto t, bf16_t *dst_a, bf16_t *dst_b) {
+        constexpr int Tk = decltype(t)::value;
+        if constexpr (Tk < A_LD) load16_to_lds(rs_dy, va[Tk], dst_a + (wave + NW * Tk) * RPLA * BMT);
+        else load16_to_lds(rs_x, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * RPLB * BNT);
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[MI][NI];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NI; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // transposing-read geometry: 16-lane group g, lane j within it
+    // transposing-read geometry: 16-lane group g, lane j within it.  One read: 4 pixel rows x 16 channels.
     const int g = lane >> 4, j16 = lane & 15;
     const int tr_row = (g >> 1) * 8 + (j16 >> 2);        // pixel row within a 16-pixel k-step (second read: +4)
     const int tr_ch = (g & 1) * 16 + (j16 & 3) * 4;      // channel within a 32-channel block
-
-    auto frag = [&](const bf16_t *tile, int ch_base, int ks) -> bf16x8 {
-        const int row = ks * 16 + tr_row;
+    // element offsets of the two reads within a 16-pixel k-step, per operand, for channel block 0
+    auto tr_off = [&](auto rc, int ch_base, int row) {
+        constexpr int RC = decltype(rc)::value;
         const int ch = ch_base + tr_ch;
-        const bf16_t *p0 = tile + swz(row, ch >> 3) + (ch & 7);
-        const bf16_t *p1 = tile + swz(row + 4, ch >> 3) + (ch & 7);
-        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p0);
-        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p1);
-        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return row * (RC * 8) + ((((ch >> 3) ^ row_swz<RC>(row))) << 3) + (ch & 7);
+    };
+    int offa_lo[MI], offa_hi[MI], offb_lo[NI], offb_hi[NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) { offa_lo[i] = tr_off(IC<RCA>{}, wave_m + i * 32, tr_row); offa_hi[i] = tr_off(IC<RCA>{}, wave_m + i * 32, tr_row + 4); }
+#pragma unroll
+    for (int j = 0; j < NI; ++j) { offb_lo[j] = tr_off(IC<RCB>{}, wave_n + j * 32, tr_row); offb_hi[j] = tr_off(IC<RCB>{}, wave_n + j * 32, tr_row + 4); }
+
+    struct Frags { bf16x8 a[MI], b[NI]; };
+    // the swizzle depends on row % 4 only and a k-step advances the row by 16: offsets just shift
+    auto read_task = [&](auto t, Frags &f, const bf16_t *src_a, const bf16_t *src_b, int ks) {
+        constexpr int Tk = decltype(t)::value;
+        if constexpr (Tk < MI) {
+            const bf16_t *q = src_a + ks * 16 * BMT;
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(q + offa_lo[Tk]));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(q + offa_hi[Tk]));
+            f.a[Tk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        } else {
+            const bf16_t *q = src_b + ks * 16 * BNT;
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(q + offb_lo[Tk - MI]));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(q + offb_hi[Tk - MI]));
+            f.b[Tk - MI] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    };
+    constexpr int N_READ = MI + NI;
+
+    auto mfma_with = [&](const Frags &f, auto ntask, auto &&task) {
+        constexpr int NTASK = decltype(ntask)::value;
+        static_for<NMF>([&](auto s) {
+            constexpr int S = decltype(s)::value;
+            acc[S / NI][S % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[S / NI], f.b[S % NI], acc[S / NI][S % NI], 0, 0, 0);
+            static_for<NTASK>([&](auto t) {
+                constexpr int Tk = decltype(t)::value;
+                if constexpr (Tk * NMF / NTASK == S) task(t);
+            });
+            pin();
+        });
     };
 
-    if (KT > 0) {
-        load_global();
-        store_lds(0);
-    }
+    // ---- pipeline (same shape as the forward kernel's) --------------------------------------------
+    Frags f0, f1;
+    static_for<NS>([&](auto s) {
+        static_for<L>([&](auto t) { addr_task(t); });
+        static_for<L>([&](auto t) { load_task(t, stage_a(s), stage_b(s)); });
+    });
+    wait_vmcnt<L * (NS - 1)>();
     __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_global();
-#pragma unroll
-        for (int ks = 0; ks < BP / 16; ++ks) {
-            bf16x8 fa[2], fb[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = frag(lds_a[buf], wave_m + i * 32, ks);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) fb[j] = frag(lds_b[buf], wave_n + j * 32, ks);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < KT) store_lds(buf ^ 1);
+    static_for<N_READ>([&](auto t) { read_task(t, f0, sa0, sb0, 0); });
+
+    auto run_stage = [&](auto s) {
+        constexpr int S = decltype(s)::value;
+        constexpr int S1 = (S + 1) % NS;
+        bf16_t *ca = stage_a(s), *cb = stage_b(s);
+        static_for<KS - 1>([&](auto k) {
+            constexpr int ks = decltype(k)::value;
+            Frags &cur = (ks & 1) ? f1 : f0;
+            Frags &nxt = (ks & 1) ? f0 : f1;
+            if constexpr (ks == KS - 2) {
+                mfma_with(cur, IC<N_READ + L>{}, [&](auto t) {
+                    constexpr int Tk = decltype(t)::value;
+                    if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<Tk - N_READ>{});
+                });
+            } else {
+                mfma_with(cur, IC<N_READ>{}, [&](auto t) { read_task(t, nxt, ca, cb, ks + 1); });
+            }
+        });
+        wait_lgkmcnt0();
+        wait_vmcnt<L * (NS - 2)>();
         __syncthreads();
+        mfma_with(f1, IC<L + N_READ>{}, [&](auto t) {
+            constexpr int Tk = decltype(t)::value;
+            if constexpr (Tk < L) load_task(t, ca, cb);
+            else read_task(IC<Tk - L>{}, f0, stage_a(IC<S1>{}), stage_b(IC<S1>{}), 0);
+        });
+    };
+    for (int kt = 0; kt < KT; kt += NS) {
+        run_stage(IC<0>{});
+        if (kt + 1 < KT) run_stage(IC<1>{});
+        if constexpr (NS > 2) if (kt + 2 < KT) run_stage(IC<2>{});
+        if constexpr (NS > 3) if (kt + 3 < KT) run_stage(IC<3>{});
     }
+    wait_vmcnt<0>();
 
     // ---- fp32 partial tile -> workspace ------------------------------------------------------
     float *out = p.partial + (size_t)z * p.K * RSC;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int k = k0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
             if (k >= p.K) continue;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < NI; ++j) {
                 const int c = n0 + wave_n + j * 32 + (lane & 31);
                 if (c < RSC) out[(size_t)k * RSC + c] = acc[i][j][e];
             }
@@ -186,53 +304,122 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     dw[gid] = acc;
 }
 
+struct WgradTile { int bm, bn, bp, slots; const char *name; };   // slots: workgroups that fit one CU
+const WgradTile kTiles[] = {
+    {128, 128, 64, 2, "wgrad_128x128_p64s2_w4"},
+    {256, 256, 32, 1, "wgrad_256x256_p32s4_w8"},
+    {256, 128, 32, 1, "wgrad_256x128_p32s4_w8"},
+    {128, 256, 32, 1, "wgrad_128x256_p32s4_w8"},
+    {64, 64, 64, 4, "wgrad_64x64_p64s2_w4"},
+    {64, 128, 64, 2, "wgrad_64x128_p64s2_w4"},
+    {128, 64, 64, 2, "wgrad_128x64_p64s2_w4"},
+};
+constexpr int N_TILES = sizeof(kTiles) / sizeof(kTiles[0]);
+
+template <int BMT, int BNT, int BP, int NS, int WR, int WC>
+int launch(const WgradParams &p, int tiles, hipStream_t st)
+{
+    hipLaunchKernelGGL((wgrad_kernel<BMT, BNT, BP, NS, WR, WC>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(64 * WR * WC), 0,
+                       st, p);
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
+int launch_choice(int idx, const WgradParams &p, int tiles, hipStream_t st)
+{
+    switch (idx) {
+    case 0: return launch<128, 128, 64, 2, 2, 2>(p, tiles, st);
+    case 1: return launch<256, 256, 32, 4, 2, 4>(p, tiles, st);
+    case 2: return launch<256, 128, 32, 4, 4, 2>(p, tiles, st);
+    case 3: return launch<128, 256, 32, 4, 2, 4>(p, tiles, st);
+    case 4: return launch<64, 64, 64, 2, 2, 2>(p, tiles, st);
+    case 5: return launch<64, 128, 64, 2, 2, 2>(p, tiles, st);
+    default: return launch<128, 64, 64, 2, 2, 2>(p, tiles, st);
+    }
+}
+
+struct Plan { int tile, k_tiles, n_tiles, splits, span; };
+
+// Tile and split choice.  MXC_FORCE_WGRAD=<name> (tuning sweeps only) overrides the tile.
+Plan make_plan(const ConvShape &s)
+{
+    const int RSC = s.R * s.S * s.C;
+    const long long M = (long long)s.N * s.P * s.Q;
+    int t = 0;
+    if (s.K <= 64 && RSC <= 64) t = 4;
+    else if (s.K <= 64) t = 5;
+    else if (RSC <= 64) t = 6;
+    if (const char *f = getenv("MXC_FORCE_WGRAD"))
+        for (int i = 0; i < N_TILES; ++i)
+            if (!strcmp(f, kTiles[i].name)) t = i;
+    Plan pl;
+    pl.tile = t;
+    pl.k_tiles = (s.K + kTiles[t].bm - 1) / kTiles[t].bm;
+    pl.n_tiles = (RSC + kTiles[t].bn - 1) / kTiles[t].bn;
+    const long long tiles = (long long)pl.k_tiles * pl.n_tiles;
+    // Splits: fill whole rounds of the chip's workgroup slots (256 CUs x slots per CU) as evenly as
+    // possible, with a small penalty per split for the partial-tile traffic, and at least 8 stages
+    // of work per split.
+    const long long slots = 256LL * kTiles[t].slots;
+    long long max_splits = (M + 8LL * kTiles[t].bp - 1) / (8LL * kTiles[t].bp);
+    if (max_splits > 256) max_splits = 256;
+    if (max_splits < 1) max_splits = 1;
+    long long splits = 1;
+    double best = -1.0;
+    for (long long sp = 1; sp <= max_splits; ++sp) {
+        const long long wgs = tiles * sp, rounds = (wgs + slots - 1) / slots;
+        const double score = (double)wgs / (double)(rounds * slots) - 0.004 * (double)sp;
+        if (score > best) { best = score; splits = sp; }
+    }
+    long long span = (M + splits - 1) / splits;
+    span = (span + kTiles[t].bp - 1) / kTiles[t].bp * kTiles[t].bp;
+    pl.splits = (int)((M + span - 1) / span);
+    pl.span = (int)span;
+    return pl;
+}
+
 }  // namespace
 
-bool wgrad_supported(const ConvShape &s) { return s.C % 8 == 0 && s.K % 8 == 0; }
-
-int wgrad_splits(const ConvShape &s)
+bool wgrad_supported(const ConvShape &s)
 {
     const long long M = (long long)s.N * s.P * s.Q;
-    const long long tiles = (long long)((s.K + BM - 1) / BM) * ((s.R * s.S * s.C + BN - 1) / BN);
-    long long splits = (1024 + tiles - 1) / tiles;          // aim for ~4 workgroups per CU
-    const long long max_by_work = (M + 4 * BP - 1) / (4 * BP);  // at least 4 stages per split
-    if (splits > max_by_work) splits = max_by_work;
-    if (splits > 1024) splits = 1024;
-    if (splits < 1) splits = 1;
-    return (int)splits;
+    return s.C % 8 == 0 && s.K % 8 == 0 && M < 0x7FFF0000ll && (long long)s.N * s.H * s.W * s.C * 2 < 0x7FFF0000ll &&
+           M * s.K * 2 < 0x7FFF0000ll && s.H + s.R + s.pad <= 8192 && s.W + s.S + s.pad <= 8192 &&
+           (long long)s.P * s.stride <= 8192 && (long long)s.Q * s.stride <= 8192 &&
+           (long long)s.K * s.R * s.S * s.C < 0x7FFFFFFFll;
 }
 
 size_t wgrad_workspace(const ConvShape &s)
 {
-    return (size_t)wgrad_splits(s) * s.K * s.R * s.S * s.C * sizeof(float);
+    return (size_t)make_plan(s).splits * s.K * s.R * s.S * s.C * sizeof(float);
 }
 
 int wgrad(const ConvShape &s, const void *x, const void *dy, float *dw, float *partial, hipStream_t st,
           const char **variant)
 {
+    const Plan pl = make_plan(s);
+    const WgradTile &tc = kTiles[pl.tile];
     WgradParams p{};
     p.x = (const bf16_t *)x; p.dy = (const bf16_t *)dy; p.partial = partial;
     p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.R = s.R; p.S = s.S;
     p.stride = s.stride; p.pad = s.pad; p.P = s.P; p.Q = s.Q;
-    p.k_tiles = (s.K + BM - 1) / BM;
-    p.n_tiles = (s.R * s.S * s.C + BN - 1) / BN;
-    p.splits = wgrad_splits(s);
-    const long long M = (long long)s.N * s.P * s.Q;
-    long long span = (M + p.splits - 1) / p.splits;
-    span = (span + BP - 1) / BP * BP;
-    p.span = span;
-    p.dq = BP % s.Q;
-    const int rows = BP / s.Q;
+    p.n_tiles = pl.n_tiles;
+    p.splits = pl.splits;
+    p.span = pl.span;
+    p.M = s.N * s.P * s.Q;
+    p.dq = tc.bp % s.Q;
+    const int rows = tc.bp / s.Q;
     p.dp = rows % s.P;
     p.dn = rows / s.P;
-    const long long tiles = (long long)p.k_tiles * p.n_tiles;
+    p.x_bytes = (unsigned)((long long)s.N * s.H * s.W * s.C * 2);
+    p.dy_bytes = (unsigned)((long long)p.M * s.K * 2);
+    const long long tiles = (long long)pl.k_tiles * pl.n_tiles;
     if (tiles > 0x7FFFFFFFll || p.splits > 65535) return MXC_ERR_SHAPE;
-    hipLaunchKernelGGL(wgrad_kernel, dim3((unsigned)tiles, (unsigned)p.splits), dim3(NT), 0, st, p);
-    if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
+    const int rc = launch_choice(pl.tile, p, (int)tiles, st);
+    if (rc != MXC_OK) return rc;
     const int total = s.K * s.R * s.S * s.C;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, dw, total,
                        p.splits);
-    *variant = "wgrad_128x128_splitk";
+    *variant = tc.name;
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
 
