@@ -312,25 +312,57 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
     }
     wait_vmcnt<0>();   // drain the zero-fill loads of the stages past the end before the tile's LDS is abandoned
 
-    // ---- epilogue: fp32 -> bf16 (RNE), scatter to the output pixels -------------------------
+    // ---- epilogue: fp32 -> bf16 (RNE), to the output pixels ------------------------------------
     // accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+    auto out_pixel = [&](int m) -> long long {
+        if (p.linear_out) return m;
+        const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
+        const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
+        return ((long long)n * p.Ho + ((int)a * p.out_mul + p.out_off_h)) * p.Wo + ((int)b * p.out_mul + p.out_off_w);
+    };
+    if ((p.Co & 7) == 0) {
+        // Through LDS, one 32-row block of the wave tile at a time, so that global stores are 16 bytes
+        // per lane and a row's WN channels leave as one contiguous run.
+        static_assert(NW * 32 * WN <= (SZA > SZB ? SZA : SZB), "epilogue staging must fit one stage buffer");
+        constexpr int CPR = WN / 8;                   // 16-byte chunks per staged row
+        wait_lgkmcnt0();
+        __syncthreads();                              // every wave is done reading operands: LDS is free
+        bf16_t *stg = (SZA >= SZB ? sa0 : sb0) + wave * (32 * WN);
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+        for (int i = 0; i < MI; ++i) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
-            if (m >= p.M) continue;
-            long long pix = m;
-            if (!p.linear_out) {
-                const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
-                const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
-                pix = ((long long)n * p.Ho + ((int)a * p.out_mul + p.out_off_h)) * p.Wo + ((int)b * p.out_mul + p.out_off_w);
+            for (int e = 0; e < 16; ++e)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    stg[(8 * (e >> 2) + 4 * frag_kg + (e & 3)) * WN + j * 32 + frag_row] = f32_to_bf16(acc[i][j][e]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int k = 0; k < 32 * CPR / 64; ++k) {
+                const int idx = k * 64 + lane;
+                const int r = idx / CPR, c = idx % CPR;
+                const int m = m0 + wave_m + i * 32 + r, co = n0 + wave_n + c * 8;
+                const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * WN + c * 8);
+                if (m < p.M && co < p.Co) *reinterpret_cast<uint4 *>(p.out + out_pixel(m) * p.Co + co) = v;
             }
-            bf16_t *orow = p.out + pix * p.Co;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    } else {
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int co = n0 + wave_n + j * 32 + frag_row;
-                if (co < p.Co) orow[co] = f32_to_bf16(acc[i][j][e]);
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
+                if (m >= p.M) continue;
+                bf16_t *orow = p.out + out_pixel(m) * p.Co;
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int co = n0 + wave_n + j * 32 + frag_row;
+                    if (co < p.Co) orow[co] = f32_to_bf16(acc[i][j][e]);
+                }
             }
         }
     }
@@ -354,42 +386,56 @@ int launch(IgemmParams p, hipStream_t st)
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
 
-struct TileChoice { int bm, bn; const char *name; };
+// A tile shape the launcher can pick: output tile, workgroups that fit one CU at a time (LDS and
+// register budget) and the matrix-pipe utilisation it reaches relative to the 256x256 tile when the
+// chip is full (measured on the VGG-style 3x3 layers).
+struct TileChoice { int bm, bn, slots; float util; const char *name; };
 const TileChoice kTiles[] = {
-    {128, 128, "igemm_128x128_k64s2_w4"}, {256, 256, "igemm_256x256_k32s4_w8"}, {256, 128, "igemm_256x128_k64s3_w8"},
-    {256, 128, "igemm_256x128_k32s4_w4"}, {128, 128, "igemm_128x128_k64s4_w4"}, {128, 128, "igemm_128x128_k32s4_w4"},
-    {128, 64, "igemm_128x64_k64s2_w4"}, {256, 64, "igemm_256x64_k64s3_w4"}, {128, 32, "igemm_128x32_k64s2_w4"},
-    {256, 32, "igemm_256x32_k64s3_w4"}, {256, 256, "igemm_256x256_k64s2_w8"}, {256, 256, "igemm_256x256_k32s3_w8"},
+    {128, 128, 2, 0.91f, "igemm_128x128_k64s2_w4"},
+    {256, 256, 1, 1.00f, "igemm_256x256_k64s2_w8"},
+    {256, 128, 1, 0.84f, "igemm_256x128_k64s3_w8"},
+    {128, 256, 1, 0.84f, "igemm_128x256_k64s3_w8"},
+    {128, 64, 3, 0.70f, "igemm_128x64_k64s2_w4"},
+    {256, 64, 2, 0.70f, "igemm_256x64_k32s3_w4"},
+    {128, 32, 4, 0.50f, "igemm_128x32_k64s2_w4"},
+    {256, 32, 2, 0.50f, "igemm_256x32_k64s2_w4"},
 };
+constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
 
 int launch_choice(int idx, const IgemmParams &p, hipStream_t st)
 {
     switch (idx) {
     case 0: return launch<128, 128, 64, 2, 2, 2>(p, st);
-    case 1: return launch<256, 256, 32, 4, 2, 4>(p, st);
+    case 1: return launch<256, 256, 64, 2, 2, 4>(p, st);
     case 2: return launch<256, 128, 64, 3, 4, 2>(p, st);
-    case 3: return launch<256, 128, 32, 4, 2, 2>(p, st);
-    case 4: return launch<128, 128, 64, 4, 2, 2>(p, st);
-    case 5: return launch<128, 128, 32, 4, 2, 2>(p, st);
-    case 6: return launch<128, 64, 64, 2, 2, 2>(p, st);
-    case 7: return launch<256, 64, 64, 3, 4, 1>(p, st);
-    case 8: return launch<128, 32, 64, 2, 4, 1>(p, st);
-    case 9: return launch<256, 32, 64, 3, 4, 1>(p, st);
-    case 10: return launch<256, 256, 64, 2, 2, 4>(p, st);
-    default: return launch<256, 256, 32, 3, 2, 4>(p, st);
+    case 3: return launch<128, 256, 64, 3, 2, 4>(p, st);
+    case 4: return launch<128, 64, 64, 2, 2, 2>(p, st);
+    case 5: return launch<256, 64, 32, 3, 4, 1>(p, st);
+    case 6: return launch<128, 32, 64, 2, 4, 1>(p, st);
+    default: return launch<256, 32, 64, 2, 4, 1>(p, st);
     }
 }
 
-// Tile choice.  MXC_FORCE_VARIANT=<name> (tuning sweeps only) overrides the heuristic.
+// Tile choice: the shape with the least modelled time = rounds over the chip's workgroup slots x
+// work per round / utilisation (padding waste and the partly filled last round are what differ).
+// MXC_FORCE_VARIANT=<name> (tuning sweeps only) overrides it.
 int choose_tile(long long M, int Co, int Kd)
 {
-    (void)M; (void)Kd;
+    (void)Kd;
     if (const char *f = getenv("MXC_FORCE_VARIANT"))
-        for (int i = 0; i < (int)(sizeof(kTiles) / sizeof(kTiles[0])); ++i)
+        for (int i = 0; i < N_TILE_CHOICES; ++i)
             if (!strcmp(f, kTiles[i].name)) return i;
-    if (Co <= 32) return 8;
-    if (Co <= 64) return 6;
-    return 0;
+    int best = 0;
+    double best_t = 1e300;
+    for (int i = 0; i < N_TILE_CHOICES; ++i) {
+        const TileChoice &t = kTiles[i];
+        const long long tiles = ((M + t.bm - 1) / t.bm) * ((Co + t.bn - 1) / t.bn);
+        const long long slots = 256LL * t.slots;
+        const long long rounds = (tiles + slots - 1) / slots;
+        const double time = (double)rounds * t.slots * t.bm * t.bn / t.util;
+        if (time < best_t) { best_t = time; best = i; }
+    }
+    return best;
 }
 
 // The kernel addresses both operands with signed 32-bit byte offsets, packs tile-row coordinates
