@@ -2,6 +2,8 @@
 // and kernel selection.  See include/mxc.h for the contract of every call.
 #include <string.h>
 
+#include <string>
+
 #include "mxc_internal.h"
 
 namespace mxc {
@@ -51,19 +53,54 @@ int validate_shape(int N, int C, int H, int W, int K, int R, int S, int stride, 
 
 bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
 
+#define MXC_TRY(expr)                 \
+    do {                              \
+        const int rc_ = (expr);       \
+        if (rc_ != MXC_OK) return rc_; \
+    } while (0)
+
 // ---- passes in the working layout (NHWC / KRSC) --------------------------------
 // dry == true: only account workspace.
 
+ConvShape with_channels(const ConvShape &s, int C)
+{
+    ConvShape t = s;
+    t.C = C;
+    return t;
+}
+
 int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *y, Carver &ws, hipStream_t st, bool dry)
 {
-    (void)ws;
-    if (dry) return MXC_OK;
-    if (dtype == MXC_BF16 && igemm_fwd_supported(s)) {
-        const char *v = "";
+    const char *v = "";
+    if (dtype == MXC_BF16 && s.C % 8 == 0 && igemm_fwd_supported(s)) {
+        if (dry) return MXC_OK;
         const int rc = igemm_fwd(s, x, w, y, st, &v);
         set_variant("fwd", v);
         return rc;
     }
+    if (dtype == MXC_BF16 && s.C <= 4 && igemm_fwd_smallc_supported(s)) {
+        // first-layer style: zero-bordered image with 4 or 8 channels per pixel, filter rows as runs
+        const SmallCGeom g = smallc_geom(s);
+        void *xp = ws.take((size_t)s.N * g.Hp * g.Wp * g.pix * 2), *wp = ws.take((size_t)s.K * s.R * g.run * 2);
+        if (dry) return MXC_OK;
+        MXC_TRY(smallc_pack_x(s, x, xp, st));
+        MXC_TRY(smallc_pack_w(s, w, wp, st));
+        const int rc = igemm_fwd_smallc(s, xp, wp, y, st, &v);
+        set_variant("fwd", (std::string("smallc+") + v).c_str());
+        return rc;
+    }
+    const int C8 = (s.C + 7) / 8 * 8;
+    if (dtype == MXC_BF16 && s.C % 8 != 0 && igemm_fwd_supported(with_channels(s, C8))) {
+        // other channel counts: zero-pad the channels of x and w to a multiple of 8
+        void *xp = ws.take((size_t)s.N * s.H * s.W * C8 * 2), *wp = ws.take((size_t)s.K * s.R * s.S * C8 * 2);
+        if (dry) return MXC_OK;
+        MXC_TRY(pad_channels(x, xp, (long long)s.N * s.H * s.W, s.C, st));
+        MXC_TRY(pad_channels(w, wp, (long long)s.K * s.R * s.S, s.C, st));
+        const int rc = igemm_fwd(with_channels(s, C8), xp, wp, y, st, &v);
+        set_variant("fwd", (std::string("chanpad+") + v).c_str());
+        return rc;
+    }
+    if (dry) return MXC_OK;
     set_variant("fwd", "direct");
     return direct_fwd(s, dtype, x, w, y, st);
 }
@@ -87,12 +124,34 @@ int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, 
 int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw, Carver &ws, hipStream_t st,
                     bool dry)
 {
-    if (dtype == MXC_BF16 && wgrad_supported(s)) {
-        float *partial = (float *)ws.take(wgrad_workspace(s));
+    const char *v = "";
+    if (dtype == MXC_BF16 && s.C % 8 == 0 && wgrad_supported(wgrad_geom_plain(s))) {
+        const WgradGeom g = wgrad_geom_plain(s);
+        float *partial = (float *)ws.take(wgrad_workspace(g));
         if (dry) return MXC_OK;
-        const char *v = "";
-        const int rc = wgrad(s, x, dy, dw, partial, st, &v);
+        const int rc = wgrad(g, x, dy, dw, partial, st, &v);
         set_variant("bwd_weight", v);
+        return rc;
+    }
+    if (dtype == MXC_BF16 && s.C <= 4 && wgrad_supported(wgrad_geom_smallc(s))) {
+        const SmallCGeom sg = smallc_geom(s);
+        const WgradGeom g = wgrad_geom_smallc(s);
+        void *xp = ws.take((size_t)s.N * sg.Hp * sg.Wp * sg.pix * 2);
+        float *partial = (float *)ws.take(wgrad_workspace(g));
+        if (dry) return MXC_OK;
+        MXC_TRY(smallc_pack_x(s, x, xp, st));
+        const int rc = wgrad(g, xp, dy, dw, partial, st, &v);
+        set_variant("bwd_weight", (std::string("smallc+") + v).c_str());
+        return rc;
+    }
+    if (dtype == MXC_BF16 && s.C % 8 != 0 && wgrad_supported(wgrad_geom_chanpad(s))) {
+        const WgradGeom g = wgrad_geom_chanpad(s);
+        void *xp = ws.take((size_t)s.N * s.H * s.W * g.pix * 2);
+        float *partial = (float *)ws.take(wgrad_workspace(g));
+        if (dry) return MXC_OK;
+        MXC_TRY(pad_channels(x, xp, (long long)s.N * s.H * s.W, s.C, st));
+        const int rc = wgrad(g, xp, dy, dw, partial, st, &v);
+        set_variant("bwd_weight", (std::string("chanpad+") + v).c_str());
         return rc;
     }
     const int splits = direct_bwd_weight_splits(s);
@@ -103,12 +162,6 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
 }
 
 // ---- one driver per pass: handles the caller's layout ---------------------------
-
-#define MXC_TRY(expr)                 \
-    do {                              \
-        const int rc_ = (expr);       \
-        if (rc_ != MXC_OK) return rc_; \
-    } while (0)
 
 int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a, const void *b, void *out, Carver &ws,
              hipStream_t st, bool dry)

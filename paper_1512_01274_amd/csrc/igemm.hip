@@ -36,7 +36,9 @@ struct IgemmParams {
     const bf16_t *in;    // activations [N][Hi][Wi][Ci]
     const bf16_t *wm;    // filter matrix [Co][T*Ci]
     bf16_t *out;         // output tensor [N][Ho][Wo][Co]
-    int N, Hi, Wi, Ci;
+    int N, Hi, Wi;
+    int Ci;              // reduction elements per tap: a contiguous run starting at the tap's pixel
+    int pix;             // elements per pixel in memory (== Ci for plain NHWC; smaller when a run spans pixels)
     int Co;
     int TR, TS, tstep;   // tap grid and direction (+1 or -1)
     int Mh, Mw;          // output grid of this launch (per image)
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
         int2 e;
         if (t < T) {
             const int dh = (t / p.TS) * p.tstep, dv = (t % p.TS) * p.tstep;
-            e.x = ((dh * p.Wi + dv) * p.Ci) * 2;
+            e.x = ((dh * p.Wi + dv) * p.pix) * 2;
             e.y = (dh & 0xFFFF) | (dv << 16);
         } else {
             e.x = 0;
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
             const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
             const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
             const int h = (int)a * p.in_mul + p.in_off_h, w = (int)b * p.in_mul + p.in_off_w;
-            a_off[i] = (int)((((long long)n * p.Hi + h) * p.Wi + w) * p.Ci * 2);
+            a_off[i] = (int)((((long long)n * p.Hi + h) * p.Wi + w) * p.pix * 2);
             a_hw[i] = (h & 0xFFFF) | (w << 16);
         } else {
             a_off[i] = 0;
@@ -377,7 +379,7 @@ int launch(IgemmParams p, hipStream_t st)
     if (mt * p.n_tiles > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
     p.M = (int)M;
     p.m_tiles = (int)mt;
-    p.in_bytes = (unsigned)((long long)p.N * p.Hi * p.Wi * p.Ci * 2);
+    p.in_bytes = (unsigned)((long long)p.N * p.Hi * p.Wi * p.pix * 2);
     p.wm_bytes = (unsigned)((long long)p.Co * p.TR * p.TS * p.Ci * 2);
     p.linear_out = (p.out_mul == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
     const int total = p.m_tiles * p.n_tiles;
@@ -489,12 +491,36 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
 {
     IgemmParams p{};
     p.in = (const bf16_t *)x; p.wm = (const bf16_t *)w; p.out = (bf16_t *)y;
-    p.N = s.N; p.Hi = s.H; p.Wi = s.W; p.Ci = s.C; p.Co = s.K;
+    p.N = s.N; p.Hi = s.H; p.Wi = s.W; p.Ci = s.C; p.pix = s.C; p.Co = s.K;
     p.TR = s.R; p.TS = s.S; p.tstep = 1;
     p.Mh = s.P; p.Mw = s.Q;
     p.in_mul = s.stride; p.in_off_h = -s.pad; p.in_off_w = -s.pad;
     p.Ho = s.P; p.Wo = s.Q; p.out_mul = 1; p.out_off_h = 0; p.out_off_w = 0;
     const int tc = choose_tile((long long)s.N * s.P * s.Q, s.K, s.R * s.S * s.C);
+    *variant = kTiles[tc].name;
+    return launch_choice(tc, p, st);
+}
+
+bool igemm_fwd_smallc_supported(const ConvShape &s)
+{
+    const SmallCGeom g = smallc_geom(s);
+    return s.C <= 4 && igemm_dims_ok((long long)s.N * g.Hp * g.Wp * g.pix, (long long)s.K * s.R * g.run,
+                                     (long long)s.N * s.P * s.Q, g.Hp, g.Wp, s.R + s.S + s.stride, s.R);
+}
+
+// Forward for a small-C image packed by smallc_pack_x / smallc_pack_w: R taps (filter rows), each a
+// contiguous run of S*pix elements of the zero-bordered image.
+int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y, hipStream_t st, const char **variant)
+{
+    const SmallCGeom g = smallc_geom(s);
+    IgemmParams p{};
+    p.in = (const bf16_t *)xp; p.wm = (const bf16_t *)wp; p.out = (bf16_t *)y;
+    p.N = s.N; p.Hi = g.Hp; p.Wi = g.Wp; p.Ci = g.run; p.pix = g.pix; p.Co = s.K;
+    p.TR = s.R; p.TS = 1; p.tstep = 1;
+    p.Mh = s.P; p.Mw = s.Q;
+    p.in_mul = s.stride; p.in_off_h = 0; p.in_off_w = 0;
+    p.Ho = s.P; p.Wo = s.Q; p.out_mul = 1; p.out_off_h = 0; p.out_off_w = 0;
+    const int tc = choose_tile((long long)s.N * s.P * s.Q, s.K, s.R * g.run);
     *variant = kTiles[tc].name;
     return launch_choice(tc, p, st);
 }
@@ -529,7 +555,7 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
             const int Mw = v_first < s.W ? (s.W - 1 - v_first) / s.stride + 1 : 0;
             IgemmParams p{};
             p.in = (const bf16_t *)dy; p.wm = (const bf16_t *)wt + wt_off; p.out = (bf16_t *)dx;
-            p.N = s.N; p.Hi = s.P; p.Wi = s.Q; p.Ci = s.K; p.Co = s.C;
+            p.N = s.N; p.Hi = s.P; p.Wi = s.Q; p.Ci = s.K; p.pix = s.K; p.Co = s.C;
             p.TR = TR; p.TS = TS; p.tstep = -1;
             p.Mh = Mh; p.Mw = Mw;
             p.in_mul = 1; p.in_off_h = hh0; p.in_off_w = vv0;

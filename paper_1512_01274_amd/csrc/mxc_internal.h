@@ -56,10 +56,31 @@ size_t igemm_bwd_data_workspace(const ConvShape &s);   // bytes for the re-packe
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
                    const char **variant);
 
+// ---- prep.hip: re-packing for channel counts that are not a multiple of 8 ---------
+// [rows][C] -> [rows][C8] (C8 = C rounded up to 8, new channels zero); bf16 only.
+int pad_channels(const void *src, void *dst, long long rows, int C, hipStream_t st);
+// Small-C (C <= 4) image packing: `pix` channels per pixel, explicit zero border, padded size Hp x Wp;
+// one filter row's taps form a contiguous run of `run` elements.
+struct SmallCGeom { int pix, Hp, Wp, run; };
+SmallCGeom smallc_geom(const ConvShape &s);
+int smallc_pack_x(const ConvShape &s, const void *x, void *xp, hipStream_t st);   // xp: N*Hp*Wp*pix elements
+int smallc_pack_w(const ConvShape &s, const void *w, void *wp, hipStream_t st);   // wp: K*R*run elements
+bool igemm_fwd_smallc_supported(const ConvShape &s);
+int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y, hipStream_t st, const char **variant);
+
 // ---- wgrad.hip: bf16 MFMA backward-weight with split reduction ------------------
-bool wgrad_supported(const ConvShape &s);
-size_t wgrad_workspace(const ConvShape &s);            // bytes of fp32 partial tiles
-int wgrad(const ConvShape &s, const void *x, const void *dy, float *dw, float *partial, hipStream_t st,
+// The problem as the kernel sees it: x[N][H][W][pix], dy[N][P][Q][K]; filter columns are TR*TS taps of
+// `run` contiguous elements each; dw[k][r][s][c] (dense R,S,C) is read back from column
+// r*col_r + s*col_s + c.
+struct WgradGeom {
+    int N, H, W, pix, K, P, Q, stride, pad, TR, TS, run, R, S, C, col_r, col_s;
+};
+WgradGeom wgrad_geom_plain(const ConvShape &s);     // C % 8 == 0
+WgradGeom wgrad_geom_chanpad(const ConvShape &s);   // x already padded to C8 channels
+WgradGeom wgrad_geom_smallc(const ConvShape &s);    // x already packed by smallc_pack_x
+bool wgrad_supported(const WgradGeom &g);
+size_t wgrad_workspace(const WgradGeom &g);            // bytes of fp32 partial tiles
+int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *partial, hipStream_t st,
           const char **variant);
 
 }  // namespace mxc

@@ -36,10 +36,12 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 constexpr unsigned OOB = 0x80000000u;   // a buffer offset no operand reaches: the load returns zeros
 
 struct WgradParams {
-    const bf16_t *x;    // [N][H][W][C]
+    const bf16_t *x;    // [N][H][W][pix]
     const bf16_t *dy;   // [N][P][Q][K]
-    float *partial;     // [splits][K][R*S*C]
-    int N, C, H, W, K, R, S, stride, pad, P, Q;
+    float *partial;     // [splits][K][ncols]
+    int N, H, W, pix;   // x geometry: pix elements per pixel in memory
+    int K, P, Q, stride, pad;
+    int TS, run, ncols; // filter columns: col = tap*run + e, tap = fr*TS + fs, e = offset in the tap's contiguous run
     int n_tiles, splits;
     int span;           // pixels per split (multiple of the stage size)
     int M;              // N*P*Q
@@ -107,7 +109,7 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
     const int wave_m = (wave / WC) * WM, wave_n = (wave % WC) * WN;
     const int tile = blockIdx.x, z = blockIdx.y;
     const int k0 = (tile / p.n_tiles) * BMT, n0 = (tile % p.n_tiles) * BNT;
-    const int RSC = p.R * p.S * p.C;
+    const int RSC = p.ncols;
     const int m_begin = z * p.span;
     const int m_end = min(m_begin + p.span, p.M);
     const int KT = m_end > m_begin ? (m_end - m_begin + BP - 1) / BP : 0;
@@ -129,9 +131,9 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
     const int lb_chunk = (lane % RCB) ^ row_swz<RCB>(RPLB * wave + lb_sub);
     const int col = n0 + lb_chunk * 8;
     const bool col_ok = col < RSC;
-    const int tap = col_ok ? col / p.C : 0, cc = col_ok ? col % p.C : 0;
-    const int fr = tap / p.S, fs = tap % p.S;
-    const int tap_off = col_ok ? ((fr * p.W + fs) * p.C + cc) * 2 : 0;     // bytes, relative to the window origin
+    const int tap = col_ok ? col / p.run : 0, cc = col_ok ? col % p.run : 0;
+    const int fr = tap / p.TS, fs = tap % p.TS;
+    const int tap_off = col_ok ? ((fr * p.W + fs) * p.pix + cc) * 2 : 0;   // bytes, relative to the window origin
     // window origin (p*stride-pad, q*stride-pad) of each row, its byte offset, and (n,p,q) to advance it
     int b_n[B_LD], b_p[B_LD], b_q[B_LD], b_m[B_LD];
 #pragma unroll
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
             const s16x2 hw = __builtin_bit_cast(s16x2, (h0 & 0xFFFF) | (w0 << 16)) + __builtin_bit_cast(s16x2, tap_hw);
             const s16x2 d = __builtin_bit_cast(s16x2, lim_hw) - hw;
             const int bad = (__builtin_bit_cast(int, hw) | __builtin_bit_cast(int, d)) & (int)0x80008000;
-            const int org = ((b_n[i] * p.H + h0 - p.pad) * p.W + (w0 - p.pad)) * (p.C * 2);
+            const int org = ((b_n[i] * p.H + h0 - p.pad) * p.W + (w0 - p.pad)) * (p.pix * 2);
             vb[i] = (bad == 0 && b_m[i] < m_end && col_ok) ? (unsigned)(org + tap_off) : OOB;
             // advance by BP pixels
             b_m[i] += BP;
@@ -293,14 +295,21 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
         }
 }
 
-// dw[i] = partial[0][i] + partial[1][i] + ... (ascending split order)
+// dw[k][r][s][c] = sum over splits (ascending order) of partial[z][k][r*col_r + s*col_s + c].
+// For plain NHWC operands (col_r = S*C, col_s = C) source and destination indices coincide; the
+// re-packed operands of odd channel counts have wider columns that are dropped here.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ partial, float *__restrict__ dw,
-                                                           int total, int splits)
+                                                           int total, int splits, int ncols, int RSC, int SC, int C,
+                                                           int col_r, int col_s, size_t split_stride)
 {
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
-    float acc = partial[gid];
-    for (int zz = 1; zz < splits; ++zz) acc += partial[(size_t)zz * total + gid];
+    const int k = gid / RSC, rem = gid % RSC;
+    const int r = rem / SC, rem2 = rem % SC;
+    const int sidx = rem2 / C, c = rem2 % C;
+    const size_t src = (size_t)k * ncols + r * col_r + sidx * col_s + c;
+    float acc = partial[src];
+    for (int zz = 1; zz < splits; ++zz) acc += partial[(size_t)zz * split_stride + src];
     dw[gid] = acc;
 }
 
@@ -340,35 +349,38 @@ int launch_choice(int idx, const WgradParams &p, int tiles, hipStream_t st)
 struct Plan { int tile, k_tiles, n_tiles, splits, span; };
 
 // Tile and split choice.  MXC_FORCE_WGRAD=<name> (tuning sweeps only) overrides the tile.
-Plan make_plan(const ConvShape &s)
+Plan make_plan(const WgradGeom &g)
 {
-    const int RSC = s.R * s.S * s.C;
-    const long long M = (long long)s.N * s.P * s.Q;
+    const int RSC = g.TR * g.TS * g.run;
+    const long long M = (long long)g.N * g.P * g.Q;
     int t = 0;
-    if (s.K <= 64 && RSC <= 64) t = 4;
-    else if (s.K <= 64) t = 5;
+    if (g.K <= 64 && RSC <= 64) t = 4;
+    else if (g.K <= 64) t = 5;
     else if (RSC <= 64) t = 6;
     if (const char *f = getenv("MXC_FORCE_WGRAD"))
         for (int i = 0; i < N_TILES; ++i)
             if (!strcmp(f, kTiles[i].name)) t = i;
     Plan pl;
     pl.tile = t;
-    pl.k_tiles = (s.K + kTiles[t].bm - 1) / kTiles[t].bm;
+    pl.k_tiles = (g.K + kTiles[t].bm - 1) / kTiles[t].bm;
     pl.n_tiles = (RSC + kTiles[t].bn - 1) / kTiles[t].bn;
     const long long tiles = (long long)pl.k_tiles * pl.n_tiles;
-    // Splits: fill whole rounds of the chip's workgroup slots (256 CUs x slots per CU) as evenly as
-    // possible, with a small penalty per split for the partial-tile traffic, and at least 8 stages
-    // of work per split.
+    // Splits: minimise a simple time model - rounds over the chip's workgroup slots (256 CUs x slots
+    // per CU) times the stages each split walks, plus the traffic of writing and re-reading one fp32
+    // partial tensor per split.
     const long long slots = 256LL * kTiles[t].slots;
-    long long max_splits = (M + 8LL * kTiles[t].bp - 1) / (8LL * kTiles[t].bp);
-    if (max_splits > 256) max_splits = 256;
+    const double stage_us = 2.0 * kTiles[t].bm * kTiles[t].bn * kTiles[t].bp * kTiles[t].slots / (2.5e15 / 256 * 0.5) * 1e6;
+    const double split_us = (double)g.K * RSC * 8.0 / 3e12 * 1e6;
+    long long max_splits = (M + 2LL * kTiles[t].bp - 1) / (2LL * kTiles[t].bp);
+    if (max_splits > 1024) max_splits = 1024;
     if (max_splits < 1) max_splits = 1;
     long long splits = 1;
-    double best = -1.0;
+    double best = 1e300;
     for (long long sp = 1; sp <= max_splits; ++sp) {
         const long long wgs = tiles * sp, rounds = (wgs + slots - 1) / slots;
-        const double score = (double)wgs / (double)(rounds * slots) - 0.004 * (double)sp;
-        if (score > best) { best = score; splits = sp; }
+        const long long stages = ((M + sp - 1) / sp + kTiles[t].bp - 1) / kTiles[t].bp;
+        const double t_us = (double)rounds * (double)stages * stage_us + (double)sp * split_us;
+        if (t_us < best) { best = t_us; splits = sp; }
     }
     long long span = (M + splits - 1) / splits;
     span = (span + kTiles[t].bp - 1) / kTiles[t].bp * kTiles[t].bp;
@@ -379,46 +391,64 @@ Plan make_plan(const ConvShape &s)
 
 }  // namespace
 
-bool wgrad_supported(const ConvShape &s)
+WgradGeom wgrad_geom_plain(const ConvShape &s)
 {
-    const long long M = (long long)s.N * s.P * s.Q;
-    return s.C % 8 == 0 && s.K % 8 == 0 && M < 0x7FFF0000ll && (long long)s.N * s.H * s.W * s.C * 2 < 0x7FFF0000ll &&
-           M * s.K * 2 < 0x7FFF0000ll && s.H + s.R + s.pad <= 8192 && s.W + s.S + s.pad <= 8192 &&
-           (long long)s.P * s.stride <= 8192 && (long long)s.Q * s.stride <= 8192 &&
-           (long long)s.K * s.R * s.S * s.C < 0x7FFFFFFFll;
+    return WgradGeom{s.N, s.H, s.W, s.C, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, s.C, s.R, s.S, s.C, s.S * s.C, s.C};
 }
 
-size_t wgrad_workspace(const ConvShape &s)
+WgradGeom wgrad_geom_chanpad(const ConvShape &s)
 {
-    return (size_t)make_plan(s).splits * s.K * s.R * s.S * s.C * sizeof(float);
+    const int C8 = (s.C + 7) / 8 * 8;
+    return WgradGeom{s.N, s.H, s.W, C8, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, C8, s.R, s.S, s.C, s.S * C8, C8};
 }
 
-int wgrad(const ConvShape &s, const void *x, const void *dy, float *dw, float *partial, hipStream_t st,
+WgradGeom wgrad_geom_smallc(const ConvShape &s)
+{
+    const SmallCGeom g = smallc_geom(s);
+    return WgradGeom{s.N, g.Hp, g.Wp, g.pix, s.K, s.P, s.Q, s.stride, 0, s.R, 1, g.run, s.R, s.S, s.C, g.run, g.pix};
+}
+
+bool wgrad_supported(const WgradGeom &g)
+{
+    const long long M = (long long)g.N * g.P * g.Q;
+    return g.pix % 4 == 0 && g.run % 8 == 0 && g.K % 8 == 0 && M < 0x7FFF0000ll &&
+           (long long)g.N * g.H * g.W * g.pix * 2 < 0x7FFF0000ll && M * g.K * 2 < 0x7FFF0000ll && g.H + g.TR + g.pad <= 8192 &&
+           g.W + g.TS + g.pad <= 8192 && (long long)g.P * g.stride <= 8192 && (long long)g.Q * g.stride <= 8192 &&
+           (long long)g.K * g.TR * g.TS * g.run < 0x7FFFFFFFll;
+}
+
+size_t wgrad_workspace(const WgradGeom &g)
+{
+    return (size_t)make_plan(g).splits * g.K * g.TR * g.TS * g.run * sizeof(float);
+}
+
+int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *partial, hipStream_t st,
           const char **variant)
 {
-    const Plan pl = make_plan(s);
+    const Plan pl = make_plan(g);
     const WgradTile &tc = kTiles[pl.tile];
     WgradParams p{};
     p.x = (const bf16_t *)x; p.dy = (const bf16_t *)dy; p.partial = partial;
-    p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.R = s.R; p.S = s.S;
-    p.stride = s.stride; p.pad = s.pad; p.P = s.P; p.Q = s.Q;
+    p.N = g.N; p.H = g.H; p.W = g.W; p.pix = g.pix; p.K = g.K; p.P = g.P; p.Q = g.Q;
+    p.stride = g.stride; p.pad = g.pad;
+    p.TS = g.TS; p.run = g.run; p.ncols = g.TR * g.TS * g.run;
     p.n_tiles = pl.n_tiles;
     p.splits = pl.splits;
     p.span = pl.span;
-    p.M = s.N * s.P * s.Q;
-    p.dq = tc.bp % s.Q;
-    const int rows = tc.bp / s.Q;
-    p.dp = rows % s.P;
-    p.dn = rows / s.P;
-    p.x_bytes = (unsigned)((long long)s.N * s.H * s.W * s.C * 2);
-    p.dy_bytes = (unsigned)((long long)p.M * s.K * 2);
+    p.M = g.N * g.P * g.Q;
+    p.dq = tc.bp % g.Q;
+    const int rows = tc.bp / g.Q;
+    p.dp = rows % g.P;
+    p.dn = rows / g.P;
+    p.x_bytes = (unsigned)((long long)g.N * g.H * g.W * g.pix * 2);
+    p.dy_bytes = (unsigned)((long long)p.M * g.K * 2);
     const long long tiles = (long long)pl.k_tiles * pl.n_tiles;
     if (tiles > 0x7FFFFFFFll || p.splits > 65535) return MXC_ERR_SHAPE;
     const int rc = launch_choice(pl.tile, p, (int)tiles, st);
     if (rc != MXC_OK) return rc;
-    const int total = s.K * s.R * s.S * s.C;
+    const int total = g.K * g.R * g.S * g.C;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, dw, total,
-                       p.splits);
+                       p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, (size_t)g.K * p.ncols);
     *variant = tc.name;
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
