@@ -108,6 +108,16 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
 int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, Carver &ws, hipStream_t st,
                   bool dry)
 {
+    if (dtype == MXC_BF16 && igemm_bwd_data_smallc_supported(s)) {
+        size_t w2_bytes, dx4_bytes;
+        igemm_bwd_data_smallc_workspace(s, &w2_bytes, &dx4_bytes);
+        void *w2 = ws.take(w2_bytes), *dx4 = ws.take(dx4_bytes);
+        if (dry) return MXC_OK;
+        const char *v = "";
+        const int rc = igemm_bwd_data_smallc(s, dy, w, dx, w2, dx4, st, &v);
+        set_variant("bwd_data", (std::string("smallc+") + v).c_str());
+        return rc;
+    }
     if (dtype == MXC_BF16 && igemm_bwd_data_supported(s)) {
         void *wt = ws.take(igemm_bwd_data_workspace(s));
         if (dry) return MXC_OK;

@@ -40,10 +40,10 @@ struct IgemmParams {
     int Ci;              // reduction elements per tap: a contiguous run starting at the tap's pixel
     int pix;             // elements per pixel in memory (== Ci for plain NHWC; smaller when a run spans pixels)
     int Co;
-    int TR, TS, tstep;   // tap grid and direction (+1 or -1)
+    int TR, TS, tstep_h, tstep_w;   // tap grid and the direction (+1 or -1) taps advance in, per axis
     int Mh, Mw;          // output grid of this launch (per image)
-    int in_mul, in_off_h, in_off_w;     // input coordinate of tap 0: a*in_mul + in_off
-    int Ho, Wo, out_mul, out_off_h, out_off_w;  // output coordinate: a*out_mul + out_off
+    int in_mul_h, in_mul_w, in_off_h, in_off_w;     // input coordinate of tap 0: a*in_mul + in_off
+    int Ho, Wo, out_mul_h, out_mul_w, out_off_h, out_off_w;  // output coordinate: a*out_mul + out_off
     int linear_out;      // output pixel index == m (forward, and stride-1 backward-data)
     int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
     int m_tiles, n_tiles;
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
     for (int t = tid; t <= T; t += NT) {
         int2 e;
         if (t < T) {
-            const int dh = (t / p.TS) * p.tstep, dv = (t % p.TS) * p.tstep;
+            const int dh = (t / p.TS) * p.tstep_h, dv = (t % p.TS) * p.tstep_w;
             e.x = ((dh * p.Wi + dv) * p.pix) * 2;
             e.y = (dh & 0xFFFF) | (dv << 16);
         } else {
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
         if (m < p.M) {
             const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
             const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
-            const int h = (int)a * p.in_mul + p.in_off_h, w = (int)b * p.in_mul + p.in_off_w;
+            const int h = (int)a * p.in_mul_h + p.in_off_h, w = (int)b * p.in_mul_w + p.in_off_w;
             a_off[i] = (int)((((long long)n * p.Hi + h) * p.Wi + w) * p.pix * 2);
             a_hw[i] = (h & 0xFFFF) | (w << 16);
         } else {
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
         if (p.linear_out) return m;
         const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
         const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
-        return ((long long)n * p.Ho + ((int)a * p.out_mul + p.out_off_h)) * p.Wo + ((int)b * p.out_mul + p.out_off_w);
+        return ((long long)n * p.Ho + ((int)a * p.out_mul_h + p.out_off_h)) * p.Wo + ((int)b * p.out_mul_w + p.out_off_w);
     };
     if ((p.Co & 7) == 0) {
         // Through LDS, one 32-row block of the wave tile at a time, so that global stores are 16 bytes
@@ -381,7 +381,7 @@ int launch(IgemmParams p, hipStream_t st)
     p.m_tiles = (int)mt;
     p.in_bytes = (unsigned)((long long)p.N * p.Hi * p.Wi * p.pix * 2);
     p.wm_bytes = (unsigned)((long long)p.Co * p.TR * p.TS * p.Ci * 2);
-    p.linear_out = (p.out_mul == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
+    p.linear_out = (p.out_mul_h == 1 && p.out_mul_w == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
     const int total = p.m_tiles * p.n_tiles;
     const int grid = ((total + 7) / 8) * 8;
     hipLaunchKernelGGL((igemm_kernel<BM, BN, BKT, NS, WR, WC>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
@@ -492,10 +492,10 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
     IgemmParams p{};
     p.in = (const bf16_t *)x; p.wm = (const bf16_t *)w; p.out = (bf16_t *)y;
     p.N = s.N; p.Hi = s.H; p.Wi = s.W; p.Ci = s.C; p.pix = s.C; p.Co = s.K;
-    p.TR = s.R; p.TS = s.S; p.tstep = 1;
+    p.TR = s.R; p.TS = s.S; p.tstep_h = 1; p.tstep_w = 1;
     p.Mh = s.P; p.Mw = s.Q;
-    p.in_mul = s.stride; p.in_off_h = -s.pad; p.in_off_w = -s.pad;
-    p.Ho = s.P; p.Wo = s.Q; p.out_mul = 1; p.out_off_h = 0; p.out_off_w = 0;
+    p.in_mul_h = s.stride; p.in_mul_w = s.stride; p.in_off_h = -s.pad; p.in_off_w = -s.pad;
+    p.Ho = s.P; p.Wo = s.Q; p.out_mul_h = 1; p.out_mul_w = 1; p.out_off_h = 0; p.out_off_w = 0;
     const int tc = choose_tile((long long)s.N * s.P * s.Q, s.K, s.R * s.S * s.C);
     *variant = kTiles[tc].name;
     return launch_choice(tc, p, st);
@@ -516,10 +516,10 @@ int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y
     IgemmParams p{};
     p.in = (const bf16_t *)xp; p.wm = (const bf16_t *)wp; p.out = (bf16_t *)y;
     p.N = s.N; p.Hi = g.Hp; p.Wi = g.Wp; p.Ci = g.run; p.pix = g.pix; p.Co = s.K;
-    p.TR = s.R; p.TS = 1; p.tstep = 1;
+    p.TR = s.R; p.TS = 1; p.tstep_h = 1; p.tstep_w = 1;
     p.Mh = s.P; p.Mw = s.Q;
-    p.in_mul = s.stride; p.in_off_h = 0; p.in_off_w = 0;
-    p.Ho = s.P; p.Wo = s.Q; p.out_mul = 1; p.out_off_h = 0; p.out_off_w = 0;
+    p.in_mul_h = s.stride; p.in_mul_w = s.stride; p.in_off_h = 0; p.in_off_w = 0;
+    p.Ho = s.P; p.Wo = s.Q; p.out_mul_h = 1; p.out_mul_w = 1; p.out_off_h = 0; p.out_off_w = 0;
     const int tc = choose_tile((long long)s.N * s.P * s.Q, s.K, s.R * g.run);
     *variant = kTiles[tc].name;
     return launch_choice(tc, p, st);
@@ -556,10 +556,10 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
             IgemmParams p{};
             p.in = (const bf16_t *)dy; p.wm = (const bf16_t *)wt + wt_off; p.out = (bf16_t *)dx;
             p.N = s.N; p.Hi = s.P; p.Wi = s.Q; p.Ci = s.K; p.pix = s.K; p.Co = s.C;
-            p.TR = TR; p.TS = TS; p.tstep = -1;
+            p.TR = TR; p.TS = TS; p.tstep_h = -1; p.tstep_w = -1;
             p.Mh = Mh; p.Mw = Mw;
-            p.in_mul = 1; p.in_off_h = hh0; p.in_off_w = vv0;
-            p.Ho = s.H; p.Wo = s.W; p.out_mul = s.stride; p.out_off_h = h_first; p.out_off_w = v_first;
+            p.in_mul_h = 1; p.in_mul_w = 1; p.in_off_h = hh0; p.in_off_w = vv0;
+            p.Ho = s.H; p.Wo = s.W; p.out_mul_h = s.stride; p.out_mul_w = s.stride; p.out_off_h = h_first; p.out_off_w = v_first;
             wt_off += (size_t)s.C * TR * TS * s.K;
             if (Mh <= 0 || Mw <= 0) continue;
             tc = choose_tile((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
@@ -569,6 +569,133 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
     }
     *variant = kTiles[tc].name;
     return MXC_OK;
+}
+
+// ---- backward-data for small C (first layers) ------------------------------------------------
+// With C <= 4 output channels the GEMM's N dimension would be almost empty.  Instead G consecutive
+// output columns form one GEMM row: N' = G*4 (channels padded to 4), and the reduction runs over the
+// U columns of dy that reach any of the G pixels.  Per residue class ph of (h+pad) mod stride:
+//     dx4[n][h][b*G+g][c] = sum_{j,u,k} dy[n][hh-j][b*G/stride + uoff + u][k] * W2[(g,c)][(j,u,k)]
+//     W2[(g,c)][(j,u,k)]  = w[k][ph+stride*j][s][c],  s = g + pad - stride*(u + uoff), zero if s outside [0,S)
+// dx4 is then compacted to the caller's C channels.
+
+namespace {
+
+struct SmallCBwd { int G, U, uoff, Wg; };
+
+SmallCBwd smallc_bwd_geom(const ConvShape &s)
+{
+    SmallCBwd g;
+    g.G = 8;
+    // floor((pad - S + 1) / stride)
+    const int num = s.pad - s.S + 1;
+    g.uoff = num >= 0 ? num / s.stride : -((-num + s.stride - 1) / s.stride);
+    g.U = (g.G - 1 + s.pad) / s.stride - g.uoff + 1;
+    g.Wg = (s.W + g.G - 1) / g.G;
+    return g;
+}
+
+// all residue classes one after another; class ph holds [G*4][TR_ph*U*K]
+__global__ __launch_bounds__(256) void smallc_bwd_pack_w_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ w2, int K,
+                                                               int C, int R, int S, int stride, int pad, int G, int U,
+                                                               int uoff)
+{
+    const int rows = G * 4;
+    int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    int ph = 0, TRp = 0;
+    for (; ph < stride; ++ph) {
+        TRp = ph < R ? (R - ph + stride - 1) / stride : 0;
+        const int sz = rows * TRp * U * K;
+        if (gid < sz) break;
+        gid -= sz;
+    }
+    if (ph == stride) return;
+    const int k = gid % K; int t = gid / K;
+    const int u = t % U; t /= U;
+    const int j = t % TRp; t /= TRp;
+    const int c = t & 3, g = t >> 2;
+    const int r = ph + stride * j;
+    const int sidx = g + pad - stride * (u + uoff);
+    bf16_t v = 0;
+    if (c < C && sidx >= 0 && sidx < S) v = w[(((size_t)k * R + r) * S + sidx) * C + c];
+    const size_t phase_base = (size_t)(blockIdx.x * blockDim.x + threadIdx.x) - gid;
+    w2[phase_base + gid] = v;
+}
+
+// dx[n][h][w][c] = dx4[n][h][w][c], c < C; dx4 rows are Wg*G pixels wide
+__global__ __launch_bounds__(256) void smallc_compact_kernel(const uint2 *__restrict__ dx4, bf16_t *__restrict__ dx, long long rows,
+                                                            int W, int W4, int C)
+{
+    const long long total = rows * W;
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const long long row = gid / W;
+    const int wv = (int)(gid % W);
+    const uint2 v = dx4[row * W4 + wv];
+    bf16_t *d = dx + gid * C;
+    d[0] = (bf16_t)(v.x & 0xFFFF);
+    if (C > 1) d[1] = (bf16_t)(v.x >> 16);
+    if (C > 2) d[2] = (bf16_t)(v.y & 0xFFFF);
+    if (C > 3) d[3] = (bf16_t)(v.y >> 16);
+}
+
+}  // namespace
+
+bool igemm_bwd_data_smallc_supported(const ConvShape &s)
+{
+    const SmallCBwd g = smallc_bwd_geom(s);
+    return s.C <= 4 && s.K % 8 == 0 && (s.stride == 1 || s.stride == 2 || s.stride == 4) &&
+           igemm_dims_ok((long long)s.N * s.P * s.Q * s.K, (long long)g.G * 4 * s.R * g.U * s.K, (long long)s.N * s.H * g.Wg, s.P,
+                         s.Q, s.pad + s.R + s.S + s.stride + g.U, s.R * g.U) &&
+           (long long)s.N * s.H * g.Wg * g.G * 4 * 2 < 0x7FFF0000ll;
+}
+
+void igemm_bwd_data_smallc_workspace(const ConvShape &s, size_t *w2_bytes, size_t *dx4_bytes)
+{
+    const SmallCBwd g = smallc_bwd_geom(s);
+    size_t taps = 0;
+    for (int ph = 0; ph < s.stride; ++ph) taps += ph < s.R ? (s.R - ph + s.stride - 1) / s.stride : 0;
+    *w2_bytes = (size_t)g.G * 4 * taps * g.U * s.K * 2;
+    *dx4_bytes = (size_t)s.N * s.H * g.Wg * g.G * 4 * 2;
+}
+
+int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, void *dx, void *w2, void *dx4, hipStream_t st,
+                          const char **variant)
+{
+    const SmallCBwd g = smallc_bwd_geom(s);
+    size_t w2_bytes, dx4_bytes;
+    igemm_bwd_data_smallc_workspace(s, &w2_bytes, &dx4_bytes);
+    const int total = (int)(w2_bytes / 2);
+    hipLaunchKernelGGL(smallc_bwd_pack_w_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t *)w,
+                       (bf16_t *)w2, s.K, s.C, s.R, s.S, s.stride, s.pad, g.G, g.U, g.uoff);
+    if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
+    size_t w2_off = 0;
+    int tc = 0;
+    for (int ph = 0; ph < s.stride; ++ph) {
+        const int TR = ph < s.R ? (s.R - ph + s.stride - 1) / s.stride : 0;
+        const int hh0 = ph >= s.pad ? 0 : (s.pad - ph + s.stride - 1) / s.stride;
+        const int h_first = ph - s.pad + s.stride * hh0;
+        const int Mh = h_first < s.H ? (s.H - 1 - h_first) / s.stride + 1 : 0;
+        IgemmParams p{};
+        p.in = (const bf16_t *)dy; p.wm = (const bf16_t *)w2 + w2_off; p.out = (bf16_t *)dx4;
+        p.N = s.N; p.Hi = s.P; p.Wi = s.Q; p.Ci = s.K; p.pix = s.K; p.Co = g.G * 4;
+        p.TR = TR; p.TS = g.U; p.tstep_h = -1; p.tstep_w = 1;
+        p.Mh = Mh; p.Mw = g.Wg;
+        p.in_mul_h = 1; p.in_mul_w = g.G / s.stride; p.in_off_h = hh0; p.in_off_w = g.uoff;
+        p.Ho = s.H; p.Wo = g.Wg; p.out_mul_h = s.stride; p.out_mul_w = 1; p.out_off_h = h_first; p.out_off_w = 0;
+        w2_off += (size_t)g.G * 4 * TR * g.U * s.K;
+        if (Mh <= 0) continue;
+        tc = choose_tile((long long)s.N * Mh * g.Wg, p.Co, TR * g.U * s.K);
+        const int rc = launch_choice(tc, p, st);
+        if (rc != MXC_OK) return rc;
+    }
+    const long long rows = (long long)s.N * s.H;
+    const long long blocks = (rows * s.W + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+    hipLaunchKernelGGL(smallc_compact_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint2 *)dx4, (bf16_t *)dx, rows,
+                       s.W, g.Wg * g.G, s.C);
+    *variant = kTiles[tc].name;
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
 
 }  // namespace mxc

@@ -56,6 +56,12 @@ size_t igemm_bwd_data_workspace(const ConvShape &s);   // bytes for the re-packe
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
                    const char **variant);
 
+// backward-data for C <= 4: G output columns form one GEMM row (see igemm.hip)
+bool igemm_bwd_data_smallc_supported(const ConvShape &s);
+void igemm_bwd_data_smallc_workspace(const ConvShape &s, size_t *w2_bytes, size_t *dx4_bytes);
+int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, void *dx, void *w2, void *dx4, hipStream_t st,
+                          const char **variant);
+
 // ---- prep.hip: re-packing for channel counts that are not a multiple of 8 ---------
 // [rows][C] -> [rows][C8] (C8 = C rounded up to 8, new channels zero); bf16 only.
 int pad_channels(const void *src, void *dst, long long rows, int C, hipStream_t st);

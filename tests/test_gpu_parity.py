@@ -78,6 +78,12 @@ SWEEP = [
     (1, 136, 6, 5, 264, 3, 3, 1, 1),    # C, K beyond one tile with ragged tails
     (5, 32, 17, 17, 48, 3, 3, 2, 0),
     (1, 8, 40, 3, 8, 3, 3, 1, 1),       # tall and narrow
+    (2, 3, 13, 11, 16, 3, 3, 1, 1),     # small-C paths: stride 1, W not a multiple of the column group
+    (1, 2, 12, 15, 8, 5, 5, 2, 2),      # small-C, stride 2
+    (2, 4, 9, 9, 8, 3, 3, 1, 0),        # C == 4, no padding
+    (1, 3, 20, 20, 16, 7, 7, 2, 3),
+    (1, 12, 9, 9, 16, 3, 3, 1, 1),      # C % 8 != 0, C > 4: channel-padded path
+    (2, 20, 7, 8, 24, 3, 3, 2, 1),
 ]
 
 
