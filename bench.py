@@ -132,20 +132,27 @@ def time_calls(torch, net, steps):
     return out
 
 
+def kernel_of(variant):
+    """'fwd:smallc+igemm_128x64_k64s2_w4' -> 'igemm_128x64_k64s2_w4' (the main kernel of the call)."""
+    return variant.split(":")[-1].split("+")[-1]
+
+
 def roofline_of(per_call, net):
-    """Roofline entry of the kernel variant that takes the most time in a step."""
-    by_variant = {}
+    """Roofline entry of the kernel that takes the most time in a step.  Its launches are timed with HIP
+    events around the ABI call; only calls that are exactly one launch of that kernel (plain forward
+    calls) enter the figure, so that the event time is the kernel's duration (plus the launch gap)."""
+    by_kernel = {}
     for c in per_call:
-        by_variant.setdefault(c["variant"], []).append(c)
-    dominant = max(by_variant, key=lambda v: sum(c["ms"] for c in by_variant[v]))
-    group = by_variant[dominant]
+        by_kernel.setdefault(kernel_of(c["variant"]), []).append(c)
+    dominant = max(by_kernel, key=lambda v: sum(c["ms"] for c in by_kernel[v]))
+    group = [c for c in by_kernel[dominant] if c["op"] == "fwd" and "+" not in c["variant"]] or by_kernel[dominant]
     t = sum(c["ms"] for c in group) * 1e-3
     flops = sum(c["state"].L.flops_per_pass for c in group if c["op"] != "layout")
     nbytes = sum(algorithmic_bytes(c["state"].L, c["op"], net.esize) for c in group if c["op"] != "layout")
     peak_tf = PEAK_BF16_TFLOPS if net.cfg.dtype == "bf16" else PEAK_F32_TFLOPS
     t_mfma, t_hbm = flops / (peak_tf * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
     if t_mfma >= t_hbm:
-        bound = "mfma" if net.cfg.dtype == "bf16" or "mfma" in dominant else "alu"
+        bound = "mfma" if net.cfg.dtype == "bf16" else "alu"
         ach = flops / t / 1e12
         r = {"bound": bound, "achieved": round(ach, 2), "peak": peak_tf, "unit": "TFLOP/s", "frac": round(ach / peak_tf, 4)}
     else:
@@ -153,8 +160,10 @@ def roofline_of(per_call, net):
         r = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
              "frac": round(ach / PEAK_HBM_GBS, 4)}
     r["kernel"] = dominant
-    r["launches_per_step"] = len(group)
+    r["launches"] = [c["layer"] + ":" + c["op"] for c in group]
     r["avg_launch_ms"] = round(t * 1e3 / len(group), 4)
+    r["algorithmic_flops_per_launch"] = flops // len(group)
+    r["algorithmic_bytes_per_launch"] = nbytes // len(group)
     r["traffic"] = load_traffic(net.cfg.name, dominant)
     return r
 
@@ -195,7 +204,10 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other layer stacks (extra 'networks' field)")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    ap.add_argument("--cpu-sample-batch", type=int, default=128)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (mxc_layout_convert, same layout) so that a counter run "
+                         "can scale FETCH_SIZE / WRITE_SIZE against a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by contract (one MI355X, no collectives); run with --gpus 1",
@@ -213,6 +225,13 @@ def main():
         per_call = time_calls(torch, net, steps)
         return net, sec, per_call
 
+    if args.calibrate_copy:
+        n_el = 1 << 28                      # 2^28 fp32 = 1 GiB read + 1 GiB written
+        src = torch.ones(n_el, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        mxc.mxc_layout_convert(1, 1, 1 << 14, 1 << 14, mxc.MXC_F32, mxc.MXC_NCHW, mxc.MXC_NCHW, src, dst)
+        torch.cuda.synchronize()
+        del src, dst
     cfg = gen.config_by_name(args.workload)
     net, sec, per_call = run_one(cfg, args.steps, args.warmup)
     value = net.flops_per_step / sec / 1e12

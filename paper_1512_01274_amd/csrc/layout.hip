@@ -35,6 +35,20 @@ __global__ __launch_bounds__(256) void transpose_tile_kernel(const T *__restrict
     }
 }
 
+// Few channels (c <= 8): one thread per pixel.  planar[b][c][pixels] <-> interleaved[b][pixels][c];
+// both sides are contiguous across the lanes of a wave.
+template <typename T, bool TO_INTERLEAVED>
+__global__ __launch_bounds__(256) void small_c_kernel(const T *__restrict__ src, T *__restrict__ dst, int c, long long pixels)
+{
+    const long long pix = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pix >= pixels) return;
+    const size_t base = (size_t)blockIdx.y * c * pixels;
+    for (int ch = 0; ch < c; ++ch) {
+        if (TO_INTERLEAVED) dst[base + (size_t)pix * c + ch] = src[base + (size_t)ch * pixels + pix];
+        else dst[base + (size_t)ch * pixels + pix] = src[base + (size_t)pix * c + ch];
+    }
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16,
                                                    const unsigned char *__restrict__ tail_src,
                                                    unsigned char *__restrict__ tail_dst, int tail)
@@ -49,6 +63,20 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src
 int launch_transpose(const void *src, void *dst, int batch, int rows, int cols, int elem_bytes, hipStream_t stream)
 {
     if (batch <= 0 || rows <= 0 || cols <= 0) return MXC_ERR_SHAPE;
+    if ((rows <= 8 || cols <= 8) && batch <= 65535 && (elem_bytes == 2 || elem_bytes == 4)) {
+        const bool to_inter = rows <= 8;           // [c][pixels] -> [pixels][c]
+        const int c = to_inter ? rows : cols;
+        const long long pixels = to_inter ? cols : rows;
+        dim3 grid((unsigned)((pixels + 255) / 256), (unsigned)batch), block(256);
+        if (elem_bytes == 2) {
+            if (to_inter) hipLaunchKernelGGL((small_c_kernel<uint16_t, true>), grid, block, 0, stream, (const uint16_t *)src, (uint16_t *)dst, c, pixels);
+            else hipLaunchKernelGGL((small_c_kernel<uint16_t, false>), grid, block, 0, stream, (const uint16_t *)src, (uint16_t *)dst, c, pixels);
+        } else {
+            if (to_inter) hipLaunchKernelGGL((small_c_kernel<uint32_t, true>), grid, block, 0, stream, (const uint32_t *)src, (uint32_t *)dst, c, pixels);
+            else hipLaunchKernelGGL((small_c_kernel<uint32_t, false>), grid, block, 0, stream, (const uint32_t *)src, (uint32_t *)dst, c, pixels);
+        }
+        return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+    }
     const unsigned gx = (unsigned)((cols + TILE - 1) / TILE), gy = (unsigned)((rows + TILE - 1) / TILE);
     if (gy > 65535u || (unsigned)batch > 65535u) return MXC_ERR_SHAPE;
     dim3 grid(gx, gy, (unsigned)batch), block(256);
