@@ -78,6 +78,17 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
         set_variant("fwd", v);
         return rc;
     }
+    if (dtype == MXC_BF16 && s2d_applicable(s) && igemm_fwd_supported(s2d_shape(s))) {
+        // strided first layer: space-to-depth turns it into a stride-1 problem with stride^2*C channels
+        const ConvShape s2 = s2d_shape(s);
+        void *x2 = ws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2), *w2 = ws.take((size_t)s2.K * s2.R * s2.S * s2.C * 2);
+        if (dry) return MXC_OK;
+        MXC_TRY(s2d_pack_x(s, x, x2, st));
+        MXC_TRY(s2d_pack_w(s, w, w2, st));
+        const int rc = igemm_fwd(s2, x2, w2, y, st, &v);
+        set_variant("fwd", (std::string("s2d+") + v).c_str());
+        return rc;
+    }
     if (dtype == MXC_BF16 && s.C <= 4 && igemm_fwd_smallc_supported(s)) {
         // first-layer style: zero-bordered image with 4 or 8 channels per pixel, filter rows as runs
         const SmallCGeom g = smallc_geom(s);
@@ -108,6 +119,17 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
 int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, Carver &ws, hipStream_t st,
                   bool dry)
 {
+    if (dtype == MXC_BF16 && s.K % 8 == 0 && s2d_applicable(s) && igemm_bwd_data_supported(s2d_shape(s))) {
+        const ConvShape s2 = s2d_shape(s);
+        void *w2 = ws.take((size_t)s2.K * s2.R * s2.S * s2.C * 2), *wt = ws.take(igemm_bwd_data_workspace(s2));
+        void *dx2 = ws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2);
+        if (dry) return MXC_OK;
+        const char *v = "";
+        MXC_TRY(s2d_pack_w(s, w, w2, st));
+        MXC_TRY(igemm_bwd_data(s2, dy, w2, dx2, wt, st, &v));
+        set_variant("bwd_data", (std::string("s2d+") + v).c_str());
+        return s2d_unpack_dx(s, dx2, dx, st);
+    }
     if (dtype == MXC_BF16 && igemm_bwd_data_smallc_supported(s)) {
         size_t w2_bytes, dx4_bytes;
         igemm_bwd_data_smallc_workspace(s, &w2_bytes, &dx4_bytes);
@@ -141,6 +163,17 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
         if (dry) return MXC_OK;
         const int rc = wgrad(g, x, dy, dw, partial, st, &v);
         set_variant("bwd_weight", v);
+        return rc;
+    }
+    if (dtype == MXC_BF16 && s2d_applicable(s) && wgrad_supported(wgrad_geom_s2d(s))) {
+        const ConvShape s2 = s2d_shape(s);
+        const WgradGeom g = wgrad_geom_s2d(s);
+        void *x2 = ws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2);
+        float *partial = (float *)ws.take(wgrad_workspace(g));
+        if (dry) return MXC_OK;
+        MXC_TRY(s2d_pack_x(s, x, x2, st));
+        const int rc = wgrad(g, x2, dy, dw, partial, st, &v);
+        set_variant("bwd_weight", (std::string("s2d+") + v).c_str());
         return rc;
     }
     if (dtype == MXC_BF16 && s.C <= 4 && wgrad_supported(wgrad_geom_smallc(s))) {

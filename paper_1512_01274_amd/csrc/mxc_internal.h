@@ -71,6 +71,14 @@ struct SmallCGeom { int pix, Hp, Wp, run; };
 SmallCGeom smallc_geom(const ConvShape &s);
 int smallc_pack_x(const ConvShape &s, const void *x, void *xp, hipStream_t st);   // xp: N*Hp*Wp*pix elements
 int smallc_pack_w(const ConvShape &s, const void *w, void *wp, hipStream_t st);   // wp: K*R*run elements
+// Space-to-depth (C <= 4, stride 2 or 4): s x s pixel blocks become channels of a stride-1 problem.
+struct S2DGeom { int s, Cq, C2, R2, S2, H2, W2; };
+S2DGeom s2d_geom(const ConvShape &s);
+bool s2d_applicable(const ConvShape &s);
+ConvShape s2d_shape(const ConvShape &s);      // the equivalent stride-1 problem: x2[N][H2][W2][C2], w2[K][R2][S2][C2]
+int s2d_pack_x(const ConvShape &s, const void *x, void *x2, hipStream_t st);
+int s2d_pack_w(const ConvShape &s, const void *w, void *w2, hipStream_t st);
+int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st);
 bool igemm_fwd_smallc_supported(const ConvShape &s);
 int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y, hipStream_t st, const char **variant);
 
@@ -78,9 +86,12 @@ int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y
 // The problem as the kernel sees it: x[N][H][W][pix], dy[N][P][Q][K]; filter columns are TR*TS taps of
 // `run` contiguous elements each; dw[k][r][s][c] (dense R,S,C) is read back from column
 // r*col_r + s*col_s + c.
+// With s2d > 1 the columns come from a space-to-depth problem: filter tap (r,s) sits in block
+// (r/s2d, s/s2d) at channel ((r%s2d)*s2d + s%s2d)*Cq + c.
 struct WgradGeom {
-    int N, H, W, pix, K, P, Q, stride, pad, TR, TS, run, R, S, C, col_r, col_s;
+    int N, H, W, pix, K, P, Q, stride, pad, TR, TS, run, R, S, C, col_r, col_s, s2d, Cq;
 };
+WgradGeom wgrad_geom_s2d(const ConvShape &s);       // x already packed by s2d_pack_x
 WgradGeom wgrad_geom_plain(const ConvShape &s);     // C % 8 == 0
 WgradGeom wgrad_geom_chanpad(const ConvShape &s);   // x already padded to C8 channels
 WgradGeom wgrad_geom_smallc(const ConvShape &s);    // x already packed by smallc_pack_x

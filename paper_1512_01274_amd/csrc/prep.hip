@@ -4,7 +4,11 @@
 // re-packings make any channel count fit:
 //   - channel padding: [rows][C] -> [rows][C8], C8 = C rounded up to 8, zeros in the new channels
 //     (used when C % 8 != 0 and C > 4);
-//   - small-C image packing (C <= 4, first layers): the image gets `pix` (4 or 8) channels per pixel
+//   - space-to-depth (C <= 4, stride 2 or 4, first layers): stride x stride pixel blocks become the
+//     channels of one pixel of a stride-1 problem, x2[n][h2][w2][(dh*s+dw)*Cq+c] with the zero border
+//     folded in, filter likewise (zero taps beyond R,S); all three passes then run the ordinary
+//     kernels on a stride-1 convolution with s*s*Cq channels;
+//   - small-C image packing (C <= 4, stride 1): the image gets `pix` (4) channels per pixel
 //     and an explicit zero border, so that for one filter row r the taps s = 0..S-1 of all channels
 //     form ONE contiguous run of S*pix elements - the reduction then walks R long runs instead of
 //     R*S*C scattered triples, and no bounds test can fail.  The filter is laid out to match:
@@ -73,6 +77,67 @@ __global__ __launch_bounds__(256) void smallc_pack_w_kernel(const bf16_t *__rest
     wp[gid] = (s < S && c < C) ? w[((size_t)kr * S + s) * C + c] : (bf16_t)0;
 }
 
+// x2[n][h2][w2][(dh*s+dw)*Cq + c] = x[n][h2*s+dh-pad][w2*s+dw-pad][c] (0 outside the image or for c >= C).
+// One thread per 16-byte chunk of x2.
+__global__ __launch_bounds__(256) void s2d_pack_x_kernel(const bf16_t *__restrict__ x, uint4 *__restrict__ x2, int N, int C, int H,
+                                                         int W, int pad, int s, int Cq, int C2, int H2, int W2)
+{
+    const int chunks = C2 >> 3;
+    const long long total = (long long)N * H2 * W2 * chunks;
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int ch0 = (int)(gid % chunks) * 8;
+    long long t = gid / chunks;
+    const int w2 = (int)(t % W2); t /= W2;
+    const int h2 = (int)(t % H2);
+    const int n = (int)(t / H2);
+    uint32_t v[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int e = ch0 + j, blk = e / Cq, c = e % Cq;
+        const int h = h2 * s + blk / s - pad, w = w2 * s + blk % s - pad;
+        uint32_t val = 0;
+        if (c < C && h >= 0 && h < H && w >= 0 && w < W) val = x[(((long long)n * H + h) * W + w) * C + c];
+        v[j >> 1] |= val << ((j & 1) * 16);
+    }
+    x2[gid] = make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// w2[k][r2][s2][(dh*s+dw)*Cq + c] = w[k][r2*s+dh][s2*s+dw][c], zero where r >= R, s >= S or c >= C
+__global__ __launch_bounds__(256) void s2d_pack_w_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ w2, int K, int C, int R,
+                                                         int S, int s, int Cq, int C2, int R2, int S2)
+{
+    const int total = K * R2 * S2 * C2;
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int e = gid % C2; int t = gid / C2;
+    const int sb = t % S2; t /= S2;
+    const int rb = t % R2;
+    const int k = t / R2;
+    const int blk = e / Cq, c = e % Cq;
+    const int r = rb * s + blk / s, sc = sb * s + blk % s;
+    w2[gid] = (c < C && r < R && sc < S) ? w[(((size_t)k * R + r) * S + sc) * C + c] : (bf16_t)0;
+}
+
+// dx[n][h][w][c] = dx2[n][(h+pad)/s][(w+pad)/s][(((h+pad)%s)*s + (w+pad)%s)*Cq + c]; 0 where no window reaches
+__global__ __launch_bounds__(256) void s2d_unpack_dx_kernel(const bf16_t *__restrict__ dx2, bf16_t *__restrict__ dx, int N, int C,
+                                                            int H, int W, int pad, int s, int Cq, int C2, int H2, int W2)
+{
+    const long long total = (long long)N * H * W;
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int w = (int)(gid % W);
+    long long t = gid / W;
+    const int h = (int)(t % H);
+    const int n = (int)(t / H);
+    const int hp = h + pad, wp = w + pad;
+    const int h2 = hp / s, w2 = wp / s;
+    const bool in = h2 < H2 && w2 < W2;
+    const bf16_t *src = dx2 + (((long long)n * H2 + h2) * W2 + w2) * C2 + ((hp % s) * s + wp % s) * Cq;
+    bf16_t *d = dx + gid * C;
+    for (int c = 0; c < C; ++c) d[c] = in ? src[c] : (bf16_t)0;
+}
+
 inline int ok() { return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH; }
 
 }  // namespace
@@ -91,9 +156,8 @@ int pad_channels(const void *src, void *dst, long long rows, int C, hipStream_t 
 SmallCGeom smallc_geom(const ConvShape &s)
 {
     SmallCGeom g;
-    // window origins sit at pixel q*stride of the padded row: 16-byte aligned for every q only if
-    // stride*pix is a multiple of 8
-    g.pix = (s.stride % 2 == 0) ? 4 : 8;
+    // 4 channels per pixel: window origins are 8-byte aligned, which the 16-byte buffer loads accept
+    g.pix = 4;
     g.Hp = s.H + 2 * s.pad;
     g.Wp = (s.W + 2 * s.pad + 1) / 2 * 2;
     g.run = (s.S * g.pix + 7) / 8 * 8;
@@ -117,6 +181,59 @@ int smallc_pack_w(const ConvShape &s, const void *w, void *wp, hipStream_t st)
     const int total = s.K * s.R * g.run;
     hipLaunchKernelGGL(smallc_pack_w_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t *)w,
                        (bf16_t *)wp, s.K, s.C, s.R, s.S, g.pix, g.run);
+    return ok();
+}
+
+S2DGeom s2d_geom(const ConvShape &s)
+{
+    S2DGeom g;
+    g.s = s.stride;
+    g.Cq = s.C;
+    while ((g.s * g.s * g.Cq) % 8 != 0) ++g.Cq;
+    g.C2 = g.s * g.s * g.Cq;
+    g.R2 = (s.R + g.s - 1) / g.s;
+    g.S2 = (s.S + g.s - 1) / g.s;
+    g.H2 = s.P + g.R2 - 1;
+    g.W2 = s.Q + g.S2 - 1;
+    return g;
+}
+
+bool s2d_applicable(const ConvShape &s) { return s.C <= 4 && (s.stride == 2 || s.stride == 4); }
+
+ConvShape s2d_shape(const ConvShape &s)
+{
+    const S2DGeom g = s2d_geom(s);
+    return ConvShape{s.N, g.C2, g.H2, g.W2, s.K, g.R2, g.S2, 1, 0, s.P, s.Q};
+}
+
+int s2d_pack_x(const ConvShape &s, const void *x, void *x2, hipStream_t st)
+{
+    const S2DGeom g = s2d_geom(s);
+    const long long total = (long long)s.N * g.H2 * g.W2 * (g.C2 / 8);
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+    hipLaunchKernelGGL(s2d_pack_x_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)x, (uint4 *)x2, s.N, s.C, s.H,
+                       s.W, s.pad, g.s, g.Cq, g.C2, g.H2, g.W2);
+    return ok();
+}
+
+int s2d_pack_w(const ConvShape &s, const void *w, void *w2, hipStream_t st)
+{
+    const S2DGeom g = s2d_geom(s);
+    const int total = s.K * g.R2 * g.S2 * g.C2;
+    hipLaunchKernelGGL(s2d_pack_w_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t *)w, (bf16_t *)w2,
+                       s.K, s.C, s.R, s.S, g.s, g.Cq, g.C2, g.R2, g.S2);
+    return ok();
+}
+
+int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st)
+{
+    const S2DGeom g = s2d_geom(s);
+    const long long total = (long long)s.N * s.H * s.W;
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+    hipLaunchKernelGGL(s2d_unpack_dx_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)dx2, (bf16_t *)dx, s.N, s.C,
+                       s.H, s.W, s.pad, g.s, g.Cq, g.C2, g.H2, g.W2);
     return ok();
 }
 

@@ -295,19 +295,20 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
         }
 }
 
-// dw[k][r][s][c] = sum over splits (ascending order) of partial[z][k][r*col_r + s*col_s + c].
+// dw[k][r][s][c] = sum over splits (ascending order) of partial[z][k][col], col = (r/d)*col_r + (s/d)*col_s +
+// ((r%d)*d + s%d)*Cq + c with d = s2d (1 for everything but space-to-depth operands, where it is the stride).
 // For plain NHWC operands (col_r = S*C, col_s = C) source and destination indices coincide; the
 // re-packed operands of odd channel counts have wider columns that are dropped here.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ partial, float *__restrict__ dw,
                                                            int total, int splits, int ncols, int RSC, int SC, int C,
-                                                           int col_r, int col_s, size_t split_stride)
+                                                           int col_r, int col_s, int s2d, int Cq, size_t split_stride)
 {
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
     const int k = gid / RSC, rem = gid % RSC;
     const int r = rem / SC, rem2 = rem % SC;
     const int sidx = rem2 / C, c = rem2 % C;
-    const size_t src = (size_t)k * ncols + r * col_r + sidx * col_s + c;
+    const size_t src = (size_t)k * ncols + (r / s2d) * col_r + (sidx / s2d) * col_s + ((r % s2d) * s2d + sidx % s2d) * Cq + c;
     float acc = partial[src];
     for (int zz = 1; zz < splits; ++zz) acc += partial[(size_t)zz * split_stride + src];
     dw[gid] = acc;
@@ -393,19 +394,25 @@ Plan make_plan(const WgradGeom &g)
 
 WgradGeom wgrad_geom_plain(const ConvShape &s)
 {
-    return WgradGeom{s.N, s.H, s.W, s.C, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, s.C, s.R, s.S, s.C, s.S * s.C, s.C};
+    return WgradGeom{s.N, s.H, s.W, s.C, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, s.C, s.R, s.S, s.C, s.S * s.C, s.C, 1, 0};
 }
 
 WgradGeom wgrad_geom_chanpad(const ConvShape &s)
 {
     const int C8 = (s.C + 7) / 8 * 8;
-    return WgradGeom{s.N, s.H, s.W, C8, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, C8, s.R, s.S, s.C, s.S * C8, C8};
+    return WgradGeom{s.N, s.H, s.W, C8, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, C8, s.R, s.S, s.C, s.S * C8, C8, 1, 0};
 }
 
 WgradGeom wgrad_geom_smallc(const ConvShape &s)
 {
     const SmallCGeom g = smallc_geom(s);
-    return WgradGeom{s.N, g.Hp, g.Wp, g.pix, s.K, s.P, s.Q, s.stride, 0, s.R, 1, g.run, s.R, s.S, s.C, g.run, g.pix};
+    return WgradGeom{s.N, g.Hp, g.Wp, g.pix, s.K, s.P, s.Q, s.stride, 0, s.R, 1, g.run, s.R, s.S, s.C, g.run, g.pix, 1, 0};
+}
+
+WgradGeom wgrad_geom_s2d(const ConvShape &s)
+{
+    const S2DGeom g = s2d_geom(s);
+    return WgradGeom{s.N, g.H2, g.W2, g.C2, s.K, s.P, s.Q, 1, 0, g.R2, g.S2, g.C2, s.R, s.S, s.C, g.S2 * g.C2, g.C2, g.s, g.Cq};
 }
 
 bool wgrad_supported(const WgradGeom &g)
@@ -448,7 +455,7 @@ int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *p
     if (rc != MXC_OK) return rc;
     const int total = g.K * g.R * g.S * g.C;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, dw, total,
-                       p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, (size_t)g.K * p.ncols);
+                       p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq, (size_t)g.K * p.ncols);
     *variant = tc.name;
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
