@@ -42,7 +42,7 @@ struct WgradParams {
     int N, H, W, pix;   // x geometry: pix elements per pixel in memory
     int K, P, Q, stride, pad;
     int TS, run, ncols; // filter columns: col = tap*run + e, tap = fr*TS + fs, e = offset in the tap's contiguous run
-    int n_tiles, splits;
+    int n_tiles, splits, tiles, n_wg;
     int span;           // pixels per split (multiple of the stage size)
     int M;              // N*P*Q
     int dq, dp, dn;     // decomposition of a one-stage pixel advance: BP = dq + Q*(dp + P*dn)
@@ -107,7 +107,14 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = (wave / WC) * WM, wave_n = (wave % WC) * WN;
-    const int tile = blockIdx.x, z = blockIdx.y;
+    // Workgroup -> (split z, tile).  Consecutive workgroup ids go round-robin to the 8 XCDs; give each
+    // XCD a contiguous range with the tile index fastest, so the tiles that reduce the same pixel
+    // range (and read the same dy and x rows) share one L2.
+    const int total_wg = p.n_wg;
+    const int per_xcd = (total_wg + 7) / 8;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total_wg) return;
+    const int tile = logical % p.tiles, z = logical / p.tiles;
     const int k0 = (tile / p.n_tiles) * BMT, n0 = (tile % p.n_tiles) * BNT;
     const int RSC = p.ncols;
     const int m_begin = z * p.span;
@@ -314,6 +321,35 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     dw[gid] = acc;
 }
 
+// Same sum for many splits and few outputs: a workgroup of 16 waves owns 64 consecutive outputs; wave v
+// adds the splits v, v+16, v+32, ... (lanes = outputs, so every load is a contiguous 256-byte row) and
+// the 16 wave sums are then added in wave order through LDS.  The order of additions depends only on the
+// split count, so results are reproducible.
+__global__ __launch_bounds__(1024) void wgrad_reduce_wide_kernel(const float *__restrict__ partial, float *__restrict__ dw,
+                                                                 int total, int splits, int ncols, int RSC, int SC, int C,
+                                                                 int col_r, int col_s, int s2d, int Cq, size_t split_stride)
+{
+    __shared__ float part[16][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int gid = blockIdx.x * 64 + lane;
+    float acc = 0.f;
+    if (gid < total) {
+        const int k = gid / RSC, rem = gid % RSC;
+        const int r = rem / SC, rem2 = rem % SC;
+        const int sidx = rem2 / C, c = rem2 % C;
+        const size_t src = (size_t)k * ncols + (r / s2d) * col_r + (sidx / s2d) * col_s + ((r % s2d) * s2d + sidx % s2d) * Cq + c;
+        for (int zz = wave; zz < splits; zz += 16) acc += partial[(size_t)zz * split_stride + src];
+    }
+    part[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && gid < total) {
+        float sum = part[0][lane];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) sum += part[v][lane];
+        dw[gid] = sum;
+    }
+}
+
 struct WgradTile { int bm, bn, bp, slots; const char *name; };   // slots: workgroups that fit one CU
 const WgradTile kTiles[] = {
     {128, 128, 64, 2, "wgrad_128x128_p64s2_w4"},
@@ -329,8 +365,11 @@ constexpr int N_TILES = sizeof(kTiles) / sizeof(kTiles[0]);
 template <int BMT, int BNT, int BP, int NS, int WR, int WC>
 int launch(const WgradParams &p, int tiles, hipStream_t st)
 {
-    hipLaunchKernelGGL((wgrad_kernel<BMT, BNT, BP, NS, WR, WC>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(64 * WR * WC), 0,
-                       st, p);
+    WgradParams q = p;
+    q.tiles = tiles;
+    q.n_wg = tiles * p.splits;
+    const int grid = (q.n_wg + 7) / 8 * 8;
+    hipLaunchKernelGGL((wgrad_kernel<BMT, BNT, BP, NS, WR, WC>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, q);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
 
@@ -450,12 +489,18 @@ int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *p
     p.x_bytes = (unsigned)((long long)g.N * g.H * g.W * g.pix * 2);
     p.dy_bytes = (unsigned)((long long)p.M * g.K * 2);
     const long long tiles = (long long)pl.k_tiles * pl.n_tiles;
-    if (tiles > 0x7FFFFFFFll || p.splits > 65535) return MXC_ERR_SHAPE;
+    if (tiles * p.splits > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
     const int rc = launch_choice(pl.tile, p, (int)tiles, st);
     if (rc != MXC_OK) return rc;
     const int total = g.K * g.R * g.S * g.C;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, dw, total,
-                       p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq, (size_t)g.K * p.ncols);
+    if (p.splits > 16 && (long long)total * 4 < 256LL * 1024 * 4)
+        hipLaunchKernelGGL(wgrad_reduce_wide_kernel, dim3((unsigned)((total + 63) / 64)), dim3(1024), 0, st, partial, dw, total,
+                           p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq,
+                           (size_t)g.K * p.ncols);
+    else
+        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, dw, total,
+                           p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq,
+                           (size_t)g.K * p.ncols);
     *variant = tc.name;
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
