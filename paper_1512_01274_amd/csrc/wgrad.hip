@@ -350,15 +350,16 @@ __global__ __launch_bounds__(1024) void wgrad_reduce_wide_kernel(const float *__
     }
 }
 
-struct WgradTile { int bm, bn, bp, slots; const char *name; };   // slots: workgroups that fit one CU
+// slots: workgroups that fit one CU; util: fraction of the CU's matrix peak the tile sustains (measured)
+struct WgradTile { int bm, bn, bp, slots; float util; const char *name; };
 const WgradTile kTiles[] = {
-    {128, 128, 64, 2, "wgrad_128x128_p64s2_w4"},
-    {256, 256, 32, 1, "wgrad_256x256_p32s4_w8"},
-    {256, 128, 32, 1, "wgrad_256x128_p32s4_w8"},
-    {128, 256, 32, 1, "wgrad_128x256_p32s4_w8"},
-    {64, 64, 64, 4, "wgrad_64x64_p64s2_w4"},
-    {64, 128, 64, 2, "wgrad_64x128_p64s2_w4"},
-    {128, 64, 64, 2, "wgrad_128x64_p64s2_w4"},
+    {128, 128, 64, 2, 0.36f, "wgrad_128x128_p64s2_w4"},
+    {256, 256, 32, 1, 0.47f, "wgrad_256x256_p32s4_w8"},
+    {256, 128, 32, 1, 0.30f, "wgrad_256x128_p32s4_w8"},
+    {128, 256, 32, 1, 0.30f, "wgrad_128x256_p32s4_w8"},
+    {64, 64, 64, 4, 0.12f, "wgrad_64x64_p64s2_w4"},
+    {64, 128, 64, 2, 0.22f, "wgrad_64x128_p64s2_w4"},
+    {128, 64, 64, 2, 0.22f, "wgrad_128x64_p64s2_w4"},
 };
 constexpr int N_TILES = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -388,45 +389,48 @@ int launch_choice(int idx, const WgradParams &p, int tiles, hipStream_t st)
 
 struct Plan { int tile, k_tiles, n_tiles, splits, span; };
 
-// Tile and split choice.  MXC_FORCE_WGRAD=<name> (tuning sweeps only) overrides the tile.
+// Tile and split choice: the pair with the least modelled time - rounds over the chip's workgroup
+// slots (256 CUs x slots per CU) x stages each split walks x time per stage, plus the traffic of
+// writing and re-reading one fp32 partial tensor per split.  MXC_FORCE_WGRAD=<name> (tuning sweeps
+// only) fixes the tile.
 Plan make_plan(const WgradGeom &g)
 {
     const int RSC = g.TR * g.TS * g.run;
     const long long M = (long long)g.N * g.P * g.Q;
-    int t = 0;
-    if (g.K <= 64 && RSC <= 64) t = 4;
-    else if (g.K <= 64) t = 5;
-    else if (RSC <= 64) t = 6;
+    int forced = -1;
     if (const char *f = getenv("MXC_FORCE_WGRAD"))
         for (int i = 0; i < N_TILES; ++i)
-            if (!strcmp(f, kTiles[i].name)) t = i;
-    Plan pl;
-    pl.tile = t;
-    pl.k_tiles = (g.K + kTiles[t].bm - 1) / kTiles[t].bm;
-    pl.n_tiles = (RSC + kTiles[t].bn - 1) / kTiles[t].bn;
-    const long long tiles = (long long)pl.k_tiles * pl.n_tiles;
-    // Splits: minimise a simple time model - rounds over the chip's workgroup slots (256 CUs x slots
-    // per CU) times the stages each split walks, plus the traffic of writing and re-reading one fp32
-    // partial tensor per split.
-    const long long slots = 256LL * kTiles[t].slots;
-    const double stage_us = 2.0 * kTiles[t].bm * kTiles[t].bn * kTiles[t].bp * kTiles[t].slots / (2.5e15 / 256 * 0.5) * 1e6;
-    const double split_us = (double)g.K * RSC * 8.0 / 3e12 * 1e6;
-    long long max_splits = (M + 2LL * kTiles[t].bp - 1) / (2LL * kTiles[t].bp);
-    if (max_splits > 1024) max_splits = 1024;
-    if (max_splits < 1) max_splits = 1;
-    long long splits = 1;
+            if (!strcmp(f, kTiles[i].name)) forced = i;
+    Plan best_pl{};
     double best = 1e300;
-    for (long long sp = 1; sp <= max_splits; ++sp) {
-        const long long wgs = tiles * sp, rounds = (wgs + slots - 1) / slots;
-        const long long stages = ((M + sp - 1) / sp + kTiles[t].bp - 1) / kTiles[t].bp;
-        const double t_us = (double)rounds * (double)stages * stage_us + (double)sp * split_us;
-        if (t_us < best) { best = t_us; splits = sp; }
+    for (int t = 0; t < N_TILES; ++t) {
+        if (forced >= 0 && t != forced) continue;
+        const WgradTile &tc = kTiles[t];
+        // no tile dimension more than twice the problem's (a 256-wide tile needs at least 256 rows/columns)
+        if (forced < 0 && ((tc.bm > 64 && tc.bm > g.K) || (tc.bn > 64 && tc.bn > RSC) || (tc.bm == 256 && g.K < 256) ||
+                           (tc.bn == 256 && RSC < 256)))
+            continue;
+        const int k_tiles = (g.K + tc.bm - 1) / tc.bm, n_tiles = (RSC + tc.bn - 1) / tc.bn;
+        const long long tiles = (long long)k_tiles * n_tiles;
+        const long long slots = 256LL * tc.slots;
+        const double stage_us = 2.0 * tc.bm * tc.bn * tc.bp * tc.slots / (2.5e15 / 256 * tc.util) * 1e6;
+        const double split_us = (double)g.K * RSC * 8.0 / 3e12 * 1e6;
+        long long max_splits = (M + 2LL * tc.bp - 1) / (2LL * tc.bp);
+        if (max_splits > 1024) max_splits = 1024;
+        if (max_splits < 1) max_splits = 1;
+        for (long long sp = 1; sp <= max_splits; ++sp) {
+            const long long wgs = tiles * sp, rounds = (wgs + slots - 1) / slots;
+            const long long stages = ((M + sp - 1) / sp + tc.bp - 1) / tc.bp;
+            const double t_us = (double)rounds * (double)(stages + 6) * stage_us + (double)sp * split_us;
+            if (t_us < best) {
+                best = t_us;
+                long long span = (M + sp - 1) / sp;
+                span = (span + tc.bp - 1) / tc.bp * tc.bp;
+                best_pl = Plan{t, k_tiles, n_tiles, (int)((M + span - 1) / span), (int)span};
+            }
+        }
     }
-    long long span = (M + splits - 1) / splits;
-    span = (span + kTiles[t].bp - 1) / kTiles[t].bp * kTiles[t].bp;
-    pl.splits = (int)((M + span - 1) / span);
-    pl.span = (int)span;
-    return pl;
+    return best_pl;
 }
 
 }  // namespace
