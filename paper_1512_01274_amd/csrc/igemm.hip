@@ -286,14 +286,12 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
             constexpr int ks = decltype(k)::value;
             Frags &cur = (ks & 1) ? f1 : f0;
             Frags &nxt = (ks & 1) ? f0 : f1;
-            if constexpr (ks == KS - 2) {
-                mfma_with(cur, IC<N_READ + N_ADDR>{}, [&](auto t) {
-                    constexpr int Tk = decltype(t)::value;
-                    if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<Tk - N_READ>{});
-                });
-            } else {
-                mfma_with(cur, IC<N_READ>{}, [&](auto t) { read_task(t, nxt, ca, cb, ks + 1); });
-            }
+            // this k-step's share of the address tasks, spread evenly over k-steps 0..KS-2
+            constexpr int a0 = ks * N_ADDR / (KS - 1), a1 = (ks + 1) * N_ADDR / (KS - 1);
+            mfma_with(cur, IC<N_READ + (a1 - a0)>{}, [&](auto t) {
+                constexpr int Tk = decltype(t)::value;
+                if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<a0 + Tk - N_READ>{});
+            });
         });
         // the last k-step's operands are in f1; all reads of this slot must have returned before it is refilled
         wait_lgkmcnt0();

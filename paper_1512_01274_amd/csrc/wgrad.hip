@@ -260,14 +260,12 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
             constexpr int ks = decltype(k)::value;
             Frags &cur = (ks & 1) ? f1 : f0;
             Frags &nxt = (ks & 1) ? f0 : f1;
-            if constexpr (ks == KS - 2) {
-                mfma_with(cur, IC<N_READ + L>{}, [&](auto t) {
-                    constexpr int Tk = decltype(t)::value;
-                    if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<Tk - N_READ>{});
-                });
-            } else {
-                mfma_with(cur, IC<N_READ>{}, [&](auto t) { read_task(t, nxt, ca, cb, ks + 1); });
-            }
+            // this k-step's share of the address tasks, spread evenly over k-steps 0..KS-2
+            constexpr int a0 = ks * L / (KS - 1), a1 = (ks + 1) * L / (KS - 1);
+            mfma_with(cur, IC<N_READ + (a1 - a0)>{}, [&](auto t) {
+                constexpr int Tk = decltype(t)::value;
+                if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<a0 + Tk - N_READ>{});
+            });
         });
         wait_lgkmcnt0();
         wait_vmcnt<L * (NS - 2)>();
