@@ -393,9 +393,9 @@ struct TileChoice { int bm, bn, slots; float util; const char *name; };
 const TileChoice kTiles[] = {
     {128, 128, 2, 0.91f, "igemm_128x128_k64s2_w4"},
     {256, 256, 1, 1.00f, "igemm_256x256_k64s2_w8"},
-    {256, 128, 1, 0.84f, "igemm_256x128_k64s3_w8"},
-    {128, 256, 1, 0.84f, "igemm_128x256_k64s3_w8"},
-    {128, 64, 3, 0.66f, "igemm_128x64_k64s2_w4"},
+    {256, 128, 1, 0.90f, "igemm_256x128_k64s3_w8"},
+    {128, 256, 1, 0.95f, "igemm_128x256_k64s3_w8"},
+    {128, 64, 3, 0.72f, "igemm_128x64_k64s2_w4"},
     {256, 64, 2, 0.66f, "igemm_256x64_k32s3_w4"},
     {128, 32, 4, 0.33f, "igemm_128x32_k64s2_w4"},
     {256, 32, 2, 0.33f, "igemm_256x32_k64s2_w4"},

@@ -78,29 +78,25 @@ __global__ __launch_bounds__(256) void smallc_pack_w_kernel(const bf16_t *__rest
 }
 
 // x2[n][h2][w2][(dh*s+dw)*Cq + c] = x[n][h2*s+dh-pad][w2*s+dw-pad][c] (0 outside the image or for c >= C).
-// One thread per 16-byte chunk of x2.
-__global__ __launch_bounds__(256) void s2d_pack_x_kernel(const bf16_t *__restrict__ x, uint4 *__restrict__ x2, int N, int C, int H,
-                                                         int W, int pad, int s, int Cq, int C2, int H2, int W2)
+// One thread per source pixel slot (n, h2, w2, dh, dw): Cq elements; consecutive threads write
+// consecutive addresses and, within one dh, read consecutive addresses.
+__global__ __launch_bounds__(256) void s2d_pack_x_kernel(const bf16_t *__restrict__ x, bf16_t *__restrict__ x2, int N, int C, int H,
+                                                         int W, int pad, int s, int Cq, int H2, int W2)
 {
-    const int chunks = C2 >> 3;
-    const long long total = (long long)N * H2 * W2 * chunks;
+    const int ss = s * s;
+    const long long total = (long long)N * H2 * W2 * ss;
     const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
-    const int ch0 = (int)(gid % chunks) * 8;
-    long long t = gid / chunks;
+    const int blk = (int)(gid % ss);
+    long long t = gid / ss;
     const int w2 = (int)(t % W2); t /= W2;
     const int h2 = (int)(t % H2);
     const int n = (int)(t / H2);
-    uint32_t v[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int e = ch0 + j, blk = e / Cq, c = e % Cq;
-        const int h = h2 * s + blk / s - pad, w = w2 * s + blk % s - pad;
-        uint32_t val = 0;
-        if (c < C && h >= 0 && h < H && w >= 0 && w < W) val = x[(((long long)n * H + h) * W + w) * C + c];
-        v[j >> 1] |= val << ((j & 1) * 16);
-    }
-    x2[gid] = make_uint4(v[0], v[1], v[2], v[3]);
+    const int h = h2 * s + blk / s - pad, w = w2 * s + blk % s - pad;
+    const bool in = h >= 0 && h < H && w >= 0 && w < W;
+    const bf16_t *src = x + (((long long)n * H + h) * W + w) * C;
+    bf16_t *dst = x2 + gid * Cq;
+    for (int c = 0; c < Cq; ++c) dst[c] = (in && c < C) ? src[c] : (bf16_t)0;
 }
 
 // w2[k][r2][s2][(dh*s+dw)*Cq + c] = w[k][r2*s+dh][s2*s+dw][c], zero where r >= R, s >= S or c >= C
@@ -209,11 +205,11 @@ ConvShape s2d_shape(const ConvShape &s)
 int s2d_pack_x(const ConvShape &s, const void *x, void *x2, hipStream_t st)
 {
     const S2DGeom g = s2d_geom(s);
-    const long long total = (long long)s.N * g.H2 * g.W2 * (g.C2 / 8);
+    const long long total = (long long)s.N * g.H2 * g.W2 * g.s * g.s;
     const long long blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
-    hipLaunchKernelGGL(s2d_pack_x_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)x, (uint4 *)x2, s.N, s.C, s.H,
-                       s.W, s.pad, g.s, g.Cq, g.C2, g.H2, g.W2);
+    hipLaunchKernelGGL(s2d_pack_x_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)x, (bf16_t *)x2, s.N, s.C, s.H,
+                       s.W, s.pad, g.s, g.Cq, g.H2, g.W2);
     return ok();
 }
 
