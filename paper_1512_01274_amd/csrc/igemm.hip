@@ -323,11 +323,17 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
     if ((p.Co & 7) == 0) {
         // Through LDS, one 32-row block of the wave tile at a time, so that global stores are 16 bytes
         // per lane and a row's WN channels leave as one contiguous run.
-        static_assert(NW * 32 * WN <= (SZA > SZB ? SZA : SZB), "epilogue staging must fit one stage buffer");
         constexpr int CPR = WN / 8;                   // 16-byte chunks per staged row
+        constexpr int RS = 32 * WN;                   // staging elements per wave
+        constexpr bool USE_A = SZA >= SZB;
+        constexpr int SZ = USE_A ? SZA : SZB;
+        constexpr int WPB = SZ / RS;                  // waves whose staging fits one stage buffer
+        static_assert(WPB >= 1 && NW <= WPB * NS, "epilogue staging must fit the stage buffers of one operand");
         wait_lgkmcnt0();
         __syncthreads();                              // every wave is done reading operands: LDS is free
-        bf16_t *stg = (SZA >= SZB ? sa0 : sb0) + wave * (32 * WN);
+        const int bi = wave / WPB;
+        bf16_t *stg = bi == 0 ? (USE_A ? sa0 : sb0) : bi == 1 ? (USE_A ? sa1 : sb1) : bi == 2 ? (USE_A ? sa2 : sb2) : (USE_A ? sa3 : sb3);
+        stg += (wave % WPB) * RS;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
 #pragma unroll
