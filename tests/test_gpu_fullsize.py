@@ -1,0 +1,113 @@
+"""GPU parity at the benchmark's full layer sizes, in the launch configuration bench.py times
+(bf16, NHWC-resident operands, KRSC filters): every layer of the four bf16 stacks, all three
+passes, checked on sampled outputs that the oracle's single-element evaluators compute one by
+one - a seeded random sample plus every border class (corners, edge midpoints, the rows and
+columns the floor rule leaves unread, every stride residue class).  Same metric and bounds as
+the full-tensor tests.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_1512_01274_amd import inputs as gen
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+N_RANDOM = 8192
+WGRAD_MAC_BUDGET = 3e9      # oracle multiply-adds spent on one layer's backward-weight samples
+
+LAYERS = [(ci, li) for ci in (1, 2, 3, 4) for li in range(len(gen.CONFIGS[ci].layers))]
+
+
+@pytest.fixture(scope="module")
+def mxc():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1512_01274_amd import mxc as m
+    return m
+
+
+def _edge(n):
+    """Border and near-border positions of an axis of length n."""
+    return sorted({0, 1, 2, 3, n // 2, n - 4, n - 3, n - 2, n - 1} & set(range(n)))
+
+
+def _grid(*axes):
+    g = np.meshgrid(*[np.asarray(a, dtype=np.int64) for a in axes], indexing="ij")
+    return [a.ravel() for a in g]
+
+
+def _sample(rng, shape, border_axes, n_random):
+    """Flat row-major indices into `shape`: borders on the given axes values + a random sample."""
+    b = _grid(*border_axes)
+    flat = np.ravel_multi_index(b, shape)
+    total = int(np.prod(shape))
+    rnd = rng.integers(0, total, size=n_random, dtype=np.int64)
+    return np.unique(np.concatenate([flat, rnd]))
+
+
+def _nchw_to_nhwc_index(idx, shape):
+    n, c, h, w = np.unravel_index(idx, shape)
+    N, C, H, W = shape
+    return ((n * H + h) * W + w) * C + c
+
+
+def _gather(t, flat_idx):
+    """Values of a flat GPU tensor at the given indices, as float64 on the host."""
+    sel = t.index_select(0, torch.from_numpy(flat_idx).cuda())
+    return gen.to_host_f64(sel)
+
+
+def _check(name, got, ref, den, out_is_bf16, L):
+    err = util.metric(got, ref, den)
+    assert err <= util.TOL["bf16"], f"{L.name} {name}: err {err:.3e}"
+    excess = np.abs(got - ref) - util.tight_bound(ref, den, "bf16", out_is_bf16)
+    i = int(np.argmax(excess))
+    assert excess[i] <= 0, f"{L.name} {name}: tight bound exceeded: gpu {got[i]!r} oracle {ref[i]!r} D {den[i]!r}"
+
+
+@pytest.mark.parametrize("ci,li", LAYERS)
+def test_full_size_sampled(mxc, oracle, ci, li):
+    cfg = gen.CONFIGS[ci]
+    L, t = gen.layer_inputs(cfg, li)
+    x, w, dy = t["x"], t["w"], t["dy"]
+    N, C, H, W, K, R, S, st, pad = L.dims()
+    P, Q = L.P, L.Q
+    rng = np.random.Generator(np.random.Philox(key=gen.SEED + 1000 * ci + li))
+    dims = L.dims()
+    dt, lay = mxc.MXC_BF16, mxc.MXC_NHWC
+
+    def nhwc(a):    # device tensor, flat, NHWC order (torch is plumbing here)
+        d = gen.to_device(a, "bf16")
+        return d.view(*a.shape).permute(0, 2, 3, 1).contiguous().view(-1)
+
+    dx_, dw_, ddy_ = nhwc(x), nhwc(w), nhwc(dy)
+    ws = {op: mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *dims, dt, lay))
+          for op in (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT)}
+
+    # forward
+    y = torch.full((N * K * P * Q,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    mxc.mxc_conv2d_fwd(*dims, dt, lay, dx_, dw_, y, ws[mxc.MXC_FWD])
+    idx = _sample(rng, (N, K, P, Q), ([0, N - 1], [0, K // 2, K - 1], _edge(P), _edge(Q)), N_RANDOM)
+    ref, den = oracle.conv2d_fwd_at(x, w, st, pad, idx)
+    _check("fwd", _gather(y, _nchw_to_nhwc_index(idx, (N, K, P, Q))), ref, den, True, L)
+    del y
+
+    # backward-data: borders include the rows/columns beyond the last window and all residues mod stride
+    dx = torch.full((N * C * H * W,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    mxc.mxc_conv2d_bwd_data(*dims, dt, lay, ddy_, dw_, dx, ws[mxc.MXC_BWD_DATA])
+    hs = sorted(set(_edge(H)) | set(range(min(H, 2 * st))) | set(range(max(0, H - 2 * st), H)))
+    vs = sorted(set(_edge(W)) | set(range(min(W, 2 * st))) | set(range(max(0, W - 2 * st), W)))
+    idx = _sample(rng, (N, C, H, W), ([0, N - 1], [0, C // 2, C - 1], hs, vs), N_RANDOM)
+    ref, den = oracle.conv2d_bwd_data_at(dy, w, x.shape, st, pad, idx)
+    _check("bwd_data", _gather(dx, _nchw_to_nhwc_index(idx, (N, C, H, W))), ref, den, True, L)
+    del dx
+
+    # backward-weight: every filter tap for corner channels + a random sample sized to the oracle budget
+    dwt = torch.full((K * C * R * S,), float("nan"), dtype=torch.float32, device="cuda")
+    mxc.mxc_conv2d_bwd_weight(*dims, dt, lay, dx_, ddy_, dwt, ws[mxc.MXC_BWD_WEIGHT])
+    n_rand = int(max(256, min(N_RANDOM, WGRAD_MAC_BUDGET / (N * P * Q))))
+    idx = _sample(rng, (K, C, R, S), ([0, K - 1], [0, C - 1], range(R), range(S)), n_rand)
+    ref, den = oracle.conv2d_bwd_weight_at(x, dy, w.shape, st, pad, idx)
+    _check("bwd_weight", _gather(dwt, _nchw_to_nhwc_index(idx, (K, C, R, S))), ref, den, False, L)
+    torch.cuda.synchronize()
