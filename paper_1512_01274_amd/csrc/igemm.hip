@@ -394,15 +394,15 @@ int launch(IgemmParams p, hipStream_t st)
 
 // A tile shape the launcher can pick: output tile, workgroups that fit one CU at a time (LDS and
 // register budget) and the matrix-pipe utilisation it reaches relative to the 256x256 tile when the
-// chip is full (measured on the VGG-style 3x3 layers).
+// chip is full (fitted to per-layer times of the AlexNet- and VGG-style stacks run back to back).
 struct TileChoice { int bm, bn, slots; float util; const char *name; };
 const TileChoice kTiles[] = {
     {128, 128, 2, 0.91f, "igemm_128x128_k64s2_w4"},
-    {256, 256, 1, 1.00f, "igemm_256x256_k64s2_w8"},
-    {256, 128, 1, 0.90f, "igemm_256x128_k64s3_w8"},
-    {128, 256, 1, 0.95f, "igemm_128x256_k64s3_w8"},
-    {128, 64, 3, 0.72f, "igemm_128x64_k64s2_w4"},
-    {256, 64, 2, 0.66f, "igemm_256x64_k32s3_w4"},
+    {256, 256, 1, 1.15f, "igemm_256x256_k64s2_w8"},
+    {256, 128, 1, 0.86f, "igemm_256x128_k64s3_w8"},
+    {128, 256, 1, 0.82f, "igemm_128x256_k64s3_w8"},
+    {128, 64, 3, 0.65f, "igemm_128x64_k64s2_w4"},
+    {256, 64, 2, 0.60f, "igemm_256x64_k32s3_w4"},
     {128, 32, 4, 0.33f, "igemm_128x32_k64s2_w4"},
     {256, 32, 2, 0.33f, "igemm_256x32_k64s2_w4"},
 };
@@ -422,8 +422,10 @@ int launch_choice(int idx, const IgemmParams &p, hipStream_t st)
     }
 }
 
-// Tile choice: the shape with the least modelled time = rounds over the chip's workgroup slots x
-// work per round / utilisation (padding waste and the partly filled last round are what differ).
+// Tile choice: the shape with the least modelled time.  Tiles are dealt evenly to the 256 CUs, so a CU
+// works through ceil(tiles/256) tiles, `slots` at a time; a tile costs its area over the utilisation
+// the shape reaches, which drops when fewer workgroups than `slots` share the CU (less latency
+// hiding).  Padding waste and the partly filled last round are what differ between shapes.
 // MXC_FORCE_VARIANT=<name> (tuning sweeps only) overrides it.
 int choose_tile(long long M, int Co, int Kd)
 {
@@ -436,9 +438,10 @@ int choose_tile(long long M, int Co, int Kd)
     for (int i = 0; i < N_TILE_CHOICES; ++i) {
         const TileChoice &t = kTiles[i];
         const long long tiles = ((M + t.bm - 1) / t.bm) * ((Co + t.bn - 1) / t.bn);
-        const long long slots = 256LL * t.slots;
-        const long long rounds = (tiles + slots - 1) / slots;
-        const double time = (double)rounds * t.slots * t.bm * t.bn / t.util;
+        const long long per_cu = (tiles + 255) / 256;
+        const double resident = per_cu < t.slots ? (double)per_cu : (double)t.slots;
+        const double util = t.util * (0.6 + 0.4 * resident / t.slots);
+        const double time = (double)per_cu * t.bm * t.bn / util;
         if (time < best_t) { best_t = time; best = i; }
     }
     return best;

@@ -49,6 +49,42 @@ __global__ __launch_bounds__(256) void small_c_kernel(const T *__restrict__ src,
     }
 }
 
+// Same permutation for 2-byte elements, C channels, 8 pixels per thread: C 16-byte loads, a register
+// shuffle, C 16-byte stores.  Needs pixels % 8 == 0 (keeps every access 16-byte aligned).
+template <int C, bool TO_INTERLEAVED>
+__global__ __launch_bounds__(256) void small_c_vec_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                          long long pixels)
+{
+    const long long pix0 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    if (pix0 >= pixels) return;
+    const size_t base = (size_t)blockIdx.y * C * pixels;
+    union V { uint4 v; uint16_t e[8]; };
+    V in[C], out[C];
+    if (TO_INTERLEAVED) {
+#pragma unroll
+        for (int ch = 0; ch < C; ++ch) in[ch].v = *reinterpret_cast<const uint4 *>(src + base + (size_t)ch * pixels + pix0);
+#pragma unroll
+        for (int j = 0; j < 8 * C; ++j) out[j / 8].e[j % 8] = in[j % C].e[j / C];
+#pragma unroll
+        for (int i = 0; i < C; ++i) *reinterpret_cast<uint4 *>(dst + base + (size_t)pix0 * C + i * 8) = out[i].v;
+    } else {
+#pragma unroll
+        for (int i = 0; i < C; ++i) in[i].v = *reinterpret_cast<const uint4 *>(src + base + (size_t)pix0 * C + i * 8);
+#pragma unroll
+        for (int j = 0; j < 8 * C; ++j) out[j % C].e[j / C] = in[j / 8].e[j % 8];
+#pragma unroll
+        for (int ch = 0; ch < C; ++ch) *reinterpret_cast<uint4 *>(dst + base + (size_t)ch * pixels + pix0) = out[ch].v;
+    }
+}
+
+template <int C>
+void launch_small_c_vec(const void *src, void *dst, int batch, long long pixels, bool to_inter, hipStream_t stream)
+{
+    dim3 grid((unsigned)((pixels / 8 + 255) / 256), (unsigned)batch), block(256);
+    if (to_inter) hipLaunchKernelGGL((small_c_vec_kernel<C, true>), grid, block, 0, stream, (const uint16_t *)src, (uint16_t *)dst, pixels);
+    else hipLaunchKernelGGL((small_c_vec_kernel<C, false>), grid, block, 0, stream, (const uint16_t *)src, (uint16_t *)dst, pixels);
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16,
                                                    const unsigned char *__restrict__ tail_src,
                                                    unsigned char *__restrict__ tail_dst, int tail)
@@ -67,6 +103,12 @@ int launch_transpose(const void *src, void *dst, int batch, int rows, int cols, 
         const bool to_inter = rows <= 8;           // [c][pixels] -> [pixels][c]
         const int c = to_inter ? rows : cols;
         const long long pixels = to_inter ? cols : rows;
+        if (elem_bytes == 2 && pixels % 8 == 0 && c >= 2 && c <= 4) {
+            if (c == 2) launch_small_c_vec<2>(src, dst, batch, pixels, to_inter, stream);
+            else if (c == 3) launch_small_c_vec<3>(src, dst, batch, pixels, to_inter, stream);
+            else launch_small_c_vec<4>(src, dst, batch, pixels, to_inter, stream);
+            return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+        }
         dim3 grid((unsigned)((pixels + 255) / 256), (unsigned)batch), block(256);
         if (elem_bytes == 2) {
             if (to_inter) hipLaunchKernelGGL((small_c_kernel<uint16_t, true>), grid, block, 0, stream, (const uint16_t *)src, (uint16_t *)dst, c, pixels);

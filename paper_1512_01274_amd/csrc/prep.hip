@@ -134,6 +134,58 @@ __global__ __launch_bounds__(256) void s2d_unpack_dx_kernel(const bf16_t *__rest
     for (int c = 0; c < C; ++c) d[c] = in ? src[c] : (bf16_t)0;
 }
 
+// Fast space-to-depth copy for C == Cq when every run of s*C elements (one source row piece of a
+// block) starts on a 4-byte boundary on both sides.  One thread per (n, h2, w2, dh), dh fastest: the
+// four threads of a block touch one contiguous destination (pack) or source (unpack) pixel of x2.
+// PACK:   x2 <- x, zeros outside the image.
+// UNPACK: dx <- dx2 for pixels inside the image; blocks beyond the H2 x W2 grid (pixels no window
+//         reaches) deliver zeros.  The grid covers ceil((H+pad)/s) x ceil((W+pad)/s) blocks.
+template <bool PACK>
+__global__ __launch_bounds__(256) void s2d_rows_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int N, int C, int H,
+                                                       int W, int pad, int s, int H2, int W2, int H2g, int W2g)
+{
+    const long long total = (long long)N * H2g * W2g * s;
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int dh = (int)(gid % s);
+    long long t = gid / s;
+    const int w2 = (int)(t % W2g); t /= W2g;
+    const int h2 = (int)(t % H2g);
+    const int n = (int)(t / H2g);
+    const int h = h2 * s + dh - pad, w0 = w2 * s - pad;
+    const int run = s * C;
+    const bool blk_ok = h2 < H2 && w2 < W2;                       // block exists in x2
+    const long long img = ((long long)n * H + h) * W * C + (long long)w0 * C;          // element offset in x / dx
+    const long long blk = ((((long long)n * H2 + h2) * W2 + w2) * s + dh) * run;      // element offset in x2 / dx2
+    const bool row_ok = h >= 0 && h < H;
+    const bool inside = row_ok && w0 >= 0 && w0 + s <= W;
+    if (PACK) {
+        if (!blk_ok) return;
+        if (inside) {
+            const uint32_t *a = reinterpret_cast<const uint32_t *>(src + img);
+            uint32_t *b = reinterpret_cast<uint32_t *>(dst + blk);
+            for (int i = 0; i < run / 2; ++i) b[i] = a[i];
+        } else {
+            for (int e = 0; e < run; ++e) {
+                const int w = w0 + e / C;
+                dst[blk + e] = (row_ok && w >= 0 && w < W) ? src[img + e] : (bf16_t)0;
+            }
+        }
+    } else {
+        if (!row_ok) return;
+        if (inside && blk_ok) {
+            const uint32_t *a = reinterpret_cast<const uint32_t *>(src + blk);
+            uint32_t *b = reinterpret_cast<uint32_t *>(dst + img);
+            for (int i = 0; i < run / 2; ++i) b[i] = a[i];
+        } else {
+            for (int e = 0; e < run; ++e) {
+                const int w = w0 + e / C;
+                if (w >= 0 && w < W) dst[img + e] = blk_ok ? src[blk + e] : (bf16_t)0;
+            }
+        }
+    }
+}
+
 inline int ok() { return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH; }
 
 }  // namespace
@@ -180,6 +232,12 @@ int smallc_pack_w(const ConvShape &s, const void *w, void *wp, hipStream_t st)
     return ok();
 }
 
+// every run of s*C elements starts 4-byte aligned in x and in x2 (and no channel padding)
+static bool s2d_rows_aligned(const ConvShape &s, const S2DGeom &g)
+{
+    return g.Cq == s.C && (s.C % 2 == 0 || (s.W % 2 == 0 && s.pad % 2 == 0 && g.s % 2 == 0));
+}
+
 S2DGeom s2d_geom(const ConvShape &s)
 {
     S2DGeom g;
@@ -205,6 +263,13 @@ ConvShape s2d_shape(const ConvShape &s)
 int s2d_pack_x(const ConvShape &s, const void *x, void *x2, hipStream_t st)
 {
     const S2DGeom g = s2d_geom(s);
+    if (s2d_rows_aligned(s, g)) {
+        const long long n_thr = (long long)s.N * g.H2 * g.W2 * g.s;
+        if ((n_thr + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+        hipLaunchKernelGGL(s2d_rows_kernel<true>, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, (const bf16_t *)x,
+                           (bf16_t *)x2, s.N, s.C, s.H, s.W, s.pad, g.s, g.H2, g.W2, g.H2, g.W2);
+        return ok();
+    }
     const long long total = (long long)s.N * g.H2 * g.W2 * g.s * g.s;
     const long long blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
@@ -225,6 +290,14 @@ int s2d_pack_w(const ConvShape &s, const void *w, void *w2, hipStream_t st)
 int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st)
 {
     const S2DGeom g = s2d_geom(s);
+    if (s2d_rows_aligned(s, g)) {
+        const int H2g = (s.H + s.pad + g.s - 1) / g.s, W2g = (s.W + s.pad + g.s - 1) / g.s;
+        const long long n_thr = (long long)s.N * H2g * W2g * g.s;
+        if ((n_thr + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+        hipLaunchKernelGGL(s2d_rows_kernel<false>, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, (const bf16_t *)dx2,
+                           (bf16_t *)dx, s.N, s.C, s.H, s.W, s.pad, g.s, g.H2, g.W2, H2g, W2g);
+        return ok();
+    }
     const long long total = (long long)s.N * s.H * s.W;
     const long long blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;

@@ -84,6 +84,8 @@ SWEEP = [
     (1, 3, 20, 20, 16, 7, 7, 2, 3),
     (1, 12, 9, 9, 16, 3, 3, 1, 1),      # C % 8 != 0, C > 4: channel-padded path
     (2, 20, 7, 8, 24, 3, 3, 2, 1),
+    (1, 3, 22, 24, 8, 11, 11, 4, 2),    # space-to-depth with 4-byte aligned rows (dword copy path)
+    (2, 4, 18, 21, 8, 5, 5, 2, 1),
 ]
 
 
@@ -151,7 +153,8 @@ def test_canaries_around_outputs(mxc, dtype):
 # ---- layout conversion: exact permutation, both directions, both element sizes --
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 5, 7), (3, 64, 8, 8), (2, 65, 9, 15), (1, 200, 3, 3), (2, 16, 70, 66)])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 5, 7), (3, 64, 8, 8), (2, 65, 9, 15), (1, 200, 3, 3), (2, 16, 70, 66),
+                                   (2, 3, 8, 24), (3, 4, 4, 6), (1, 2, 16, 3), (2, 3, 224, 224)])
 def test_layout_convert(mxc, shape, dtype):
     n, c, h, w = shape
     g = np.random.Generator(np.random.Philox(key=3))
