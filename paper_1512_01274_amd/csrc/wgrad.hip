@@ -285,19 +285,44 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
     wait_vmcnt<0>();
 
     // ---- fp32 partial tile -> workspace ------------------------------------------------------
-    float *out = p.partial + (size_t)z * p.K * RSC;
+    // Through LDS, one 32-row block of the wave tile at a time, so that a row's WN columns leave as
+    // 16-byte stores (the column count is a multiple of 8, so a group of four is valid or not as one).
+    {
+        constexpr int RS = 32 * WN * 2;               // staging per wave, in bf16 slots (fp32 = 2 slots)
+        constexpr bool USE_A = SZA >= SZB;
+        constexpr int SZ = USE_A ? SZA : SZB;
+        constexpr int WPB = SZ / RS;
+        static_assert(WPB >= 1 && NW <= WPB * NS, "partial-tile staging must fit the stage buffers of one operand");
+        constexpr int CPR = WN / 4;                   // float4 groups per staged row
+        wait_lgkmcnt0();
+        __syncthreads();
+        const int bi = wave / WPB;
+        bf16_t *sb = bi == 0 ? (USE_A ? sa0 : sb0) : bi == 1 ? (USE_A ? sa1 : sb1) : bi == 2 ? (USE_A ? sa2 : sb2) : (USE_A ? sa3 : sb3);
+        float *stg = reinterpret_cast<float *>(sb + (wave % WPB) * RS);
+        float *out = p.partial + (size_t)z * p.K * RSC;
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int k = k0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            if (k >= p.K) continue;
+            for (int e = 0; e < 16; ++e)
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int c = n0 + wave_n + j * 32 + (lane & 31);
-                if (c < RSC) out[(size_t)k * RSC + c] = acc[i][j][e];
+                for (int j = 0; j < NI; ++j)
+                    stg[(8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * WN + j * 32 + (lane & 31)] = acc[i][j][e];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int q = 0; q < 32 * CPR / 64; ++q) {
+                const int idx = q * 64 + lane;
+                const int r = idx / CPR, c4 = idx % CPR;
+                const int k = k0 + wave_m + i * 32 + r, c = n0 + wave_n + c4 * 4;
+                const float4 v = *reinterpret_cast<const float4 *>(stg + r * WN + c4 * 4);
+                if (k < p.K && c < RSC) *reinterpret_cast<float4 *>(out + (size_t)k * RSC + c) = v;
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
+    }
 }
 
 // dw[k][r][s][c] = sum over splits (ascending order) of partial[z][k][col], col = (r/d)*col_r + (s/d)*col_s +
@@ -316,6 +341,20 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     const size_t src = (size_t)k * ncols + (r / s2d) * col_r + (sidx / s2d) * col_s + ((r % s2d) * s2d + sidx % s2d) * Cq + c;
     float acc = partial[src];
     for (int zz = 1; zz < splits; ++zz) acc += partial[(size_t)zz * split_stride + src];
+    dw[gid] = acc;
+}
+
+// Plain NHWC operands (source index == destination index), four outputs per thread with 16-byte loads.
+__global__ __launch_bounds__(256) void wgrad_reduce_vec4_kernel(const float4 *__restrict__ partial, float4 *__restrict__ dw,
+                                                                int total4, int splits)
+{
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total4) return;
+    float4 acc = partial[gid];
+    for (int zz = 1; zz < splits; ++zz) {
+        const float4 v = partial[(size_t)zz * total4 + gid];
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
     dw[gid] = acc;
 }
 
@@ -495,10 +534,14 @@ int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *p
     const int rc = launch_choice(pl.tile, p, (int)tiles, st);
     if (rc != MXC_OK) return rc;
     const int total = g.K * g.R * g.S * g.C;
-    if (p.splits > 16 && (long long)total * 4 < 256LL * 1024 * 4)
+    const bool identity = g.s2d == 1 && g.col_s == g.C && g.col_r == g.S * g.C && p.ncols == g.R * g.S * g.C;
+    if (p.splits > 16 && total < 256 * 1024)
         hipLaunchKernelGGL(wgrad_reduce_wide_kernel, dim3((unsigned)((total + 63) / 64)), dim3(1024), 0, st, partial, dw, total,
                            p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq,
                            (size_t)g.K * p.ncols);
+    else if (identity && total % 4 == 0)
+        hipLaunchKernelGGL(wgrad_reduce_vec4_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, st,
+                           (const float4 *)partial, (float4 *)dw, total / 4, p.splits);
     else
         hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, dw, total,
                            p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq,
