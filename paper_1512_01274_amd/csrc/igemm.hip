@@ -71,9 +71,12 @@ template <int I> using IC = std::integral_constant<int, I>;
 template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) { (f(IC<I>{}), ...); }
 template <int N, class F> __device__ __forceinline__ void static_for(F &&f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
 
-// BM x BN output tile, BKT reduction elements per stage, NS stages, WR x WC waves.
+// BM x BN output tile, BKT reduction elements per stage, NS stages, WR x WC waves.  The register
+// budget is set for two waves per SIMD when the workgroup has 4 waves and its LDS lets two of them
+// share a CU.
 template <int BM, int BN, int BKT, int NS, int WR, int WC>
-__global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p)
+__global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT * 2 <= 80 * 1024) ? 2 : 1) void igemm_kernel(
+    const IgemmParams p)
 {
     constexpr int NW = WR * WC, NT = 64 * NW;
     constexpr int WM = BM / WR, WN = BN / WC;     // wave tile
@@ -248,14 +251,19 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
 
     // NMF MFMAs of one k-step with `NTASK` side tasks spread between them (program order is pinned:
     // the matrix pipe executes one MFMA while the wave issues the side work behind it)
-    auto mfma_with = [&](const Frags &f, auto ntask, auto &&task) {
-        constexpr int NTASK = decltype(ntask)::value;
+    // The first NFRONT tasks (operand fetches, which the next k-step waits for) go behind the first half
+    // of the MFMAs, the rest behind the second half.
+    auto mfma_with = [&](const Frags &f, auto nfront, auto ntask, auto &&task) {
+        constexpr int NFRONT = decltype(nfront)::value, NTASK = decltype(ntask)::value;
+        constexpr int H1 = NMF > 1 ? NMF / 2 : 1, H2 = NMF - H1 > 0 ? NMF - H1 : 1;
         static_for<NMF>([&](auto s) {
             constexpr int S = decltype(s)::value;
             acc[S / NI][S % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[S / NI], f.b[S % NI], acc[S / NI][S % NI], 0, 0, 0);
             static_for<NTASK>([&](auto t) {
                 constexpr int Tk = decltype(t)::value;
-                if constexpr (Tk * NMF / NTASK == S) task(t);
+                constexpr int slot = Tk < NFRONT ? Tk * H1 / NFRONT
+                                                 : (NMF > 1 ? H1 + (Tk - NFRONT) * H2 / (NTASK - NFRONT > 0 ? NTASK - NFRONT : 1) : 0);
+                if constexpr (slot == S) task(t);
             });
             pin();
         });
@@ -288,7 +296,7 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
             Frags &nxt = (ks & 1) ? f0 : f1;
             // this k-step's share of the address tasks, spread evenly over k-steps 0..KS-2
             constexpr int a0 = ks * N_ADDR / (KS - 1), a1 = (ks + 1) * N_ADDR / (KS - 1);
-            mfma_with(cur, IC<N_READ + (a1 - a0)>{}, [&](auto t) {
+            mfma_with(cur, IC<N_READ>{}, IC<N_READ + (a1 - a0)>{}, [&](auto t) {
                 constexpr int Tk = decltype(t)::value;
                 if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<a0 + Tk - N_READ>{});
             });
@@ -297,10 +305,10 @@ __global__ __launch_bounds__(64 * WR * WC) void igemm_kernel(const IgemmParams p
         wait_lgkmcnt0();
         wait_vmcnt<L * (NS - 2)>();
         __syncthreads();
-        mfma_with(f1, IC<L + N_READ>{}, [&](auto t) {
+        mfma_with(f1, IC<N_READ>{}, IC<N_READ + L>{}, [&](auto t) {
             constexpr int Tk = decltype(t)::value;
-            if constexpr (Tk < L) load_task(t, ca, cb);
-            else read_task(IC<Tk - L>{}, f0, stage_a(IC<S1>{}), stage_b(IC<S1>{}), 0);
+            if constexpr (Tk < N_READ) read_task(t, f0, stage_a(IC<S1>{}), stage_b(IC<S1>{}), 0);
+            else load_task(IC<Tk - N_READ>{}, ca, cb);
         });
     };
 
