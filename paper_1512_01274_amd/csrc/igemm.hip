@@ -494,6 +494,24 @@ __global__ __launch_bounds__(256) void repack_bwd_data_filter_kernel(const bf16_
     wt[gid] = w[(((size_t)k * R + r) * S + s) * C + c];
 }
 
+// dx[n][h_first + stride*a][v_first + stride*b][:] = 0 for the Mh x Mw pixels of one residue class;
+// one thread per cw consecutive channels (cw = 8: one 16-byte store).
+__global__ __launch_bounds__(256) void zero_phase_kernel(bf16_t *__restrict__ dx, long long n_thr, int H, int W, int C, int cw,
+                                                         int stride, int h_first, int v_first, int Mh, int Mw)
+{
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= n_thr) return;
+    const int per_pix = C / cw;
+    const int ch = (int)(gid % per_pix) * cw;
+    long long t = gid / per_pix;
+    const int b = (int)(t % Mw); t /= Mw;
+    const int a = (int)(t % Mh);
+    const long long n = t / Mh;
+    bf16_t *d = dx + ((n * H + (h_first + stride * a)) * W + (v_first + stride * b)) * C + ch;
+    if (cw == 8) *reinterpret_cast<uint4 *>(d) = make_uint4(0, 0, 0, 0);
+    else *d = 0;
+}
+
 }  // namespace
 
 bool igemm_fwd_supported(const ConvShape &s)
@@ -577,6 +595,16 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
             p.Ho = s.H; p.Wo = s.W; p.out_mul_h = s.stride; p.out_mul_w = s.stride; p.out_off_h = h_first; p.out_off_w = v_first;
             wt_off += (size_t)s.C * TR * TS * s.K;
             if (Mh <= 0 || Mw <= 0) continue;
+            if (TR * TS == 0) {
+                // no tap reaches this residue class (stride larger than the filter): its pixels are zero
+                const int cw = (s.C % 8 == 0) ? 8 : 1;   // elements written per thread
+                const long long n_thr = (long long)s.N * Mh * Mw * (s.C / cw);
+                if ((n_thr + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+                hipLaunchKernelGGL(zero_phase_kernel, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, (bf16_t *)dx, n_thr,
+                                   s.H, s.W, s.C, cw, s.stride, h_first, v_first, Mh, Mw);
+                if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
+                continue;
+            }
             tc = choose_tile((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
             const int rc = launch_choice(tc, p, st);
             if (rc != MXC_OK) return rc;
