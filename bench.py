@@ -111,11 +111,15 @@ def time_steps(torch, net, steps, warmup):
 
 def time_calls(torch, net, steps):
     """Per-call durations (ms, mean over `steps`) with HIP events on the stream the kernels run on
-    (torch's current stream), over the same sequence of calls as the timed region."""
+    (torch's current stream), over the same sequence of calls as the timed region.  An event pair
+    with nothing between it, recorded once per step behind the same busy stream, measures what the
+    two event packets themselves cost (about 5 us); that is subtracted, so that a call that is one
+    launch reads as that kernel's duration.  Returns (per-call list, event-pair overhead in ms)."""
     mxc = net.mxc
     calls = net.calls()
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
           for _ in range(steps)]
+    null = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     variants = []
     for i in range(steps):
         for j, (_, op, _, fn) in enumerate(calls):
@@ -124,12 +128,16 @@ def time_calls(torch, net, steps):
             ev[i][j][1].record()
             if i == 0:
                 variants.append(mxc.mxc_last_variant() if op != "layout" else "layout:transpose")
+        null[i][0].record()
+        null[i][1].record()
     torch.cuda.synchronize()
+    gaps = sorted(a.elapsed_time(b) for a, b in null)
+    overhead = gaps[len(gaps) // 2]
     out = []
     for j, (name, op, s, _) in enumerate(calls):
         ms = sum(ev[i][j][0].elapsed_time(ev[i][j][1]) for i in range(steps)) / steps
-        out.append({"layer": name, "op": op, "variant": variants[j], "ms": ms, "state": s})
-    return out
+        out.append({"layer": name, "op": op, "variant": variants[j], "ms": max(ms - overhead, 1e-6), "state": s})
+    return out, overhead
 
 
 def kernel_of(variant):
@@ -137,7 +145,7 @@ def kernel_of(variant):
     return variant.split(":")[-1].split("+")[-1]
 
 
-def roofline_of(per_call, net):
+def roofline_of(per_call, net, event_overhead_ms=0.0):
     """Roofline entry of the kernel that takes the most time in a step.  Its launches are timed with HIP
     events around the ABI call; only calls that are exactly one launch of that kernel (plain forward
     calls) enter the figure, so that the event time is the kernel's duration (plus the launch gap)."""
@@ -162,6 +170,7 @@ def roofline_of(per_call, net):
     r["kernel"] = dominant
     r["launches"] = [c["layer"] + ":" + c["op"] for c in group]
     r["avg_launch_ms"] = round(t * 1e3 / len(group), 4)
+    r["event_pair_overhead_ms"] = round(event_overhead_ms, 4)      # already subtracted from avg_launch_ms
     r["algorithmic_flops_per_launch"] = flops // len(group)
     r["algorithmic_bytes_per_launch"] = nbytes // len(group)
     r["traffic"] = load_traffic(net.cfg.name, dominant)
@@ -222,8 +231,8 @@ def main():
     def run_one(cfg, steps, warmup):
         net = Network(mxc, torch, gen, cfg)
         sec = time_steps(torch, net, steps, warmup)
-        per_call = time_calls(torch, net, steps)
-        return net, sec, per_call
+        per_call, ev_ms = time_calls(torch, net, steps)
+        return net, sec, per_call, ev_ms
 
     if args.calibrate_copy:
         n_el = 1 << 28                      # 2^28 fp32 = 1 GiB read + 1 GiB written
@@ -233,7 +242,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     cfg = gen.config_by_name(args.workload)
-    net, sec, per_call = run_one(cfg, args.steps, args.warmup)
+    net, sec, per_call, ev_ms = run_one(cfg, args.steps, args.warmup)
     value = net.flops_per_step / sec / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
     result = {
@@ -244,7 +253,7 @@ def main():
         "config": {"workload": cfg.name, "layers": len(cfg.layers), "batch": cfg.layers[0].N, "layout": "nhwc-resident",
                    "step": "layout(NCHW->NHWC of network input) + per layer fwd, bwd_data, bwd_weight"},
         "frac_of_mfma_peak": round(value / peak, 4),
-        "roofline": roofline_of(per_call, net),
+        "roofline": roofline_of(per_call, net, ev_ms),
     }
     if args.per_layer:
         for c in per_call:
@@ -265,7 +274,7 @@ def main():
         for other in gen.CONFIGS:
             if other.name == cfg.name:
                 continue
-            n2, s2, pc2 = run_one(other, max(3, args.steps // 4), 2)
+            n2, s2, pc2, _ = run_one(other, max(3, args.steps // 4), 2)
             pk = PEAK_BF16_TFLOPS if other.dtype == "bf16" else PEAK_F32_TFLOPS
             nbytes = sum(algorithmic_bytes(c["state"].L, c["op"], n2.esize) for c in pc2 if c["op"] != "layout")
             nets[other.name] = {"tflops": round(n2.flops_per_step / s2 / 1e12, 3), "ms_per_step": round(s2 * 1e3, 4),

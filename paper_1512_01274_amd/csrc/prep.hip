@@ -186,6 +186,94 @@ __global__ __launch_bounds__(256) void s2d_rows_kernel(const bf16_t *__restrict_
     }
 }
 
+
+// LDS-staged space-to-depth copies, same applicability as s2d_rows_kernel (C == Cq, every run of
+// s*C elements dword-aligned on both sides).  One workgroup moves one row of blocks (n, h2): the s
+// image rows and the x2 row are each contiguous in memory, so both sides are accessed with
+// consecutive lanes on consecutive dwords (16 bytes per lane when V16: image rows 16-byte aligned),
+// and the shuffle between the two orders happens in LDS at dword granularity.
+//   image row dh, dword d  <->  x2 row dword ((w2*s + dh)*run + rem)/2,  with E = 2d + pad*C,
+//   w2 = E / run, rem = E % run   (run = s*C elements).
+template <bool V16>
+__global__ __launch_bounds__(256) void s2d_stage_pack_kernel(const bf16_t *__restrict__ x, bf16_t *__restrict__ x2, int C, int H,
+                                                             int W, int pad, int s, int H2, int W2)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t s2d_lds[];
+    const int h2 = blockIdx.x % H2;
+    const long long n = blockIdx.x / H2;
+    const int row_dw = W * C / 2;                    // dwords per image row
+    const int pitch = (row_dw + 3) & ~3;
+    const int run_dw = s * C / 2;
+    for (int dh = 0; dh < s; ++dh) {
+        const int h = h2 * s + dh - pad;
+        if (h < 0 || h >= H) continue;               // uniform over the workgroup
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(x + ((n * H + h) * W) * (long long)C);
+        uint32_t *l = s2d_lds + dh * pitch;
+        if (V16) {
+            for (int i = threadIdx.x; i < row_dw / 4; i += 256)
+                reinterpret_cast<uint4 *>(l)[i] = reinterpret_cast<const uint4 *>(src)[i];
+        } else {
+            for (int i = threadIdx.x; i < row_dw; i += 256) l[i] = src[i];
+        }
+    }
+    __syncthreads();
+    const int out_dw = W2 * s * run_dw;              // multiple of 4: s*s*C is a multiple of 8
+    uint4 *dst = reinterpret_cast<uint4 *>(x2 + ((n * H2 + h2) * W2) * (long long)(s * s * C));
+    const int shift = pad * C / 2;                   // dwords of left padding
+    for (int o4 = threadIdx.x; o4 < out_dw / 4; o4 += 256) {
+        int o = o4 * 4;
+        int blk = o / run_dw, i = o - blk * run_dw;
+        int w2 = blk / s, dh = blk - w2 * s;
+        uint32_t v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int h = h2 * s + dh - pad;
+            const int d = w2 * run_dw + i - shift;   // dword within the image row
+            v[j] = (h >= 0 && h < H && d >= 0 && d < row_dw) ? s2d_lds[dh * pitch + d] : 0u;
+            if (++i == run_dw) { i = 0; if (++dh == s) { dh = 0; ++w2; } }
+        }
+        dst[o4] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+// grid: N * H2g workgroups, H2g = ceil((H+pad)/s) rows of blocks cover every image row
+template <bool V16>
+__global__ __launch_bounds__(256) void s2d_stage_unpack_kernel(const bf16_t *__restrict__ dx2, bf16_t *__restrict__ dx, int C, int H,
+                                                               int W, int pad, int s, int H2, int W2, int H2g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t s2d_lds[];
+    const int h2 = blockIdx.x % H2g;
+    const long long n = blockIdx.x / H2g;
+    const int row_dw = W * C / 2;
+    const int run_dw = s * C / 2;
+    const int in_dw = W2 * s * run_dw;
+    const bool have = h2 < H2;                       // beyond the last block row: zeros
+    if (have) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(dx2 + ((n * H2 + h2) * W2) * (long long)(s * s * C));
+        for (int i = threadIdx.x; i < in_dw / 4; i += 256) reinterpret_cast<uint4 *>(s2d_lds)[i] = src[i];
+    }
+    __syncthreads();
+    const int shift = pad * C / 2;
+    for (int dh = 0; dh < s; ++dh) {
+        const int h = h2 * s + dh - pad;
+        if (h < 0 || h >= H) continue;
+        uint32_t *dst = reinterpret_cast<uint32_t *>(dx + ((n * H + h) * W) * (long long)C);
+        constexpr int V = V16 ? 4 : 1;
+        for (int d0 = threadIdx.x * V; d0 < row_dw; d0 += 256 * V) {
+            int E = d0 + shift;
+            int w2 = E / run_dw, rem = E - w2 * run_dw;
+            uint32_t v[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                v[j] = (have && w2 < W2) ? s2d_lds[(w2 * s + dh) * run_dw + rem] : 0u;
+                if (++rem == run_dw) { rem = 0; ++w2; }
+            }
+            if (V16) *reinterpret_cast<uint4 *>(dst + d0) = make_uint4(v[0], v[V > 1 ? 1 : 0], v[V > 2 ? 2 : 0], v[V > 3 ? 3 : 0]);
+            else dst[d0] = v[0];
+        }
+    }
+}
+
 inline int ok() { return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH; }
 
 }  // namespace
@@ -238,6 +326,14 @@ static bool s2d_rows_aligned(const ConvShape &s, const S2DGeom &g)
     return g.Cq == s.C && (s.C % 2 == 0 || (s.W % 2 == 0 && s.pad % 2 == 0 && g.s % 2 == 0));
 }
 
+// both staging buffers (s image rows; one row of x2 blocks) fit the 64 KB of LDS a launch may ask for
+static bool s2d_stage_fits(const ConvShape &s, const S2DGeom &g)
+{
+    const size_t img = (size_t)g.s * (((size_t)s.W * s.C / 2 + 3) & ~(size_t)3) * 4;
+    const size_t blk = (size_t)g.W2 * g.C2 * 2;
+    return img <= 65536 && blk <= 65536 && ((size_t)s.W * s.C) % 2 == 0;
+}
+
 S2DGeom s2d_geom(const ConvShape &s)
 {
     S2DGeom g;
@@ -263,6 +359,18 @@ ConvShape s2d_shape(const ConvShape &s)
 int s2d_pack_x(const ConvShape &s, const void *x, void *x2, hipStream_t st)
 {
     const S2DGeom g = s2d_geom(s);
+    if (s2d_rows_aligned(s, g) && s2d_stage_fits(s, g) && (long long)s.N * g.H2 <= 0x7FFFFFFFll) {
+        const bool v16 = ((long long)s.W * s.C * 2) % 16 == 0 && ((uintptr_t)x % 16) == 0;
+        const size_t lds = (size_t)g.s * (((size_t)s.W * s.C / 2 + 3) & ~(size_t)3) * 4;
+        const dim3 grid((unsigned)(s.N * g.H2));
+        if (v16)
+            hipLaunchKernelGGL(s2d_stage_pack_kernel<true>, grid, dim3(256), lds, st, (const bf16_t *)x, (bf16_t *)x2, s.C, s.H, s.W,
+                               s.pad, g.s, g.H2, g.W2);
+        else
+            hipLaunchKernelGGL(s2d_stage_pack_kernel<false>, grid, dim3(256), lds, st, (const bf16_t *)x, (bf16_t *)x2, s.C, s.H, s.W,
+                               s.pad, g.s, g.H2, g.W2);
+        return ok();
+    }
     if (s2d_rows_aligned(s, g)) {
         const long long n_thr = (long long)s.N * g.H2 * g.W2 * g.s;
         if ((n_thr + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
@@ -290,6 +398,19 @@ int s2d_pack_w(const ConvShape &s, const void *w, void *w2, hipStream_t st)
 int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st)
 {
     const S2DGeom g = s2d_geom(s);
+    if (s2d_rows_aligned(s, g) && s2d_stage_fits(s, g) && (long long)s.N * ((s.H + s.pad + g.s - 1) / g.s) <= 0x7FFFFFFFll) {
+        const int H2g = (s.H + s.pad + g.s - 1) / g.s;
+        const bool v16 = ((long long)s.W * s.C * 2) % 16 == 0 && ((uintptr_t)dx % 16) == 0;
+        const size_t lds = (size_t)g.W2 * g.C2 * 2;
+        const dim3 grid((unsigned)(s.N * H2g));
+        if (v16)
+            hipLaunchKernelGGL(s2d_stage_unpack_kernel<true>, grid, dim3(256), lds, st, (const bf16_t *)dx2, (bf16_t *)dx, s.C, s.H,
+                               s.W, s.pad, g.s, g.H2, g.W2, H2g);
+        else
+            hipLaunchKernelGGL(s2d_stage_unpack_kernel<false>, grid, dim3(256), lds, st, (const bf16_t *)dx2, (bf16_t *)dx, s.C, s.H,
+                               s.W, s.pad, g.s, g.H2, g.W2, H2g);
+        return ok();
+    }
     if (s2d_rows_aligned(s, g)) {
         const int H2g = (s.H + s.pad + g.s - 1) / g.s, W2g = (s.W + s.pad + g.s - 1) / g.s;
         const long long n_thr = (long long)s.N * H2g * W2g * g.s;
