@@ -443,10 +443,9 @@ Plan make_plan(const WgradGeom &g)
     for (int t = 0; t < N_TILES; ++t) {
         if (forced >= 0 && t != forced) continue;
         const WgradTile &tc = kTiles[t];
-        // no tile dimension more than twice the problem's (a 256-wide tile needs at least 256 rows/columns)
-        if (forced < 0 && ((tc.bm > 64 && tc.bm > g.K) || (tc.bn > 64 && tc.bn > RSC) || (tc.bm == 256 && g.K < 256) ||
-                           (tc.bn == 256 && RSC < 256)))
-            continue;
+        // no tile dimension (beyond 64) more than a third larger than the problem's: past that the padding
+        // rows cost more than the larger tile gains
+        if (forced < 0 && ((tc.bm > 64 && tc.bm * 3 > g.K * 4) || (tc.bn > 64 && tc.bn * 3 > RSC * 4))) continue;
         const int k_tiles = (g.K + tc.bm - 1) / tc.bm, n_tiles = (RSC + tc.bn - 1) / tc.bn;
         const long long tiles = (long long)k_tiles * n_tiles;
         const long long slots = 256LL * tc.slots;
