@@ -45,7 +45,7 @@ def algorithmic_bytes(L, op, esize):
 class LayerState:
     """Device tensors of one layer, NHWC/KRSC resident, plus workspaces."""
 
-    def __init__(self, mxc, torch, cfg, li, gen):
+    def __init__(self, mxc, torch, cfg, li, gen, layout="nhwc"):
         L, t = gen.layer_inputs(cfg, li)
         self.L = L
         self.dims = L.dims()
@@ -53,23 +53,28 @@ class LayerState:
         td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
         dev = lambda a: gen.to_device(a, cfg.dtype)
         x_nchw = dev(t["x"])
-        self.x_nchw = x_nchw if li == 0 else None            # only the network input is converted in the step
-        self.x = x_nchw.view(L.N, L.C, L.H, L.W).permute(0, 2, 3, 1).contiguous().view(-1)
-        self.w = dev(t["w"]).view(L.K, L.C, L.R, L.S).permute(0, 2, 3, 1).contiguous().view(-1)
-        self.dy = dev(t["dy"]).view(L.N, L.K, L.P, L.Q).permute(0, 2, 3, 1).contiguous().view(-1)
+        self.lay = mxc.MXC_NHWC if layout == "nhwc" else mxc.MXC_NCHW
+        if layout == "nhwc":
+            self.x_nchw = x_nchw if li == 0 else None        # only the network input is converted in the step
+            self.x = x_nchw.view(L.N, L.C, L.H, L.W).permute(0, 2, 3, 1).contiguous().view(-1)
+            self.w = dev(t["w"]).view(L.K, L.C, L.R, L.S).permute(0, 2, 3, 1).contiguous().view(-1)
+            self.dy = dev(t["dy"]).view(L.N, L.K, L.P, L.Q).permute(0, 2, 3, 1).contiguous().view(-1)
+        else:                                                # operands stay NCHW / KCRS; every call converts inside
+            self.x_nchw = None
+            self.x, self.w, self.dy = x_nchw, dev(t["w"]), dev(t["dy"])
         del t
         self.y = torch.empty(L.N * L.K * L.P * L.Q, dtype=td, device="cuda")
         self.dx = torch.empty(L.N * L.C * L.H * L.W, dtype=td, device="cuda")
         self.dw = torch.empty(L.K * L.C * L.R * L.S, dtype=torch.float32, device="cuda")
         self.ws = {}
         for op in (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT):
-            self.ws[op] = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *self.dims, self.dt, mxc.MXC_NHWC))
+            self.ws[op] = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *self.dims, self.dt, self.lay))
 
 
 class Network:
-    def __init__(self, mxc, torch, gen, cfg):
-        self.mxc, self.torch, self.cfg = mxc, torch, cfg
-        self.layers = [LayerState(mxc, torch, cfg, li, gen) for li in range(len(cfg.layers))]
+    def __init__(self, mxc, torch, gen, cfg, layout="nhwc"):
+        self.mxc, self.torch, self.cfg, self.layout = mxc, torch, cfg, layout
+        self.layers = [LayerState(mxc, torch, cfg, li, gen, layout) for li in range(len(cfg.layers))]
         self.flops_per_step = 3 * sum(s.L.flops_per_pass for s in self.layers)
         self.esize = 2 if cfg.dtype == "bf16" else 4
 
@@ -79,15 +84,16 @@ class Network:
         out = []
         s0 = self.layers[0]
         L0 = s0.L
-        out.append(("layout", "layout", s0, lambda: m.mxc_layout_convert(
-            L0.N, L0.C, L0.H, L0.W, s0.dt, m.MXC_NCHW, m.MXC_NHWC, s0.x_nchw, s0.x)))
+        if self.layout == "nhwc":
+            out.append(("layout", "layout", s0, lambda: m.mxc_layout_convert(
+                L0.N, L0.C, L0.H, L0.W, s0.dt, m.MXC_NCHW, m.MXC_NHWC, s0.x_nchw, s0.x)))
         for s in self.layers:
             out.append((s.L.name, "fwd", s, lambda s=s: m.mxc_conv2d_fwd(
-                *s.dims, s.dt, m.MXC_NHWC, s.x, s.w, s.y, s.ws[m.MXC_FWD])))
+                *s.dims, s.dt, s.lay, s.x, s.w, s.y, s.ws[m.MXC_FWD])))
             out.append((s.L.name, "bwd_data", s, lambda s=s: m.mxc_conv2d_bwd_data(
-                *s.dims, s.dt, m.MXC_NHWC, s.dy, s.w, s.dx, s.ws[m.MXC_BWD_DATA])))
+                *s.dims, s.dt, s.lay, s.dy, s.w, s.dx, s.ws[m.MXC_BWD_DATA])))
             out.append((s.L.name, "bwd_weight", s, lambda s=s: m.mxc_conv2d_bwd_weight(
-                *s.dims, s.dt, m.MXC_NHWC, s.x, s.dy, s.dw, s.ws[m.MXC_BWD_WEIGHT])))
+                *s.dims, s.dt, s.lay, s.x, s.dy, s.dw, s.ws[m.MXC_BWD_WEIGHT])))
         return out
 
     def step(self):
@@ -95,8 +101,8 @@ class Network:
             fn()
 
 
-def time_steps(torch, net, steps, warmup):
-    calls = [c[3] for c in net.calls()]
+def time_steps(torch, net, steps, warmup, keep=lambda c: True):
+    calls = [c[3] for c in net.calls() if keep(c)]
     for _ in range(warmup):
         for fn in calls:
             fn()
@@ -107,6 +113,36 @@ def time_steps(torch, net, steps, warmup):
             fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps
+
+
+def measure_ceilings(torch, mxc):
+    """On-box ceilings beside the published ones: the matrix pipe running a register-resident bf16
+    MFMA loop (two workgroups of four waves per CU) and a plain device copy of 1 GiB."""
+    out = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    mxc.mxc_probe_mfma(512, 2000, out)
+    torch.cuda.synchronize()
+    e0.record()
+    flops = mxc.mxc_probe_mfma(512, 20000, out)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_tflops = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    n_el = 1 << 28                      # 2^28 fp32 = 1 GiB read + 1 GiB written
+    src = torch.ones(n_el, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    copy = lambda: mxc.mxc_layout_convert(1, 1, 1 << 14, 1 << 14, mxc.MXC_F32, mxc.MXC_NCHW, mxc.MXC_NCHW, src, dst)
+    copy()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        copy()
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2.0 * n_el * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst, out
+    torch.cuda.empty_cache()
+    return {"mfma_bf16_tflops_measured": round(mfma_tflops, 1), "copy_gbs_measured": round(copy_gbs, 1),
+            "note": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 waves/SIMD; 1 GiB device copy, read + write bytes"}
 
 
 def time_calls(torch, net, steps):
@@ -212,6 +248,9 @@ def main():
     ap.add_argument("--workload", default="alexnet_b128")
     ap.add_argument("--all", action="store_true", help="also time the other layer stacks (extra 'networks' field)")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
+    ap.add_argument("--layout", choices=["nhwc", "nchw"], default="nhwc",
+                    help="nhwc: tensors resident in the working layout, network input converted once per step (headline); "
+                         "nchw: every call takes NCHW/KCRS operands and converts inside (three extra HBM passes per call)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cpu-sample-batch", type=int, default=128)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -229,7 +268,7 @@ def main():
     torch.cuda.set_device(0)
 
     def run_one(cfg, steps, warmup):
-        net = Network(mxc, torch, gen, cfg)
+        net = Network(mxc, torch, gen, cfg, args.layout)
         sec = time_steps(torch, net, steps, warmup)
         per_call, ev_ms = time_calls(torch, net, steps)
         return net, sec, per_call, ev_ms
@@ -242,7 +281,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     cfg = gen.config_by_name(args.workload)
+    ceilings = measure_ceilings(torch, mxc)
     net, sec, per_call, ev_ms = run_one(cfg, args.steps, args.warmup)
+    # the same step without backward-data of the first layer, which a training run never needs
+    # (nothing consumes the gradient of the network input); reported beside the headline, labelled
+    first = net.layers[0]
+    sec_pruned = time_steps(torch, net, args.steps, args.warmup, keep=lambda c: not (c[1] == "bwd_data" and c[2] is first))
+    flops_pruned = net.flops_per_step - first.L.flops_per_pass
     value = net.flops_per_step / sec / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
     result = {
@@ -250,11 +295,22 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "layers": len(cfg.layers), "batch": cfg.layers[0].N, "layout": "nhwc-resident",
-                   "step": "layout(NCHW->NHWC of network input) + per layer fwd, bwd_data, bwd_weight"},
+        "config": {"workload": cfg.name, "layers": len(cfg.layers), "batch": cfg.layers[0].N,
+                   "layout": "nhwc-resident" if args.layout == "nhwc" else "nchw-per-call",
+                   "step": ("layout(NCHW->NHWC of network input) + " if args.layout == "nhwc" else "") +
+                           "per layer fwd, bwd_data, bwd_weight"},
         "frac_of_mfma_peak": round(value / peak, 4),
         "roofline": roofline_of(per_call, net, ev_ms),
+        "ceilings": ceilings,
+        "without_first_layer_bwd_data": {"value": round(flops_pruned / sec_pruned / 1e12, 3), "unit": "TFLOP/s",
+                                         "ms_per_step": round(sec_pruned * 1e3, 4)},
     }
+    if cfg.dtype == "bf16":
+        result["frac_of_measured_mfma"] = round(value / ceilings["mfma_bf16_tflops_measured"], 4)
+        if result["roofline"]["bound"] == "mfma":
+            result["roofline"]["frac_of_measured"] = round(result["roofline"]["achieved"] / ceilings["mfma_bf16_tflops_measured"], 4)
+    if result["roofline"]["bound"] == "hbm":
+        result["roofline"]["frac_of_measured"] = round(result["roofline"]["achieved"] / ceilings["copy_gbs_measured"], 4)
     if args.per_layer:
         for c in per_call:
             L = c["state"].L

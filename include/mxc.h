@@ -124,6 +124,19 @@ const char *mxc_last_variant(void);
 /* Library version as major*10000 + minor*100 + patch. */
 int mxc_version(void);
 
+/* Measurement aid (not part of the convolution path): enqueues one launch of a
+ * register-resident loop of bf16 matrix instructions (v_mfma_f32_32x32x16_bf16, fp32
+ * accumulate, no memory traffic) on `workgroups` workgroups of 256 threads, `iters`
+ * iterations of four instructions per wave, and stores in *flops (host memory) the number
+ * of floating-point operations that launch performs.  The caller times the launch; flops
+ * over time is the matrix-pipe ceiling of this device at its sustained clock, the
+ * "measured peak" that the benchmark reports beside the published one (the paper, Section 4,
+ * compares on measured speed only).  `out`: device buffer of at least workgroups*256 floats
+ * (16-byte aligned; receives values of no interest), caller-owned.  Errors: MXC_ERR_NULL,
+ * MXC_ERR_SHAPE (non-positive counts), MXC_ERR_WORKSPACE (out too small), MXC_ERR_ALIGN,
+ * MXC_ERR_LAUNCH. */
+int mxc_probe_mfma(int workgroups, int iters, void *out, size_t out_bytes, double *flops, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -345,4 +345,13 @@ const char *mxc_last_variant(void) { return g_variant; }
 
 int mxc_version(void) { return 100; }
 
+int mxc_probe_mfma(int workgroups, int iters, void *out, size_t out_bytes, double *flops, void *hip_stream)
+{
+    if (!out || !flops) return MXC_ERR_NULL;
+    if (workgroups <= 0 || iters <= 0) return MXC_ERR_SHAPE;
+    if (out_bytes < (size_t)workgroups * 256 * sizeof(float)) return MXC_ERR_WORKSPACE;
+    if (misaligned(out)) return MXC_ERR_ALIGN;
+    return probe_mfma(workgroups, iters, (float *)out, flops, (hipStream_t)hip_stream);
+}
+
 }  // extern "C"

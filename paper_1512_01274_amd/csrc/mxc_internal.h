@@ -40,6 +40,10 @@ int launch_transpose(const void *src, void *dst, int batch, int rows, int cols, 
                      hipStream_t stream);
 int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
 
+// ---- probe.hip: matrix-pipe ceiling measurement -------------------------------------
+// launches the register-resident MFMA loop; *flops = floating-point operations the launch performs
+int probe_mfma(int workgroups, int iters, float *out, double *flops, hipStream_t st);
+
 // ---- direct.hip: one-thread-per-output kernels, any shape, NHWC/KRSC --------
 int direct_fwd(const ConvShape &s, int dtype, const void *x, const void *w, void *y, hipStream_t st);
 int direct_bwd_data(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, hipStream_t st);

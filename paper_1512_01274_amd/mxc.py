@@ -37,6 +37,8 @@ _lib.mxc_last_variant.argtypes = []
 _lib.mxc_last_variant.restype = ctypes.c_char_p
 _lib.mxc_version.argtypes = []
 _lib.mxc_version.restype = _I
+_lib.mxc_probe_mfma.argtypes = [_I, _I, _VP, _SZ, ctypes.POINTER(ctypes.c_double), _VP]
+_lib.mxc_probe_mfma.restype = _I
 
 
 class MxcError(RuntimeError):
@@ -111,6 +113,16 @@ def mxc_layout_convert(n, c, h, w, dtype, src_layout, dst_layout, src, dst, stre
     rc = _lib.mxc_layout_convert(n, c, h, w, dtype, src_layout, dst_layout, _ptr(src), _ptr(dst), _stream(stream))
     if rc != MXC_OK:
         raise MxcError(rc)
+
+
+def mxc_probe_mfma(workgroups, iters, out, stream=None) -> float:
+    """Enqueue the matrix-pipe probe; returns the floating-point operations of that launch."""
+    flops = ctypes.c_double(0.0)
+    rc = _lib.mxc_probe_mfma(workgroups, iters, _ptr(out), out.numel() * out.element_size(), ctypes.byref(flops),
+                             _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+    return float(flops.value)
 
 
 def raw():

@@ -198,3 +198,15 @@ def test_error_codes_on_gpu(mxc):
     assert e.value.status == mxc.MXC_ERR_SHAPE
     torch.cuda.synchronize()
     assert (y == 5.0).all()
+
+
+# ---- the measurement aid ----------------------------------------------------------
+
+def test_mfma_probe(mxc):
+    out = torch.empty(8 * 256, dtype=torch.float32, device="cuda")
+    flops = mxc.mxc_probe_mfma(8, 10, out)
+    torch.cuda.synchronize()
+    assert flops == 8 * 4 * 10 * 4 * 2 * 32 * 32 * 16        # workgroups x waves x iterations x instructions x flops each
+    assert torch.isfinite(out).all()
+    with pytest.raises(mxc.MxcError):
+        mxc.mxc_probe_mfma(16, 10, out)                      # output buffer too small for 16 workgroups
