@@ -111,3 +111,49 @@ def test_full_size_sampled(mxc, oracle, ci, li):
     ref, den = oracle.conv2d_bwd_weight_at(x, dy, w.shape, st, pad, idx)
     _check("bwd_weight", _gather(dwt, _nchw_to_nhwc_index(idx, (K, C, R, S))), ref, den, False, L)
     torch.cuda.synchronize()
+
+
+def test_tensors_beyond_2gib(mxc, oracle):
+    """Maximum sizes: activation tensors of more than 2^31 bytes.  The matrix-core kernels address
+    operands with signed 32-bit byte offsets and decline such tensors; the call must then run on the
+    64-bit-indexed kernels and still be exact at sampled outputs, including the very last elements."""
+    dims = (1, 8, 11600, 11600, 8, 3, 3, 1, 1)
+    N, C, H, W, K, R, S, st, pad = dims
+    assert N * C * H * W * 2 > 2 ** 31
+    rng = np.random.Generator(np.random.Philox(key=gen.SEED + 77))
+    small = lambda shape: rng.integers(-8, 9, size=shape, dtype=np.int8).astype(np.float32) / 8.0   # bf16-exact
+    x, w, dy = small((N, C, H, W)), small((K, C, R, S)), small((N, K, H, W))
+    dt, lay = mxc.MXC_BF16, mxc.MXC_NHWC
+    tag = type("T", (), {"name": "beyond-2GiB " + str(dims)})
+
+    def nhwc(a):
+        d = gen.to_device(a, "bf16")
+        return d.view(*a.shape).permute(0, 2, 3, 1).contiguous().view(-1)
+
+    dx_, dw_, ddy_ = nhwc(x), nhwc(w), nhwc(dy)
+    ends = [0, 1, H // 2, H - 2, H - 1]
+
+    y = torch.full((N * K * H * W,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_FWD, *dims, dt, lay))
+    mxc.mxc_conv2d_fwd(*dims, dt, lay, dx_, dw_, y, ws)
+    assert "igemm" not in mxc.mxc_last_variant()
+    idx = _sample(rng, (N, K, H, W), ([0], [0, K - 1], ends, ends), 4096)
+    ref, den = oracle.conv2d_fwd_at(x, w, st, pad, idx)
+    _check("fwd", _gather(y, _nchw_to_nhwc_index(idx, (N, K, H, W))), ref, den, True, tag)
+    del y, ws
+
+    dx = torch.full((N * C * H * W,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_BWD_DATA, *dims, dt, lay))
+    mxc.mxc_conv2d_bwd_data(*dims, dt, lay, ddy_, dw_, dx, ws)
+    idx = _sample(rng, (N, C, H, W), ([0], [0, C - 1], ends, ends), 4096)
+    ref, den = oracle.conv2d_bwd_data_at(dy, w, x.shape, st, pad, idx)
+    _check("bwd_data", _gather(dx, _nchw_to_nhwc_index(idx, (N, C, H, W))), ref, den, True, tag)
+    del dx, ws
+
+    dwt = torch.full((K * C * R * S,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_BWD_WEIGHT, *dims, dt, lay))
+    mxc.mxc_conv2d_bwd_weight(*dims, dt, lay, dx_, ddy_, dwt, ws)
+    idx = np.unique(rng.integers(0, K * C * R * S, size=24, dtype=np.int64))
+    ref, den = oracle.conv2d_bwd_weight_at(x, dy, w.shape, st, pad, idx)
+    _check("bwd_weight", _gather(dwt, _nchw_to_nhwc_index(idx, (K, C, R, S))), ref, den, False, tag)
+    torch.cuda.synchronize()
