@@ -115,6 +115,40 @@ def time_steps(torch, net, steps, warmup, keep=lambda c: True):
     return (time.perf_counter() - t0) / steps
 
 
+def time_two_streams(torch, net, steps, warmup):
+    """The same step issued the way a dependency engine (paper Section 3.2) would: backward-weight
+    calls, which nothing in the step waits for, go to a second stream beside the forward /
+    backward-data chain.  Reported beside the headline, which stays a single in-order stream."""
+    calls = net.calls()
+    main = [c[3] for c in calls if c[1] != "bwd_weight"]
+    side = [c[3] for c in calls if c[1] == "bwd_weight"]
+    s_main, s_side = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def step():
+        fork = torch.cuda.Event()
+        fork.record(s_main)
+        s_side.wait_event(fork)
+        with torch.cuda.stream(s_side):
+            for fn in side:
+                fn()
+        with torch.cuda.stream(s_main):
+            for fn in main:
+                fn()
+        join = torch.cuda.Event()
+        join.record(s_side)
+        s_main.wait_event(join)
+
+    torch.cuda.synchronize()
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
 def measure_ceilings(torch, mxc):
     """On-box ceilings beside the published ones: the matrix pipe running a register-resident bf16
     MFMA loop (two workgroups of four waves per CU) and a plain device copy of 1 GiB."""
@@ -288,6 +322,7 @@ def main():
     first = net.layers[0]
     sec_pruned = time_steps(torch, net, args.steps, args.warmup, keep=lambda c: not (c[1] == "bwd_data" and c[2] is first))
     flops_pruned = net.flops_per_step - first.L.flops_per_pass
+    sec_two = time_two_streams(torch, net, args.steps, args.warmup)
     value = net.flops_per_step / sec / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
     result = {
@@ -304,6 +339,9 @@ def main():
         "ceilings": ceilings,
         "without_first_layer_bwd_data": {"value": round(flops_pruned / sec_pruned / 1e12, 3), "unit": "TFLOP/s",
                                          "ms_per_step": round(sec_pruned * 1e3, 4)},
+        "two_stream_schedule": {"value": round(net.flops_per_step / sec_two / 1e12, 3), "unit": "TFLOP/s",
+                                "ms_per_step": round(sec_two * 1e3, 4),
+                                "note": "backward-weight calls on a second stream; not the headline"},
     }
     if cfg.dtype == "bf16":
         result["frac_of_measured_mfma"] = round(value / ceilings["mfma_bf16_tflops_measured"], 4)

@@ -86,6 +86,10 @@ SWEEP = [
     (2, 20, 7, 8, 24, 3, 3, 2, 1),
     (1, 3, 22, 24, 8, 11, 11, 4, 2),    # space-to-depth with 4-byte aligned rows (dword copy path)
     (2, 4, 18, 21, 8, 5, 5, 2, 1),
+    (2, 3, 17, 16, 8, 7, 7, 2, 3),      # strided small-C with rows of whole 16-byte chunks: four column classes
+    (1, 4, 10, 12, 8, 3, 3, 2, 0),      # ... one class
+    (2, 1, 9, 16, 8, 5, 5, 4, 2),       # ... C == 1, stride 4: two classes
+    (1, 2, 8, 8, 16, 3, 3, 2, 1),       # ... C == 2
 ]
 
 
