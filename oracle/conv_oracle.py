@@ -154,3 +154,41 @@ def conv2d_bwd_weight_at(x, dy, w_shape, stride, pad, idx):
     P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
     x = _f32(x, (N, C, H, W)); dy = _f32(dy, (N, K, P, Q))
     return _at("orc_conv2d_bwd_weight_at", (N, C, H, W, K, R, S, stride, pad), x, dy, idx)
+
+
+# ---- convolution grouped with its neighbours (bias, ReLU) -----------------------------------
+# The paper groups operators into a single call where it can (Section 3.1, graph optimisation) and
+# builds networks as layer => Activation(relu) => layer (Section 2.1, symbol construction).  These
+# are the plain definitions of the grouped forms, built from the loop nests above with elementwise
+# numpy steps in float64; nothing is blocked or reordered.
+
+def conv2d_fwd_bias_act(x, w, bias, relu, stride, pad):
+    """a = act(conv(x, w) + bias[k]), act = max(0, .) when relu else identity.  Returns (a, D) with
+    D = sum |x||w| + |bias|, the magnitude the error metric divides by."""
+    bias = np.asarray(bias, dtype=np.float64)
+    K = np.asarray(w).shape[0]
+    if bias.shape != (K,):
+        raise ValueError("bias must have one entry per output channel")
+    z = conv2d_fwd(x, w, stride, pad) + bias[None, :, None, None]
+    den = conv2d_fwd(np.abs(x), np.abs(w), stride, pad) + np.abs(bias)[None, :, None, None]
+    return (np.maximum(z, 0.0) if relu else z), den
+
+
+def conv2d_bwd_data_relu(dy, w, x, stride, pad):
+    """Gradient with respect to the pre-activation that produced x = max(0, z):
+    dz = conv^T(dy, w) where x > 0, else 0 (the derivative of max(0, .) is taken as 0 at 0).
+    Returns (dz, D) with D = sum |dy||w| where x > 0, else 0."""
+    x = np.asarray(x)
+    g = conv2d_bwd_data(dy, w, x.shape, stride, pad)
+    den = conv2d_bwd_data(np.abs(dy), np.abs(w), x.shape, stride, pad)
+    keep = x > 0
+    return np.where(keep, g, 0.0), np.where(keep, den, 0.0)
+
+
+def bias_grad(dy):
+    """db[k] = sum over images and pixels of dy[n, k, p, q] (the derivative of z + bias[k] summed
+    over everything the bias is added to).  Returns (db, D) with D = sum |dy|."""
+    dy = np.asarray(dy, dtype=np.float64)
+    if dy.ndim != 4:
+        raise ValueError("dy must be N,K,P,Q")
+    return dy.sum(axis=(0, 2, 3)), np.abs(dy).sum(axis=(0, 2, 3))

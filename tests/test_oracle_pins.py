@@ -327,3 +327,85 @@ def test_config_shapes_match_benchmark_definition():
     assert sum(l.flops_per_pass for l in c["inception3a_b128"].layers) == pytest.approx(32.8e9, rel=2e-3)
     assert sum(l.flops_per_pass for l in c["resnet_bottleneck_b256"].layers) == pytest.approx(276.2e9, rel=2e-3)
     assert c["resnet_bottleneck_b256"].layers[3].P == 28
+
+
+# ---- convolution grouped with bias and ReLU ---------------------------------------------------
+
+FUSED_DIMS = [(2, 3, 7, 6, 4, 3, 3, 1, 1), (1, 5, 9, 9, 6, 3, 3, 2, 1), (2, 8, 5, 5, 8, 1, 1, 1, 0)]
+
+
+@pytest.mark.parametrize("dims", FUSED_DIMS)
+def test_fused_forms_against_torch_cpu_float64(oracle, dims):
+    """torch's conv2d with a bias argument, relu, and autograd through relu(conv(...)) are an
+    independent implementation of all three grouped forms."""
+    torch = pytest.importorskip("torch")
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy, _, _ = _case(dims, seed=21)
+    bias = _rand((K,), 22)
+    # the layer below produced x through a ReLU: make it non-negative with exact zeros
+    xin = np.maximum(x, 0.0).astype(np.float32)
+    tz = torch.tensor(xin, dtype=torch.float64, requires_grad=True)
+    tw = torch.tensor(w, dtype=torch.float64)
+    tb = torch.tensor(bias, dtype=torch.float64, requires_grad=True)
+    lin = torch.nn.functional.conv2d(tz, tw, tb, stride=st, padding=pad)
+    a, _ = oracle.conv2d_fwd_bias_act(xin, w, bias, True, st, pad)
+    z, _ = oracle.conv2d_fwd_bias_act(xin, w, bias, False, st, pad)
+    np.testing.assert_allclose(z, lin.detach().numpy(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(a, torch.relu(lin).detach().numpy(), rtol=1e-12, atol=1e-12)
+    # backward: x = relu(pre) with pre = x where positive (any negative value where x == 0)
+    pre = torch.tensor(np.where(xin > 0, xin, -1.0), dtype=torch.float64, requires_grad=True)
+    out = torch.nn.functional.conv2d(torch.relu(pre), tw, tb, stride=st, padding=pad)
+    out.backward(torch.tensor(dy, dtype=torch.float64))
+    dz, _ = oracle.conv2d_bwd_data_relu(dy, w, xin, st, pad)
+    np.testing.assert_allclose(dz, pre.grad.numpy(), rtol=1e-12, atol=1e-12)
+    db, _ = oracle.bias_grad(dy)
+    np.testing.assert_allclose(db, tb.grad.numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_fused_forward_closed_forms(oracle):
+    """Zero filter: the output is act(bias) everywhere.  Delta filter, zero bias: act(x)."""
+    x = _rand((2, 3, 6, 6), 31)
+    bias = np.array([-1.5, 0.0, 2.25, 0.5], dtype=np.float32)
+    a, den = oracle.conv2d_fwd_bias_act(x, np.zeros((4, 3, 3, 3), np.float32), bias, True, 1, 1)
+    assert np.array_equal(a, np.broadcast_to(np.maximum(bias, 0)[None, :, None, None].astype(np.float64), a.shape))
+    assert np.array_equal(den, np.broadcast_to(np.abs(bias)[None, :, None, None].astype(np.float64), den.shape))
+    w = np.zeros((3, 3, 1, 1), np.float32)
+    for c in range(3):
+        w[c, c, 0, 0] = 1.0
+    a, _ = oracle.conv2d_fwd_bias_act(x, w, np.zeros(3, np.float32), True, 1, 0)
+    assert np.array_equal(a, np.maximum(x, 0).astype(np.float64))
+    z, _ = oracle.conv2d_fwd_bias_act(x, w, np.zeros(3, np.float32), False, 1, 0)
+    assert np.array_equal(z, x.astype(np.float64))
+
+
+def test_relu_mask_special_cases(oracle):
+    """All-positive x: the masked gradient is the plain one.  All-zero x: it is zero.  A single
+    positive element keeps exactly that element."""
+    dims = (1, 4, 6, 6, 5, 3, 3, 1, 1)
+    x, w, dy, _, _ = _case(dims, seed=41)
+    plain = oracle.conv2d_bwd_data(dy, w, x.shape, 1, 1)
+    g, den = oracle.conv2d_bwd_data_relu(dy, w, np.abs(x) + 1.0, 1, 1)
+    assert np.array_equal(g, plain)
+    g, den = oracle.conv2d_bwd_data_relu(dy, w, np.zeros_like(x), 1, 1)
+    assert not g.any() and not den.any()
+    one = np.zeros_like(x)
+    one[0, 2, 3, 4] = 0.5
+    g, _ = oracle.conv2d_bwd_data_relu(dy, w, one, 1, 1)
+    assert g[0, 2, 3, 4] == plain[0, 2, 3, 4] and np.count_nonzero(g) <= 1
+    neg = -np.abs(x)
+    g, _ = oracle.conv2d_bwd_data_relu(dy, w, neg, 1, 1)
+    assert not g.any()
+
+
+def test_bias_grad_is_bwd_weight_of_a_ones_image(oracle):
+    """db equals the weight gradient of a 1x1 filter on an all-ones single-channel input: the
+    bias is such a filter's weight."""
+    dy = _rand((3, 5, 4, 6), 51)
+    db, den = oracle.bias_grad(dy)
+    ones = np.ones((3, 1, 4, 6), np.float32)
+    dw = oracle.conv2d_bwd_weight(ones, dy, (5, 1, 1, 1), 1, 0)
+    np.testing.assert_allclose(db, dw[:, 0, 0, 0], rtol=1e-13)
+    assert np.all(den >= np.abs(db))
+    # closed form: constant gradient
+    db, _ = oracle.bias_grad(np.full((2, 3, 4, 5), 0.25, np.float32))
+    assert np.array_equal(db, np.full(3, 0.25 * 2 * 4 * 5))
