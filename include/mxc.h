@@ -57,7 +57,8 @@ enum {
 
 enum { MXC_F32 = 0, MXC_BF16 = 1 };
 enum { MXC_NCHW = 0, MXC_NHWC = 1 };
-enum { MXC_FWD = 0, MXC_BWD_DATA = 1, MXC_BWD_WEIGHT = 2 };
+enum { MXC_FWD = 0, MXC_BWD_DATA = 1, MXC_BWD_WEIGHT = 2,
+       MXC_BWD_DATA_RELU = 3, MXC_BIAS_GRAD = 4 };   /* the last two: mxc_conv2d_workspace_bytes only */
 
 /*
  * Forward (the layer's "forward" evaluation, paper Section 2.1):
@@ -95,6 +96,46 @@ int mxc_conv2d_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int s
                           int dtype, int layout,
                           const void *x, const void *dy, void *dw,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Convolution grouped with the operations that follow it (the paper groups operators into a
+ * single call where it can, Section 3.1 "Graph Optimization", and chains layers as
+ * layer => Activation(relu) => layer, Section 2.1):
+ *   y[n,k,p,q] = act( forward(x, w)[n,k,p,q] + bias[k] ),   act(t) = max(0, t) if relu == 1, t if relu == 0.
+ * bias: K fp32 values in device memory (4-byte aligned), or NULL for no bias.  The sum is formed
+ * in fp32 and rounded once to `dtype`.  Everything else (layouts, workspace = that of MXC_FWD,
+ * ownership, errors) as mxc_conv2d_fwd; relu outside {0,1}: MXC_ERR_UNSUPPORTED.
+ */
+int mxc_conv2d_fwd_bias_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            int dtype, int layout,
+                            const void *x, const void *w, const float *bias, int relu, void *y,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward w.r.t. the input, grouped with the derivative of the ReLU that produced the input:
+ * with x = max(0, z) the output of the layer below,
+ *   dz[n,c,h,v] = backward_data(dy, w)[n,c,h,v]  if x[n,c,h,v] > 0,  else 0
+ * (the derivative of max(0, .) at 0 is taken as 0).  x: N*C*H*W elements of `dtype` in `layout`
+ * (read only); dz is written to dx.  Workspace: query with pass MXC_BWD_DATA_RELU.  Otherwise as
+ * mxc_conv2d_bwd_data.
+ */
+int mxc_conv2d_bwd_data_relu(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             int dtype, int layout,
+                             const void *dy, const void *w, const void *x, void *dx,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Gradient of the bias of mxc_conv2d_fwd_bias_act (derivative of forward + bias[k] in bias):
+ *   db[k] = sum_{n,p,q} dy[n,k,p,q]
+ * dy: N*K*P*Q elements of `dtype` in `layout` (NCHW: [N][K][P][Q]; NHWC: [N][P][Q][K]); db: K fp32
+ * values.  Summed in a fixed order (bit-identical from run to run).  Workspace: query
+ * mxc_conv2d_workspace_bytes with pass MXC_BIAS_GRAD (only N, K, P, Q matter: pass the layer's
+ * shape).  Errors: MXC_ERR_SHAPE, MXC_ERR_UNSUPPORTED, MXC_ERR_NULL, MXC_ERR_ALIGN,
+ * MXC_ERR_WORKSPACE, MXC_ERR_LAUNCH.
+ */
+int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout,
+                  const void *dy, float *db,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Workspace size in bytes that `pass` (MXC_FWD / MXC_BWD_DATA / MXC_BWD_WEIGHT)

@@ -69,12 +69,13 @@ ConvShape with_channels(const ConvShape &s, int C)
     return t;
 }
 
-int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *y, Carver &ws, hipStream_t st, bool dry)
+int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *y, const PostOp &post, Carver &ws, hipStream_t st,
+             bool dry)
 {
     const char *v = "";
     if (dtype == MXC_BF16 && s.C % 8 == 0 && igemm_fwd_supported(s)) {
         if (dry) return MXC_OK;
-        const int rc = igemm_fwd(s, x, w, y, st, &v);
+        const int rc = igemm_fwd(s, x, w, y, st, &v, post);
         set_variant("fwd", v);
         return rc;
     }
@@ -85,7 +86,7 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
         if (dry) return MXC_OK;
         MXC_TRY(s2d_pack_x(s, x, x2, st));
         MXC_TRY(s2d_pack_w(s, w, w2, st));
-        const int rc = igemm_fwd(s2, x2, w2, y, st, &v);
+        const int rc = igemm_fwd(s2, x2, w2, y, st, &v, post);
         set_variant("fwd", (std::string("s2d+") + v).c_str());
         return rc;
     }
@@ -96,7 +97,7 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
         if (dry) return MXC_OK;
         MXC_TRY(smallc_pack_x(s, x, xp, st));
         MXC_TRY(smallc_pack_w(s, w, wp, st));
-        const int rc = igemm_fwd_smallc(s, xp, wp, y, st, &v);
+        const int rc = igemm_fwd_smallc(s, xp, wp, y, st, &v, post);
         set_variant("fwd", (std::string("smallc+") + v).c_str());
         return rc;
     }
@@ -107,17 +108,17 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
         if (dry) return MXC_OK;
         MXC_TRY(pad_channels(x, xp, (long long)s.N * s.H * s.W, s.C, st));
         MXC_TRY(pad_channels(w, wp, (long long)s.K * s.R * s.S, s.C, st));
-        const int rc = igemm_fwd(with_channels(s, C8), xp, wp, y, st, &v);
+        const int rc = igemm_fwd(with_channels(s, C8), xp, wp, y, st, &v, post);
         set_variant("fwd", (std::string("chanpad+") + v).c_str());
         return rc;
     }
     if (dry) return MXC_OK;
     set_variant("fwd", "direct");
-    return direct_fwd(s, dtype, x, w, y, st);
+    return direct_fwd(s, dtype, x, w, y, st, post);
 }
 
-int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, Carver &ws, hipStream_t st,
-                  bool dry)
+int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, const PostOp &post, Carver &ws,
+                  hipStream_t st, bool dry)
 {
     if (dtype == MXC_BF16 && s.K % 8 == 0 && s2d_applicable(s) && igemm_bwd_data_supported(s2d_shape(s))) {
         const ConvShape s2 = s2d_shape(s);
@@ -128,7 +129,7 @@ int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, 
         MXC_TRY(s2d_pack_w(s, w, w2, st));
         MXC_TRY(igemm_bwd_data(s2, dy, w2, dx2, wt, st, &v));
         set_variant("bwd_data", (std::string("s2d+") + v).c_str());
-        return s2d_unpack_dx(s, dx2, dx, st);
+        return s2d_unpack_dx(s, dx2, dx, st, post.mask);      // the mask is applied where dx itself is written
     }
     if (dtype == MXC_BF16 && igemm_bwd_data_smallc_supported(s)) {
         size_t w2_bytes, dx4_bytes;
@@ -136,7 +137,7 @@ int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, 
         void *w2 = ws.take(w2_bytes), *dx4 = ws.take(dx4_bytes);
         if (dry) return MXC_OK;
         const char *v = "";
-        const int rc = igemm_bwd_data_smallc(s, dy, w, dx, w2, dx4, st, &v);
+        const int rc = igemm_bwd_data_smallc(s, dy, w, dx, w2, dx4, st, &v, post);
         set_variant("bwd_data", (std::string("smallc+") + v).c_str());
         return rc;
     }
@@ -144,13 +145,13 @@ int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, 
         void *wt = ws.take(igemm_bwd_data_workspace(s));
         if (dry) return MXC_OK;
         const char *v = "";
-        const int rc = igemm_bwd_data(s, dy, w, dx, wt, st, &v);
+        const int rc = igemm_bwd_data(s, dy, w, dx, wt, st, &v, post);
         set_variant("bwd_data", v);
         return rc;
     }
     if (dry) return MXC_OK;
     set_variant("bwd_data", "direct");
-    return direct_bwd_data(s, dtype, dy, w, dx, st);
+    return direct_bwd_data(s, dtype, dy, w, dx, st, post);
 }
 
 int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw, Carver &ws, hipStream_t st,
@@ -206,16 +207,16 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
 
 // ---- one driver per pass: handles the caller's layout ---------------------------
 
-int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a, const void *b, void *out, Carver &ws,
-             hipStream_t st, bool dry)
+int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a, const void *b, void *out, const PostOp &post,
+             Carver &ws, hipStream_t st, bool dry)
 {
     const int eb = (int)elem_size(dtype);
     const size_t nx = (size_t)s.N * s.C * s.H * s.W, nw = (size_t)s.K * s.C * s.R * s.S,
                  ny = (size_t)s.N * s.K * s.P * s.Q;
     if (layout == MXC_NHWC) {
         switch (pass) {
-        case MXC_FWD: return fwd_nhwc(s, dtype, a, b, out, ws, st, dry);
-        case MXC_BWD_DATA: return bwd_data_nhwc(s, dtype, a, b, out, ws, st, dry);
+        case MXC_FWD: return fwd_nhwc(s, dtype, a, b, out, post, ws, st, dry);
+        case MXC_BWD_DATA: return bwd_data_nhwc(s, dtype, a, b, out, post, ws, st, dry);
         default: return bwd_weight_nhwc(s, dtype, a, b, (float *)out, ws, st, dry);
         }
     }
@@ -226,17 +227,25 @@ int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a,
             MXC_TRY(launch_transpose(a, x2, s.N, s.C, s.H * s.W, eb, st));
             MXC_TRY(launch_transpose(b, w2, s.K, s.C, s.R * s.S, eb, st));
         }
-        MXC_TRY(fwd_nhwc(s, dtype, x2, w2, y2, ws, st, dry));
+        MXC_TRY(fwd_nhwc(s, dtype, x2, w2, y2, post, ws, st, dry));
         if (!dry) MXC_TRY(launch_transpose(y2, out, s.N, s.P * s.Q, s.K, eb, st));
         return MXC_OK;
     }
     if (pass == MXC_BWD_DATA) {
         void *dy2 = ws.take(ny * eb), *w2 = ws.take(nw * eb), *dx2 = ws.take(nx * eb);
+        // with_mask (not the pointer) decides the carve-out, so that the size query and the call agree
+        void *mask2 = post.mask != nullptr || post.relu ? ws.take(nx * eb) : nullptr;
+        PostOp post2 = post;
+        post2.relu = 0;
         if (!dry) {
             MXC_TRY(launch_transpose(a, dy2, s.N, s.K, s.P * s.Q, eb, st));
             MXC_TRY(launch_transpose(b, w2, s.K, s.C, s.R * s.S, eb, st));
+            if (post.mask != nullptr) {
+                MXC_TRY(launch_transpose(post.mask, mask2, s.N, s.C, s.H * s.W, eb, st));
+                post2.mask = mask2;
+            }
         }
-        MXC_TRY(bwd_data_nhwc(s, dtype, dy2, w2, dx2, ws, st, dry));
+        MXC_TRY(bwd_data_nhwc(s, dtype, dy2, w2, dx2, post2, ws, st, dry));
         if (!dry) MXC_TRY(launch_transpose(dx2, out, s.N, s.H * s.W, s.C, eb, st));
         return MXC_OK;
     }
@@ -251,18 +260,23 @@ int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a,
     return MXC_OK;
 }
 
+// `post.relu` doubles, for backward-data in dry runs, as "a mask will be given" (the mask pointer is
+// not known to the size query).
 int entry(int pass, int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
-          const void *a, const void *b, void *out, void *workspace, size_t workspace_bytes, void *hip_stream)
+          const void *a, const void *b, void *out, const PostOp &post, void *workspace, size_t workspace_bytes,
+          void *hip_stream)
 {
     ConvShape s;
     MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
     if (!a || !b || !out) return MXC_ERR_NULL;
-    if (misaligned(a) || misaligned(b) || misaligned(out) || misaligned(workspace)) return MXC_ERR_ALIGN;
+    if (misaligned(a) || misaligned(b) || misaligned(out) || misaligned(workspace) || misaligned(post.mask)) return MXC_ERR_ALIGN;
     Carver need(nullptr);
-    MXC_TRY(run_pass(pass, s, dtype, layout, nullptr, nullptr, nullptr, need, nullptr, true));
+    PostOp dry_post;
+    dry_post.relu = (post.mask != nullptr || post.relu) ? 1 : 0;
+    MXC_TRY(run_pass(pass, s, dtype, layout, nullptr, nullptr, nullptr, dry_post, need, nullptr, true));
     if (need.used > 0 && (!workspace || workspace_bytes < need.used)) return MXC_ERR_WORKSPACE;
     Carver ws(workspace);
-    return run_pass(pass, s, dtype, layout, a, b, out, ws, (hipStream_t)hip_stream, false);
+    return run_pass(pass, s, dtype, layout, a, b, out, post, ws, (hipStream_t)hip_stream, false);
 }
 
 }  // namespace
@@ -275,7 +289,7 @@ extern "C" {
 int mxc_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
                    const void *x, const void *w, void *y, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return entry(MXC_FWD, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, w, y, workspace, workspace_bytes,
+    return entry(MXC_FWD, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, w, y, PostOp(), workspace, workspace_bytes,
                  hip_stream);
 }
 
@@ -283,7 +297,7 @@ int mxc_conv2d_bwd_data(int N, int C, int H, int W, int K, int R, int S, int str
                         const void *dy, const void *w, void *dx, void *workspace, size_t workspace_bytes,
                         void *hip_stream)
 {
-    return entry(MXC_BWD_DATA, N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, dx, workspace, workspace_bytes,
+    return entry(MXC_BWD_DATA, N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, dx, PostOp(), workspace, workspace_bytes,
                  hip_stream);
 }
 
@@ -291,20 +305,74 @@ int mxc_conv2d_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int s
                           const void *x, const void *dy, void *dw, void *workspace, size_t workspace_bytes,
                           void *hip_stream)
 {
-    return entry(MXC_BWD_WEIGHT, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, workspace, workspace_bytes,
+    return entry(MXC_BWD_WEIGHT, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, PostOp(), workspace,
+                 workspace_bytes, hip_stream);
+}
+
+int mxc_conv2d_fwd_bias_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                            const void *x, const void *w, const float *bias, int relu, void *y, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    if (relu != 0 && relu != 1) return MXC_ERR_UNSUPPORTED;
+    if (bias != nullptr && ((uintptr_t)bias & 3u)) return MXC_ERR_ALIGN;
+    PostOp post;
+    post.bias = bias;
+    post.relu = relu;
+    // the forward pass's workspace does not depend on the grouped operations: query it as MXC_FWD
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (!x || !w || !y) return MXC_ERR_NULL;
+    if (misaligned(x) || misaligned(w) || misaligned(y) || misaligned(workspace)) return MXC_ERR_ALIGN;
+    Carver need(nullptr);
+    MXC_TRY(run_pass(MXC_FWD, s, dtype, layout, nullptr, nullptr, nullptr, PostOp(), need, nullptr, true));
+    if (need.used > 0 && (!workspace || workspace_bytes < need.used)) return MXC_ERR_WORKSPACE;
+    Carver ws(workspace);
+    return run_pass(MXC_FWD, s, dtype, layout, x, w, y, post, ws, (hipStream_t)hip_stream, false);
+}
+
+int mxc_conv2d_bwd_data_relu(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                             const void *dy, const void *w, const void *x, void *dx, void *workspace, size_t workspace_bytes,
+                             void *hip_stream)
+{
+    if (!x) return MXC_ERR_NULL;
+    PostOp post;
+    post.mask = x;
+    return entry(MXC_BWD_DATA, N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, dx, post, workspace, workspace_bytes,
                  hip_stream);
+}
+
+int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout, const void *dy, float *db, void *workspace,
+                  size_t workspace_bytes, void *hip_stream)
+{
+    if (N <= 0 || K <= 0 || P <= 0 || Q <= 0) return MXC_ERR_SHAPE;
+    if ((long double)N * K * P * Q >= 1099511627776.0L) return MXC_ERR_SHAPE;
+    if (dtype != MXC_F32 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
+    if (layout != MXC_NCHW && layout != MXC_NHWC) return MXC_ERR_UNSUPPORTED;
+    if (!dy || !db) return MXC_ERR_NULL;
+    if (misaligned(dy) || misaligned(db) || misaligned(workspace)) return MXC_ERR_ALIGN;
+    const size_t need = (size_t)bias_grad_parts(N, K, (long long)P * Q, layout) * K * sizeof(float);
+    if (!workspace || workspace_bytes < need) return MXC_ERR_WORKSPACE;
+    return bias_grad(N, K, (long long)P * Q, dtype, layout, dy, db, (float *)workspace, (hipStream_t)hip_stream);
 }
 
 int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                                int dtype, int layout, size_t *out_bytes)
 {
     if (!out_bytes) return MXC_ERR_NULL;
-    if (pass != MXC_FWD && pass != MXC_BWD_DATA && pass != MXC_BWD_WEIGHT) return MXC_ERR_UNSUPPORTED;
+    if (pass != MXC_FWD && pass != MXC_BWD_DATA && pass != MXC_BWD_WEIGHT && pass != MXC_BWD_DATA_RELU && pass != MXC_BIAS_GRAD)
+        return MXC_ERR_UNSUPPORTED;
     ConvShape s;
     const int rc = validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s);
     if (rc != MXC_OK) return rc;
+    if (pass == MXC_BIAS_GRAD) {
+        *out_bytes = align_up((size_t)bias_grad_parts(s.N, s.K, (long long)s.P * s.Q, layout) * s.K * sizeof(float), 256);
+        return MXC_OK;
+    }
     Carver need(nullptr);
-    const int rc2 = run_pass(pass, s, dtype, layout, nullptr, nullptr, nullptr, need, nullptr, true);
+    PostOp dry_post;
+    dry_post.relu = pass == MXC_BWD_DATA_RELU;
+    const int rc2 = run_pass(pass == MXC_BWD_DATA_RELU ? MXC_BWD_DATA : pass, s, dtype, layout, nullptr, nullptr, nullptr, dry_post,
+                             need, nullptr, true);
     if (rc2 != MXC_OK) return rc2;
     *out_bytes = need.used;
     return MXC_OK;

@@ -12,7 +12,7 @@ namespace {
 // y[n,p,q,k] = sum_{r,s,c} x[n,p*st-pad+r,q*st-pad+s,c] * w[k,r,s,c]
 template <typename T>
 __global__ __launch_bounds__(256) void direct_fwd_kernel(ConvShape s, const T *__restrict__ x, const T *__restrict__ w,
-                                                         T *__restrict__ y, size_t total)
+                                                         T *__restrict__ y, size_t total, const float *__restrict__ bias, int relu)
 {
     const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
@@ -33,13 +33,16 @@ __global__ __launch_bounds__(256) void direct_fwd_kernel(ConvShape s, const T *_
             for (int c = 0; c < s.C; ++c) acc = fmaf(load_f32(xp + c), load_f32(wp + c), acc);
         }
     }
+    if (bias != nullptr) acc += bias[k];
+    if (relu) acc = fmaxf(acc, 0.f);
     store_f32(y + gid, acc);
 }
 
 // dx[n,h,v,c] = sum over taps (r,s) with (h+pad-r)%st==0, (v+pad-s)%st==0, p,q in range, and k.
 template <typename T>
 __global__ __launch_bounds__(256) void direct_bwd_data_kernel(ConvShape s, const T *__restrict__ dy,
-                                                              const T *__restrict__ w, T *__restrict__ dx, size_t total)
+                                                              const T *__restrict__ w, T *__restrict__ dx, size_t total,
+                                                              const T *__restrict__ mask)
 {
     const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
@@ -65,6 +68,7 @@ __global__ __launch_bounds__(256) void direct_bwd_data_kernel(ConvShape s, const
             for (int k = 0; k < s.K; ++k) acc = fmaf(load_f32(dyp + k), load_f32(wp + (size_t)k * wk), acc);
         }
     }
+    if (mask != nullptr && !mask_keeps(mask + gid)) acc = 0.f;
     store_f32(dx + gid, acc);
 }
 
@@ -113,31 +117,31 @@ inline int ok() { return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUN
 
 }  // namespace
 
-int direct_fwd(const ConvShape &s, int dtype, const void *x, const void *w, void *y, hipStream_t st)
+int direct_fwd(const ConvShape &s, int dtype, const void *x, const void *w, void *y, hipStream_t st, const PostOp &post)
 {
     const size_t total = (size_t)s.N * s.P * s.Q * s.K;
     const size_t blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFFull) return MXC_ERR_SHAPE;
     if (dtype == MXC_BF16)
         hipLaunchKernelGGL(direct_fwd_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, st, s, (const bf16_t *)x,
-                           (const bf16_t *)w, (bf16_t *)y, total);
+                           (const bf16_t *)w, (bf16_t *)y, total, post.bias, post.relu);
     else
         hipLaunchKernelGGL(direct_fwd_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, s, (const float *)x,
-                           (const float *)w, (float *)y, total);
+                           (const float *)w, (float *)y, total, post.bias, post.relu);
     return ok();
 }
 
-int direct_bwd_data(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, hipStream_t st)
+int direct_bwd_data(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, hipStream_t st, const PostOp &post)
 {
     const size_t total = (size_t)s.N * s.H * s.W * s.C;
     const size_t blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFFull) return MXC_ERR_SHAPE;
     if (dtype == MXC_BF16)
         hipLaunchKernelGGL(direct_bwd_data_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, st, s,
-                           (const bf16_t *)dy, (const bf16_t *)w, (bf16_t *)dx, total);
+                           (const bf16_t *)dy, (const bf16_t *)w, (bf16_t *)dx, total, (const bf16_t *)post.mask);
     else
         hipLaunchKernelGGL(direct_bwd_data_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, s,
-                           (const float *)dy, (const float *)w, (float *)dx, total);
+                           (const float *)dy, (const float *)w, (float *)dx, total, (const float *)post.mask);
     return ok();
 }
 

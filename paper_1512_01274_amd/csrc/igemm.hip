@@ -48,6 +48,10 @@ struct IgemmParams {
     int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
     int m_tiles, n_tiles;
     unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
+    // applied to the accumulators before the store (all optional)
+    const float *bias;   // + bias[co]
+    int relu;            // max(0, .)
+    const bf16_t *mask;  // indexed like `out`: the stored value is 0 where mask <= 0
 };
 
 typedef __attribute__((address_space(3))) void *lds_vptr;
@@ -328,6 +332,18 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
         return ((long long)n * p.Ho + ((int)a * p.out_mul_h + p.out_off_h)) * p.Wo + ((int)b * p.out_mul_w + p.out_off_w);
     };
+    // bias of this lane's NI output columns (accumulator block j holds column j*32 + lane%32)
+    float bias_j[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int co = n0 + wave_n + j * 32 + frag_row;
+        bias_j[j] = (p.bias != nullptr && co < p.Co) ? p.bias[co] : 0.f;
+    }
+    auto finish = [&](float v, int j) -> bf16_t {
+        v += bias_j[j];
+        if (p.relu) v = fmaxf(v, 0.f);
+        return f32_to_bf16(v);
+    };
     if ((p.Co & 7) == 0) {
         // Through LDS, one 32-row block of the wave tile at a time, so that global stores are 16 bytes
         // per lane and a row's WN channels leave as one contiguous run.
@@ -348,7 +364,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
             for (int e = 0; e < 16; ++e)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    stg[(8 * (e >> 2) + 4 * frag_kg + (e & 3)) * WN + j * 32 + frag_row] = f32_to_bf16(acc[i][j][e]);
+                    stg[(8 * (e >> 2) + 4 * frag_kg + (e & 3)) * WN + j * 32 + frag_row] = finish(acc[i][j][e], j);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -357,8 +373,15 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
                 const int idx = k * 64 + lane;
                 const int r = idx / CPR, c = idx % CPR;
                 const int m = m0 + wave_m + i * 32 + r, co = n0 + wave_n + c * 8;
-                const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * WN + c * 8);
-                if (m < p.M && co < p.Co) *reinterpret_cast<uint4 *>(p.out + out_pixel(m) * p.Co + co) = v;
+                uint4 v = *reinterpret_cast<const uint4 *>(stg + r * WN + c * 8);
+                if (m < p.M && co < p.Co) {
+                    const long long off = out_pixel(m) * p.Co + co;
+                    if (p.mask != nullptr) {
+                        const uint4 mk = *reinterpret_cast<const uint4 *>(p.mask + off);
+                        v = make_uint4(mask_bf16x2(v.x, mk.x), mask_bf16x2(v.y, mk.y), mask_bf16x2(v.z, mk.z), mask_bf16x2(v.w, mk.w));
+                    }
+                    *reinterpret_cast<uint4 *>(p.out + off) = v;
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -371,11 +394,14 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
             for (int e = 0; e < 16; ++e) {
                 const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
                 if (m >= p.M) continue;
-                bf16_t *orow = p.out + out_pixel(m) * p.Co;
+                const long long orow = out_pixel(m) * p.Co;
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
                     const int co = n0 + wave_n + j * 32 + frag_row;
-                    if (co < p.Co) orow[co] = f32_to_bf16(acc[i][j][e]);
+                    if (co < p.Co) {
+                        const bool keep = p.mask == nullptr || mask_keeps(p.mask + orow + co);
+                        p.out[orow + co] = keep ? finish(acc[i][j][e], j) : (bf16_t)0;
+                    }
                 }
             }
         }
@@ -520,9 +546,10 @@ bool igemm_fwd_supported(const ConvShape &s)
                                          (long long)s.N * s.P * s.Q, s.H, s.W, s.pad + s.R + s.S + s.stride, s.R * s.S);
 }
 
-int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant)
+int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant, const PostOp &post)
 {
     IgemmParams p{};
+    p.bias = post.bias; p.relu = post.relu;
     p.in = (const bf16_t *)x; p.wm = (const bf16_t *)w; p.out = (bf16_t *)y;
     p.N = s.N; p.Hi = s.H; p.Wi = s.W; p.Ci = s.C; p.pix = s.C; p.Co = s.K;
     p.TR = s.R; p.TS = s.S; p.tstep_h = 1; p.tstep_w = 1;
@@ -543,10 +570,12 @@ bool igemm_fwd_smallc_supported(const ConvShape &s)
 
 // Forward for a small-C image packed by smallc_pack_x / smallc_pack_w: R taps (filter rows), each a
 // contiguous run of S*pix elements of the zero-bordered image.
-int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y, hipStream_t st, const char **variant)
+int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y, hipStream_t st, const char **variant,
+                     const PostOp &post)
 {
     const SmallCGeom g = smallc_geom(s);
     IgemmParams p{};
+    p.bias = post.bias; p.relu = post.relu;
     p.in = (const bf16_t *)xp; p.wm = (const bf16_t *)wp; p.out = (bf16_t *)y;
     p.N = s.N; p.Hi = g.Hp; p.Wi = g.Wp; p.Ci = g.run; p.pix = g.pix; p.Co = s.K;
     p.TR = s.R; p.TS = 1; p.tstep_h = 1; p.tstep_w = 1;
@@ -568,7 +597,7 @@ bool igemm_bwd_data_supported(const ConvShape &s)
 size_t igemm_bwd_data_workspace(const ConvShape &s) { return (size_t)s.K * s.R * s.S * s.C * sizeof(bf16_t); }
 
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
-                   const char **variant)
+                   const char **variant, const PostOp &post)
 {
     const int total = s.K * s.R * s.S * s.C;
     hipLaunchKernelGGL(repack_bwd_data_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
@@ -588,6 +617,7 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
             const int Mw = v_first < s.W ? (s.W - 1 - v_first) / s.stride + 1 : 0;
             IgemmParams p{};
             p.in = (const bf16_t *)dy; p.wm = (const bf16_t *)wt + wt_off; p.out = (bf16_t *)dx;
+            p.mask = (const bf16_t *)post.mask;
             p.N = s.N; p.Hi = s.P; p.Wi = s.Q; p.Ci = s.K; p.pix = s.K; p.Co = s.C;
             p.TR = TR; p.TS = TS; p.tstep_h = -1; p.tstep_w = -1;
             p.Mh = Mh; p.Mw = Mw;
@@ -667,7 +697,7 @@ __global__ __launch_bounds__(256) void smallc_bwd_pack_w_kernel(const bf16_t *__
 
 // dx[n][h][w][c] = dx4[n][h][w][c], c < C; dx4 rows are Wg*G pixels wide
 __global__ __launch_bounds__(256) void smallc_compact_kernel(const uint2 *__restrict__ dx4, bf16_t *__restrict__ dx, long long rows,
-                                                            int W, int W4, int C)
+                                                            int W, int W4, int C, const bf16_t *__restrict__ mask)
 {
     const long long total = rows * W;
     const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -676,10 +706,10 @@ __global__ __launch_bounds__(256) void smallc_compact_kernel(const uint2 *__rest
     const int wv = (int)(gid % W);
     const uint2 v = dx4[row * W4 + wv];
     bf16_t *d = dx + gid * C;
-    d[0] = (bf16_t)(v.x & 0xFFFF);
-    if (C > 1) d[1] = (bf16_t)(v.x >> 16);
-    if (C > 2) d[2] = (bf16_t)(v.y & 0xFFFF);
-    if (C > 3) d[3] = (bf16_t)(v.y >> 16);
+    const bf16_t e[4] = {(bf16_t)(v.x & 0xFFFF), (bf16_t)(v.x >> 16), (bf16_t)(v.y & 0xFFFF), (bf16_t)(v.y >> 16)};
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        if (c < C) d[c] = (mask == nullptr || mask_keeps(mask + gid * C + c)) ? e[c] : (bf16_t)0;
 }
 
 }  // namespace
@@ -703,7 +733,7 @@ void igemm_bwd_data_smallc_workspace(const ConvShape &s, size_t *w2_bytes, size_
 }
 
 int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, void *dx, void *w2, void *dx4, hipStream_t st,
-                          const char **variant)
+                          const char **variant, const PostOp &post)
 {
     const SmallCBwd g = smallc_bwd_geom(s);
     size_t w2_bytes, dx4_bytes;
@@ -736,7 +766,7 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, voi
     const long long blocks = (rows * s.W + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
     hipLaunchKernelGGL(smallc_compact_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint2 *)dx4, (bf16_t *)dx, rows,
-                       s.W, g.Wg * g.G, s.C);
+                       s.W, g.Wg * g.G, s.C, (const bf16_t *)post.mask);
     *variant = kTiles[tc].name;
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }

@@ -31,6 +31,24 @@ __device__ __forceinline__ float load_f32(const bf16_t *p) { return bf16_to_f32(
 __device__ __forceinline__ void store_f32(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_f32(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 
+// What the kernel that produces a result applies to it before the store (the grouped forms of the
+// convolution: see mxc_conv2d_fwd_bias_act / mxc_conv2d_bwd_data_relu).  Default: nothing.
+struct PostOp {
+    const float *bias = nullptr;   // forward: + bias[k], one fp32 value per output channel
+    int relu = 0;                  // forward: max(0, .) after the bias
+    const void *mask = nullptr;    // backward-data: result is 0 where mask <= 0; same shape, type and layout as dx
+};
+
+// keeps the halves of v (two bf16) whose mask half is > 0
+__device__ __forceinline__ uint32_t mask_bf16x2(uint32_t v, uint32_t m)
+{
+    const uint32_t lo = (int16_t)(m & 0xFFFFu) > 0 ? 0x0000FFFFu : 0u;
+    const uint32_t hi = (int16_t)(m >> 16) > 0 ? 0xFFFF0000u : 0u;
+    return v & (lo | hi);
+}
+__device__ __forceinline__ bool mask_keeps(const float *m) { return *m > 0.f; }
+__device__ __forceinline__ bool mask_keeps(const bf16_t *m) { return (int16_t)*m > 0; }
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline size_t elem_size(int dtype) { return dtype == MXC_BF16 ? 2 : 4; }
 
@@ -44,9 +62,14 @@ int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
 // launches the register-resident MFMA loop; *flops = floating-point operations the launch performs
 int probe_mfma(int workgroups, int iters, float *out, double *flops, hipStream_t st);
 
+// ---- bias.hip: bias gradient ------------------------------------------------------------
+int bias_grad_parts(long long N, int K, long long PQ, int layout);      // partial vectors of K floats the call needs as scratch
+int bias_grad(long long N, int K, long long PQ, int dtype, int layout, const void *dy, float *db, float *partial, hipStream_t st);
+
 // ---- direct.hip: one-thread-per-output kernels, any shape, NHWC/KRSC --------
-int direct_fwd(const ConvShape &s, int dtype, const void *x, const void *w, void *y, hipStream_t st);
-int direct_bwd_data(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, hipStream_t st);
+int direct_fwd(const ConvShape &s, int dtype, const void *x, const void *w, void *y, hipStream_t st, const PostOp &post = PostOp());
+int direct_bwd_data(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, hipStream_t st,
+                    const PostOp &post = PostOp());
 // partial: fp32 scratch of direct_bwd_weight_splits(s) * K*R*S*C floats
 int direct_bwd_weight_splits(const ConvShape &s);
 int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw,
@@ -54,17 +77,18 @@ int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *
 
 // ---- igemm.hip: bf16 MFMA implicit GEMM (NHWC/KRSC) ---------------------------
 bool igemm_fwd_supported(const ConvShape &s);
-int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant);
+int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant,
+              const PostOp &post = PostOp());
 bool igemm_bwd_data_supported(const ConvShape &s);
 size_t igemm_bwd_data_workspace(const ConvShape &s);   // bytes for the re-packed filter
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
-                   const char **variant);
+                   const char **variant, const PostOp &post = PostOp());
 
 // backward-data for C <= 4: G output columns form one GEMM row (see igemm.hip)
 bool igemm_bwd_data_smallc_supported(const ConvShape &s);
 void igemm_bwd_data_smallc_workspace(const ConvShape &s, size_t *w2_bytes, size_t *dx4_bytes);
 int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, void *dx, void *w2, void *dx4, hipStream_t st,
-                          const char **variant);
+                          const char **variant, const PostOp &post = PostOp());
 
 // ---- prep.hip: re-packing for channel counts that are not a multiple of 8 ---------
 // [rows][C] -> [rows][C8] (C8 = C rounded up to 8, new channels zero); bf16 only.
@@ -82,9 +106,10 @@ bool s2d_applicable(const ConvShape &s);
 ConvShape s2d_shape(const ConvShape &s);      // the equivalent stride-1 problem: x2[N][H2][W2][C2], w2[K][R2][S2][C2]
 int s2d_pack_x(const ConvShape &s, const void *x, void *x2, hipStream_t st);
 int s2d_pack_w(const ConvShape &s, const void *w, void *w2, hipStream_t st);
-int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st);
+int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st, const void *mask = nullptr);   // mask: see PostOp
 bool igemm_fwd_smallc_supported(const ConvShape &s);
-int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y, hipStream_t st, const char **variant);
+int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y, hipStream_t st, const char **variant,
+                     const PostOp &post = PostOp());
 
 // ---- wgrad.hip: bf16 MFMA backward-weight with split reduction ------------------
 // The problem as the kernel sees it: x[N][H][W][pix], dy[N][P][Q][K]; filter columns are TR*TS taps of

@@ -117,7 +117,8 @@ __global__ __launch_bounds__(256) void s2d_pack_w_kernel(const bf16_t *__restric
 
 // dx[n][h][w][c] = dx2[n][(h+pad)/s][(w+pad)/s][(((h+pad)%s)*s + (w+pad)%s)*Cq + c]; 0 where no window reaches
 __global__ __launch_bounds__(256) void s2d_unpack_dx_kernel(const bf16_t *__restrict__ dx2, bf16_t *__restrict__ dx, int N, int C,
-                                                            int H, int W, int pad, int s, int Cq, int C2, int H2, int W2)
+                                                            int H, int W, int pad, int s, int Cq, int C2, int H2, int W2,
+                                                            const bf16_t *__restrict__ mask)
 {
     const long long total = (long long)N * H * W;
     const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(256) void s2d_unpack_dx_kernel(const bf16_t *__rest
     const bool in = h2 < H2 && w2 < W2;
     const bf16_t *src = dx2 + (((long long)n * H2 + h2) * W2 + w2) * C2 + ((hp % s) * s + wp % s) * Cq;
     bf16_t *d = dx + gid * C;
-    for (int c = 0; c < C; ++c) d[c] = in ? src[c] : (bf16_t)0;
+    for (int c = 0; c < C; ++c) d[c] = (in && (mask == nullptr || mask_keeps(mask + gid * C + c))) ? src[c] : (bf16_t)0;
 }
 
 // Fast space-to-depth copy for C == Cq when every run of s*C elements (one source row piece of a
@@ -142,7 +143,8 @@ __global__ __launch_bounds__(256) void s2d_unpack_dx_kernel(const bf16_t *__rest
 //         reaches) deliver zeros.  The grid covers ceil((H+pad)/s) x ceil((W+pad)/s) blocks.
 template <bool PACK>
 __global__ __launch_bounds__(256) void s2d_rows_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int N, int C, int H,
-                                                       int W, int pad, int s, int H2, int W2, int H2g, int W2g)
+                                                       int W, int pad, int s, int H2, int W2, int H2g, int W2g,
+                                                       const bf16_t *__restrict__ mask)
 {
     const long long total = (long long)N * H2g * W2g * s;
     const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -176,11 +178,13 @@ __global__ __launch_bounds__(256) void s2d_rows_kernel(const bf16_t *__restrict_
         if (inside && blk_ok) {
             const uint32_t *a = reinterpret_cast<const uint32_t *>(src + blk);
             uint32_t *b = reinterpret_cast<uint32_t *>(dst + img);
-            for (int i = 0; i < run / 2; ++i) b[i] = a[i];
+            const uint32_t *mk = reinterpret_cast<const uint32_t *>(mask + img);
+            for (int i = 0; i < run / 2; ++i) b[i] = mask == nullptr ? a[i] : mask_bf16x2(a[i], mk[i]);
         } else {
             for (int e = 0; e < run; ++e) {
                 const int w = w0 + e / C;
-                if (w >= 0 && w < W) dst[img + e] = blk_ok ? src[blk + e] : (bf16_t)0;
+                if (w >= 0 && w < W)
+                    dst[img + e] = (blk_ok && (mask == nullptr || mask_keeps(mask + img + e))) ? src[blk + e] : (bf16_t)0;
             }
         }
     }
@@ -239,7 +243,8 @@ __global__ __launch_bounds__(256) void s2d_stage_pack_kernel(const bf16_t *__res
 // grid: N * H2g workgroups, H2g = ceil((H+pad)/s) rows of blocks cover every image row
 template <bool V16>
 __global__ __launch_bounds__(256) void s2d_stage_unpack_kernel(const bf16_t *__restrict__ dx2, bf16_t *__restrict__ dx, int C, int H,
-                                                               int W, int pad, int s, int H2, int W2, int H2g)
+                                                               int W, int pad, int s, int H2, int W2, int H2g,
+                                                               const bf16_t *__restrict__ mask)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t s2d_lds[];
     const int h2 = blockIdx.x % H2g;
@@ -258,6 +263,7 @@ __global__ __launch_bounds__(256) void s2d_stage_unpack_kernel(const bf16_t *__r
         const int h = h2 * s + dh - pad;
         if (h < 0 || h >= H) continue;
         uint32_t *dst = reinterpret_cast<uint32_t *>(dx + ((n * H + h) * W) * (long long)C);
+        const uint32_t *mk = reinterpret_cast<const uint32_t *>(mask + ((n * H + h) * W) * (long long)C);
         constexpr int V = V16 ? 4 : 1;
         for (int d0 = threadIdx.x * V; d0 < row_dw; d0 += 256 * V) {
             int E = d0 + shift;
@@ -266,6 +272,7 @@ __global__ __launch_bounds__(256) void s2d_stage_unpack_kernel(const bf16_t *__r
 #pragma unroll
             for (int j = 0; j < V; ++j) {
                 v[j] = (have && w2 < W2) ? s2d_lds[(w2 * s + dh) * run_dw + rem] : 0u;
+                if (mask != nullptr) v[j] = mask_bf16x2(v[j], mk[d0 + j]);
                 if (++rem == run_dw) { rem = 0; ++w2; }
             }
             if (V16) *reinterpret_cast<uint4 *>(dst + d0) = make_uint4(v[0], v[V > 1 ? 1 : 0], v[V > 2 ? 2 : 0], v[V > 3 ? 3 : 0]);
@@ -375,7 +382,7 @@ int s2d_pack_x(const ConvShape &s, const void *x, void *x2, hipStream_t st)
         const long long n_thr = (long long)s.N * g.H2 * g.W2 * g.s;
         if ((n_thr + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
         hipLaunchKernelGGL(s2d_rows_kernel<true>, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, (const bf16_t *)x,
-                           (bf16_t *)x2, s.N, s.C, s.H, s.W, s.pad, g.s, g.H2, g.W2, g.H2, g.W2);
+                           (bf16_t *)x2, s.N, s.C, s.H, s.W, s.pad, g.s, g.H2, g.W2, g.H2, g.W2, (const bf16_t *)nullptr);
         return ok();
     }
     const long long total = (long long)s.N * g.H2 * g.W2 * g.s * g.s;
@@ -395,7 +402,7 @@ int s2d_pack_w(const ConvShape &s, const void *w, void *w2, hipStream_t st)
     return ok();
 }
 
-int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st)
+int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st, const void *mask)
 {
     const S2DGeom g = s2d_geom(s);
     if (s2d_rows_aligned(s, g) && s2d_stage_fits(s, g) && (long long)s.N * ((s.H + s.pad + g.s - 1) / g.s) <= 0x7FFFFFFFll) {
@@ -405,10 +412,10 @@ int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st)
         const dim3 grid((unsigned)(s.N * H2g));
         if (v16)
             hipLaunchKernelGGL(s2d_stage_unpack_kernel<true>, grid, dim3(256), lds, st, (const bf16_t *)dx2, (bf16_t *)dx, s.C, s.H,
-                               s.W, s.pad, g.s, g.H2, g.W2, H2g);
+                               s.W, s.pad, g.s, g.H2, g.W2, H2g, (const bf16_t *)mask);
         else
             hipLaunchKernelGGL(s2d_stage_unpack_kernel<false>, grid, dim3(256), lds, st, (const bf16_t *)dx2, (bf16_t *)dx, s.C, s.H,
-                               s.W, s.pad, g.s, g.H2, g.W2, H2g);
+                               s.W, s.pad, g.s, g.H2, g.W2, H2g, (const bf16_t *)mask);
         return ok();
     }
     if (s2d_rows_aligned(s, g)) {
@@ -416,14 +423,14 @@ int s2d_unpack_dx(const ConvShape &s, const void *dx2, void *dx, hipStream_t st)
         const long long n_thr = (long long)s.N * H2g * W2g * g.s;
         if ((n_thr + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
         hipLaunchKernelGGL(s2d_rows_kernel<false>, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, (const bf16_t *)dx2,
-                           (bf16_t *)dx, s.N, s.C, s.H, s.W, s.pad, g.s, g.H2, g.W2, H2g, W2g);
+                           (bf16_t *)dx, s.N, s.C, s.H, s.W, s.pad, g.s, g.H2, g.W2, H2g, W2g, (const bf16_t *)mask);
         return ok();
     }
     const long long total = (long long)s.N * s.H * s.W;
     const long long blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
     hipLaunchKernelGGL(s2d_unpack_dx_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)dx2, (bf16_t *)dx, s.N, s.C,
-                       s.H, s.W, s.pad, g.s, g.Cq, g.C2, g.H2, g.W2);
+                       s.H, s.W, s.pad, g.s, g.Cq, g.C2, g.H2, g.W2, (const bf16_t *)mask);
     return ok();
 }
 

@@ -15,7 +15,7 @@ MXC_OK = 0
 MXC_ERR_NULL, MXC_ERR_SHAPE, MXC_ERR_UNSUPPORTED, MXC_ERR_WORKSPACE, MXC_ERR_ALIGN, MXC_ERR_LAUNCH = 1, 2, 3, 4, 5, 6
 MXC_F32, MXC_BF16 = 0, 1
 MXC_NCHW, MXC_NHWC = 0, 1
-MXC_FWD, MXC_BWD_DATA, MXC_BWD_WEIGHT = 0, 1, 2
+MXC_FWD, MXC_BWD_DATA, MXC_BWD_WEIGHT, MXC_BWD_DATA_RELU, MXC_BIAS_GRAD = 0, 1, 2, 3, 4
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmxc.so")
 if not os.path.exists(LIB_PATH):
@@ -37,6 +37,12 @@ _lib.mxc_last_variant.argtypes = []
 _lib.mxc_last_variant.restype = ctypes.c_char_p
 _lib.mxc_version.argtypes = []
 _lib.mxc_version.restype = _I
+_lib.mxc_conv2d_fwd_bias_act.argtypes = [_I] * 11 + [_VP, _VP, _VP, _I, _VP, _VP, _SZ, _VP]
+_lib.mxc_conv2d_fwd_bias_act.restype = _I
+_lib.mxc_conv2d_bwd_data_relu.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP, _VP, _SZ, _VP]
+_lib.mxc_conv2d_bwd_data_relu.restype = _I
+_lib.mxc_bias_grad.argtypes = [_I] * 6 + [_VP, _VP, _VP, _SZ, _VP]
+_lib.mxc_bias_grad.restype = _I
 _lib.mxc_probe_mfma.argtypes = [_I, _I, _VP, _SZ, ctypes.POINTER(ctypes.c_double), _VP]
 _lib.mxc_probe_mfma.restype = _I
 
@@ -107,6 +113,35 @@ def mxc_conv2d_bwd_data(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, 
 
 def mxc_conv2d_bwd_weight(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, workspace=None, stream=None):
     _call(_lib.mxc_conv2d_bwd_weight, (N, C, H, W, K, R, S, stride, pad), dtype, layout, x, dy, dw, workspace, stream)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _ptr(workspace), workspace.numel() * workspace.element_size()
+
+
+def mxc_conv2d_fwd_bias_act(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, w, bias, relu, y, workspace=None, stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_conv2d_fwd_bias_act(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(x), _ptr(w), _ptr(bias), int(relu),
+                                      _ptr(y), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_conv2d_bwd_data_relu(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, x, dx, workspace=None, stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_conv2d_bwd_data_relu(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(dy), _ptr(w), _ptr(x), _ptr(dx),
+                                       ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_bias_grad(N, K, P, Q, dtype, layout, dy, db, workspace=None, stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_bias_grad(N, K, P, Q, dtype, layout, _ptr(dy), _ptr(db), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
 
 
 def mxc_layout_convert(n, c, h, w, dtype, src_layout, dst_layout, src, dst, stream=None):

@@ -214,3 +214,97 @@ def test_mfma_probe(mxc):
     assert torch.isfinite(out).all()
     with pytest.raises(mxc.MxcError):
         mxc.mxc_probe_mfma(16, 10, out)                      # output buffer too small for 16 workgroups
+
+
+# ---- convolution grouped with bias / ReLU / the ReLU derivative; bias gradient ----------------
+
+FUSED_SHAPES = [
+    (2, 16, 10, 11, 24, 3, 3, 1, 1),      # plain matrix-core path, ragged tiles
+    (2, 24, 9, 9, 40, 1, 1, 2, 0),        # strided backward-data: zero-filled classes stay zero under the mask
+    (1, 3, 22, 24, 8, 11, 11, 4, 2),      # space-to-depth: mask applied by the unpack kernel (16-byte rows)
+    (1, 3, 35, 35, 8, 11, 11, 4, 2),      # ... per-pixel unpack
+    (1, 2, 12, 15, 8, 5, 5, 2, 2),        # ... dword rows
+    (2, 3, 13, 11, 16, 3, 3, 1, 1),       # small-C stride 1: mask applied by the compaction kernel
+    (1, 12, 9, 9, 16, 3, 3, 1, 1),        # channel-padded forward
+    (2, 5, 13, 13, 7, 5, 5, 1, 2),        # direct kernels
+    (1, 136, 6, 5, 264, 3, 3, 1, 1),
+]
+
+
+def _fused_case(dims, dtype, seed):
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy = gen.random_case(seed, *dims, dtype=dtype, dist="normal")
+    x = np.maximum(x, 0.0).astype(np.float32)          # the layer below ended in a ReLU: exact zeros and positives
+    rng = np.random.Generator(np.random.Philox(key=seed + 99))
+    bias = rng.standard_normal(K).astype(np.float32)
+    return x, w, dy, bias
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+@pytest.mark.parametrize("dims", FUSED_SHAPES)
+def test_grouped_operations(mxc, oracle, dims, dtype, layout):
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy, bias = _fused_case(dims, dtype, hash(dims) & 0xFFFF)
+    run = util.Runner(mxc, dims, dtype, layout)
+    P, Q = run.P, run.Q
+    tb = torch.from_numpy(bias).cuda()
+    for relu in (1, 0):
+        ref, den = oracle.conv2d_fwd_bias_act(x, w, bias, bool(relu), st, pad)
+        y = torch.full((N * K * P * Q,), float("nan"), dtype=run.tdtype, device="cuda")
+        mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, run._in(x), run._in(w), tb, relu, y, run._ws(mxc.MXC_FWD))
+        got = run._out(y, (N, K, P, Q))
+        assert util.metric(got, ref, den) <= util.TOL[dtype], (dims, relu, mxc.mxc_last_variant())
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, dtype, dtype == "bf16")), (dims, relu)
+        if relu:
+            assert got.min() >= 0.0
+    # no bias, no activation: bit-identical to the plain forward
+    y0 = run.fwd(x, w, return_tensor=True)
+    y1 = torch.empty_like(y0)
+    mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, run._in(x), run._in(w), None, 0, y1, run._ws(mxc.MXC_FWD))
+    assert torch.equal(y0.view(torch.int16 if dtype == "bf16" else torch.int32), y1.view(torch.int16 if dtype == "bf16" else torch.int32))
+
+    ref, den = oracle.conv2d_bwd_data_relu(dy, w, x, st, pad)
+    dx = torch.full((N * C * H * W,), float("nan"), dtype=run.tdtype, device="cuda")
+    mxc.mxc_conv2d_bwd_data_relu(*dims, run.dt, run.lay, run._in(dy), run._in(w), run._in(x), dx, run._ws(mxc.MXC_BWD_DATA_RELU))
+    got = run._out(dx, (N, C, H, W))
+    assert util.metric(got, ref, den) <= util.TOL[dtype], (dims, mxc.mxc_last_variant())
+    assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, dtype, dtype == "bf16")), dims
+    assert not got[x <= 0].any()
+
+    ref, den = oracle.bias_grad(dy)
+    db = torch.full((K,), float("nan"), dtype=torch.float32, device="cuda")
+    mxc.mxc_bias_grad(N, K, P, Q, run.dt, run.lay, run._in(dy), db, run._ws(mxc.MXC_BIAS_GRAD))
+    got = db.cpu().numpy().astype(np.float64)
+    assert util.metric(got, ref, den) <= util.TOL["f32"], dims      # fp32 sums of exact inputs
+    db2 = torch.empty_like(db)
+    mxc.mxc_bias_grad(N, K, P, Q, run.dt, run.lay, run._in(dy), db2, run._ws(mxc.MXC_BIAS_GRAD))
+    assert torch.equal(db.view(torch.int32), db2.view(torch.int32))
+
+
+@pytest.mark.parametrize("cfg_idx", [1, 3])
+def test_grouped_operations_network_layers(mxc, oracle, cfg_idx):
+    """The bench's launch configuration (bf16, NHWC) on every layer of the AlexNet- and VGG-style stacks, batch 2."""
+    cfg = gen.CONFIGS[cfg_idx]
+    for li in range(len(cfg.layers)):
+        L, t = gen.layer_inputs(cfg, li, batch=1 if cfg.layers[li].H >= 112 else 2)
+        dims = L.dims()
+        N, C, H, W, K, R, S, st, pad = dims
+        x = np.maximum(t["x"], 0.0).astype(np.float32)
+        w, dy = t["w"], t["dy"]
+        bias = np.linspace(-1.0, 1.0, K).astype(np.float32)
+        run = util.Runner(mxc, dims, "bf16", "nhwc")
+        ref, den = oracle.conv2d_fwd_bias_act(x, w, bias, True, st, pad)
+        y = torch.full((N * K * L.P * L.Q,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, run._in(x), run._in(w), torch.from_numpy(bias).cuda(), 1, y, run._ws(mxc.MXC_FWD))
+        got = run._out(y, (N, K, L.P, L.Q))
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), L.name
+        ref, den = oracle.conv2d_bwd_data_relu(dy, w, x, st, pad)
+        dx = torch.full((N * C * H * W,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_bwd_data_relu(*dims, run.dt, run.lay, run._in(dy), run._in(w), run._in(x), dx, run._ws(mxc.MXC_BWD_DATA_RELU))
+        got = run._out(dx, (N, C, H, W))
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), L.name
+        ref, den = oracle.bias_grad(dy)
+        db = torch.empty(K, dtype=torch.float32, device="cuda")
+        mxc.mxc_bias_grad(N, K, L.P, L.Q, run.dt, run.lay, run._in(dy), db, run._ws(mxc.MXC_BIAS_GRAD))
+        assert util.metric(db.cpu().numpy().astype(np.float64), ref, den) <= util.TOL["f32"], L.name
