@@ -26,26 +26,55 @@ __global__ __launch_bounds__(BG_THREADS) void bias_grad_rows_kernel(const T *__r
     }
 }
 
-// NHWC with few channels (K <= 128, a power of two): a workgroup's threads form 256/K row groups so
-// that all lanes stay busy; the row groups are then added in LDS in a fixed order.
-template <typename T>
-__global__ __launch_bounds__(BG_THREADS) void bias_grad_rows_narrow_kernel(const T *__restrict__ dy, float *__restrict__ partial,
-                                                                           long long rows, int K, int rows_per_wg)
+// NHWC, K a multiple of VEC (16 bytes of elements) and at most 256*VEC: thread t owns the 16-byte
+// channel chunk t % (K/VEC) of the rows  r0 + t / (K/VEC) + i * groups;  four rows are in flight per
+// thread.  The row groups are then added in LDS in ascending order.
+template <typename T, int VEC>
+__global__ __launch_bounds__(BG_THREADS) void bias_grad_rows_vec_kernel(const T *__restrict__ dy, float *__restrict__ partial,
+                                                                        long long rows, int K, int rows_per_wg)
 {
-    __shared__ float red[BG_THREADS];
-    const int groups = BG_THREADS / K;
-    const int k = threadIdx.x % K, grp = threadIdx.x / K;
+    __shared__ float red[BG_THREADS * VEC];
+    const int chunks = K / VEC, groups = BG_THREADS / chunks;
+    const int chunk = threadIdx.x % chunks, grp = threadIdx.x / chunks;
     const long long r0 = (long long)blockIdx.x * rows_per_wg;
     long long r1 = r0 + rows_per_wg;
     if (r1 > rows) r1 = rows;
-    float acc = 0.f;
-    for (long long r = r0 + grp; r < r1; r += groups) acc += load_f32(dy + r * K + k);
-    red[threadIdx.x] = acc;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    auto add = [&](const uint4 &v) {
+        if constexpr (sizeof(T) == 2) {
+            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] += __uint_as_float(u[e] << 16);
+                acc[2 * e + 1] += __uint_as_float(u[e] & 0xFFFF0000u);
+            }
+        } else {
+            acc[0] += __uint_as_float(v.x); acc[1] += __uint_as_float(v.y);
+            acc[2] += __uint_as_float(v.z); acc[3] += __uint_as_float(v.w);
+        }
+    };
+    if (grp < groups) {
+        const uint4 *base = reinterpret_cast<const uint4 *>(dy) + chunk;      // row r: base[r * chunks]
+        long long r = r0 + grp;
+        for (; r + 3LL * groups < r1; r += 4LL * groups) {
+            const uint4 a = base[r * chunks], b = base[(r + groups) * chunks], c = base[(r + 2LL * groups) * chunks],
+                        d = base[(r + 3LL * groups) * chunks];
+            add(a); add(b); add(c); add(d);
+        }
+        for (; r < r1; r += groups) add(base[r * chunks]);
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) red[threadIdx.x * VEC + e] = acc[e];
     __syncthreads();
     if (grp == 0) {
-        float s = 0.f;
-        for (int g = 0; g < groups; ++g) s += red[g * K + k];
-        partial[(size_t)blockIdx.x * K + k] = s;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            float s = 0.f;
+            for (int g = 0; g < groups; ++g) s += red[(g * chunks + chunk) * VEC + e];
+            partial[(size_t)blockIdx.x * K + chunk * VEC + e] = s;
+        }
     }
 }
 
@@ -66,14 +95,24 @@ __global__ __launch_bounds__(BG_THREADS) void bias_grad_planes_kernel(const T *_
     if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
 }
 
+// db[k] = sum of the partial vectors, in a fixed order: a workgroup owns 32 columns; its 8 thread
+// groups each add every 8th partial vector, then the 8 sums are added in ascending order.
 __global__ __launch_bounds__(BG_THREADS) void bias_grad_sum_kernel(const float *__restrict__ partial, float *__restrict__ db, int K,
                                                                    int parts)
 {
-    const int k = blockIdx.x * BG_THREADS + threadIdx.x;
-    if (k >= K) return;
+    __shared__ float red[BG_THREADS];
+    const int col = threadIdx.x % 32, grp = threadIdx.x / 32;
+    const int k = blockIdx.x * 32 + col;
     float acc = 0.f;
-    for (int i = 0; i < parts; ++i) acc += partial[(size_t)i * K + k];
-    db[k] = acc;
+    if (k < K)
+        for (int i = grp; i < parts; i += BG_THREADS / 32) acc += partial[(size_t)i * K + k];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (grp == 0 && k < K) {
+        float s = 0.f;
+        for (int g = 0; g < BG_THREADS / 32; ++g) s += red[g * 32 + col];
+        db[k] = s;
+    }
 }
 
 inline int ok() { return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH; }
@@ -87,7 +126,7 @@ int bias_grad_parts(long long N, int K, long long PQ, int layout)
     (void)K;
     const long long rows = N * PQ;
     long long parts = (rows + 255) / 256;      // at least 256 rows per workgroup
-    if (parts > 2048) parts = 2048;
+    if (parts > 512) parts = 512;
     return (int)(parts < 1 ? 1 : parts);
 }
 
@@ -105,17 +144,18 @@ int bias_grad(long long N, int K, long long PQ, int dtype, int layout, const voi
     } else {
         const long long rows = N * PQ;
         const int rows_per_wg = (int)((rows + parts - 1) / parts);
-        const bool narrow = K <= 128 && (K & (K - 1)) == 0;
+        const int vec = dtype == MXC_BF16 ? 8 : 4;
+        const bool vector = K % vec == 0 && K / vec <= BG_THREADS;
         if (dtype == MXC_BF16) {
-            if (narrow)
-                hipLaunchKernelGGL(bias_grad_rows_narrow_kernel<bf16_t>, dim3((unsigned)parts), dim3(BG_THREADS), 0, st,
+            if (vector)
+                hipLaunchKernelGGL((bias_grad_rows_vec_kernel<bf16_t, 8>), dim3((unsigned)parts), dim3(BG_THREADS), 0, st,
                                    (const bf16_t *)dy, partial, rows, K, rows_per_wg);
             else
                 hipLaunchKernelGGL(bias_grad_rows_kernel<bf16_t>, dim3((unsigned)parts), dim3(BG_THREADS), 0, st, (const bf16_t *)dy,
                                    partial, rows, K, rows_per_wg);
         } else {
-            if (narrow)
-                hipLaunchKernelGGL(bias_grad_rows_narrow_kernel<float>, dim3((unsigned)parts), dim3(BG_THREADS), 0, st,
+            if (vector)
+                hipLaunchKernelGGL((bias_grad_rows_vec_kernel<float, 4>), dim3((unsigned)parts), dim3(BG_THREADS), 0, st,
                                    (const float *)dy, partial, rows, K, rows_per_wg);
             else
                 hipLaunchKernelGGL(bias_grad_rows_kernel<float>, dim3((unsigned)parts), dim3(BG_THREADS), 0, st, (const float *)dy,
@@ -123,8 +163,7 @@ int bias_grad(long long N, int K, long long PQ, int dtype, int layout, const voi
         }
     }
     if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
-    hipLaunchKernelGGL(bias_grad_sum_kernel, dim3((unsigned)((K + BG_THREADS - 1) / BG_THREADS)), dim3(BG_THREADS), 0, st, partial, db,
-                       K, parts);
+    hipLaunchKernelGGL(bias_grad_sum_kernel, dim3((unsigned)((K + 31) / 32)), dim3(BG_THREADS), 0, st, partial, db, K, parts);
     return ok();
 }
 
