@@ -192,3 +192,17 @@ def bias_grad(dy):
     if dy.ndim != 4:
         raise ValueError("dy must be N,K,P,Q")
     return dy.sum(axis=(0, 2, 3)), np.abs(dy).sum(axis=(0, 2, 3))
+
+
+# ---- the weight update that consumes dw ------------------------------------------------------
+# The paper writes the update as w = w - eta*g (Section 2.2) and trains with learning rate .05,
+# momentum .9 and weight decay 1e-4 (Section 4) without printing the momentum form; the reading
+# taken here is the classic one:  v' = mu*v - eta*(g + lambda*w),  w' = w + v'.
+
+def sgd_update(w, g, v, lr, momentum, wd):
+    """One update in float64.  Returns (w', v')."""
+    w = np.asarray(w, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    v = np.zeros_like(w) if v is None else np.asarray(v, dtype=np.float64)
+    v2 = momentum * v - lr * (g + wd * w)
+    return w + v2, v2

@@ -409,3 +409,25 @@ def test_bias_grad_is_bwd_weight_of_a_ones_image(oracle):
     # closed form: constant gradient
     db, _ = oracle.bias_grad(np.full((2, 3, 4, 5), 0.25, np.float32))
     assert np.array_equal(db, np.full(3, 0.25 * 2 * 4 * 5))
+
+
+# ---- weight update ------------------------------------------------------------------------------
+
+def test_sgd_update_closed_forms(oracle):
+    """mu = lambda = 0: the paper's w - eta*g.  Constant gradient with momentum: the velocity is a
+    geometric series.  Weight decay alone: geometric shrinkage."""
+    w0 = _rand((3, 4), 61).astype(np.float64)
+    g = _rand((3, 4), 62).astype(np.float64)
+    w1, v1 = oracle.sgd_update(w0, g, None, 0.125, 0.0, 0.0)
+    assert np.array_equal(w1, w0 - 0.125 * g) and np.array_equal(v1, -0.125 * g)
+    w, v = w0, None
+    mu, lr, T = 0.5, 0.25, 12
+    for _ in range(T):
+        w, v = oracle.sgd_update(w, g, v, lr, mu, 0.0)
+    np.testing.assert_allclose(v, -lr * g * (1 - mu ** T) / (1 - mu), rtol=1e-13)
+    # sum of the velocities: -lr*g/(1-mu) * (T - mu*(1-mu^T)/(1-mu))
+    np.testing.assert_allclose(w - w0, -lr * g / (1 - mu) * (T - mu * (1 - mu ** T) / (1 - mu)), rtol=1e-12)
+    w = w0
+    for _ in range(7):
+        w, _ = oracle.sgd_update(w, np.zeros_like(w0), None, 0.5, 0.0, 0.25)
+    np.testing.assert_allclose(w, w0 * (1 - 0.5 * 0.25) ** 7, rtol=1e-13)
