@@ -67,6 +67,8 @@ class LayerState:
         self.dx = torch.empty(L.N * L.C * L.H * L.W, dtype=td, device="cuda")
         self.dw = torch.empty(L.K * L.C * L.R * L.S, dtype=torch.float32, device="cuda")
         self.bias = torch.linspace(-0.5, 0.5, L.K, dtype=torch.float32, device="cuda")
+        self.w_master = self.w.float() if cfg.dtype == "bf16" else None     # fp32 master weights and velocity of the update
+        self.vel = torch.zeros_like(self.w_master) if cfg.dtype == "bf16" else None
         self.db = torch.empty(L.K, dtype=torch.float32, device="cuda")
         self.ws = {}
         for op in (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT, mxc.MXC_BWD_DATA_RELU, mxc.MXC_BIAS_GRAD):
@@ -116,6 +118,10 @@ class Network:
                 if op == "bwd_weight":
                     out.append((label, "bias_grad", s, lambda s=s: m.mxc_bias_grad(
                         s.L.N, s.L.K, s.L.P, s.L.Q, s.dt, s.lay, s.dy, s.db, s.ws[m.MXC_BIAS_GRAD])))
+                    if s.w_master is not None:
+                        # a learning rate small enough that the synthetic gradients leave the weights where they are
+                        out.append((label, "sgd_update", s, lambda s=s: m.mxc_sgd_update(
+                            s.w_master, s.dw, s.vel, s.w, 1e-9, 0.9, 1e-4)))
         return out
 
     def step(self):
@@ -365,7 +371,8 @@ def main():
         "grouped_operations": {"value": round(net.flops_per_step / sec_grouped / 1e12, 3), "unit": "TFLOP/s",
                                "ms_per_step": round(sec_grouped * 1e3, 4),
                                "note": "same convolution flops; forward + bias + ReLU, backward-data with the ReLU derivative, "
-                                       "backward-weight, bias gradient (the extra work is not counted as flops)"},
+                                       "backward-weight, bias gradient, SGD update of fp32 master weights with a bf16 copy "
+                                       "(the extra work is not counted as flops)"},
         "two_stream_schedule": {"value": round(net.flops_per_step / sec_two / 1e12, 3), "unit": "TFLOP/s",
                                 "ms_per_step": round(sec_two * 1e3, 4),
                                 "note": "backward-weight calls on a second stream; not the headline"},

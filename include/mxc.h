@@ -138,6 +138,21 @@ int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The weight update that consumes dw (the paper's  w = w - eta*g  of Section 2.2, with the
+ * momentum and weight decay of its Section 4 experiment; the paper does not print the momentum
+ * form, the classic one is used):
+ *   v'[i] = momentum*v[i] - lr*(g[i] + wd*w[i]),   w'[i] = w[i] + v'[i],   i < n
+ * w: fp32 master weights, updated in place; g: fp32 gradient (mxc_conv2d_bwd_weight's dw, same
+ * element order as w); v: fp32 velocity, updated in place, or NULL when momentum == 0 (then
+ * v = 0 is used and nothing is stored); w_bf16: if not NULL, receives w' rounded to bf16 (nearest
+ * even) for the next forward pass.  All device pointers, 16-byte aligned, caller-owned; n > 0.
+ * Errors: MXC_ERR_SHAPE (n == 0 or too large for one launch), MXC_ERR_NULL (w or g NULL, or v NULL
+ * with momentum != 0), MXC_ERR_ALIGN, MXC_ERR_LAUNCH.
+ */
+int mxc_sgd_update(size_t n, float *w, const float *g, float *v, void *w_bf16,
+                   float lr, float momentum, float wd, void *hip_stream);
+
+/*
  * Workspace size in bytes that `pass` (MXC_FWD / MXC_BWD_DATA / MXC_BWD_WEIGHT)
  * needs for these arguments, written to *out_bytes (a HOST pointer).  Touches
  * no GPU state.

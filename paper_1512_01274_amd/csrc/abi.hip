@@ -355,6 +355,15 @@ int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout, const void 
     return bias_grad(N, K, (long long)P * Q, dtype, layout, dy, db, (float *)workspace, (hipStream_t)hip_stream);
 }
 
+int mxc_sgd_update(size_t n, float *w, const float *g, float *v, void *w_bf16, float lr, float momentum, float wd, void *hip_stream)
+{
+    if (n == 0) return MXC_ERR_SHAPE;
+    if (!w || !g) return MXC_ERR_NULL;
+    if (!v && momentum != 0.f) return MXC_ERR_NULL;
+    if (misaligned(w) || misaligned(g) || misaligned(v) || misaligned(w_bf16)) return MXC_ERR_ALIGN;
+    return sgd_update(n, w, g, v, w_bf16, lr, momentum, wd, (hipStream_t)hip_stream);
+}
+
 int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                                int dtype, int layout, size_t *out_bytes)
 {

@@ -95,22 +95,25 @@ __global__ __launch_bounds__(BG_THREADS) void bias_grad_planes_kernel(const T *_
     if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
 }
 
-// db[k] = sum of the partial vectors, in a fixed order: a workgroup owns 32 columns; its 8 thread
-// groups each add every 8th partial vector, then the 8 sums are added in ascending order.
-__global__ __launch_bounds__(BG_THREADS) void bias_grad_sum_kernel(const float *__restrict__ partial, float *__restrict__ db, int K,
-                                                                   int parts)
+// db[k] = sum of the partial vectors, in a fixed order: a workgroup of 1024 threads owns 32 columns;
+// its 32 thread groups each add every 32nd partial vector, then the 32 sums are added in ascending
+// order.
+constexpr int BG_SUM_THREADS = 1024;
+__global__ __launch_bounds__(BG_SUM_THREADS) void bias_grad_sum_kernel(const float *__restrict__ partial, float *__restrict__ db, int K,
+                                                                       int parts)
 {
-    __shared__ float red[BG_THREADS];
+    __shared__ float red[BG_SUM_THREADS];
+    constexpr int GROUPS = BG_SUM_THREADS / 32;
     const int col = threadIdx.x % 32, grp = threadIdx.x / 32;
     const int k = blockIdx.x * 32 + col;
     float acc = 0.f;
     if (k < K)
-        for (int i = grp; i < parts; i += BG_THREADS / 32) acc += partial[(size_t)i * K + k];
+        for (int i = grp; i < parts; i += GROUPS) acc += partial[(size_t)i * K + k];
     red[threadIdx.x] = acc;
     __syncthreads();
     if (grp == 0 && k < K) {
         float s = 0.f;
-        for (int g = 0; g < BG_THREADS / 32; ++g) s += red[g * 32 + col];
+        for (int g = 0; g < GROUPS; ++g) s += red[g * 32 + col];
         db[k] = s;
     }
 }
@@ -126,7 +129,7 @@ int bias_grad_parts(long long N, int K, long long PQ, int layout)
     (void)K;
     const long long rows = N * PQ;
     long long parts = (rows + 255) / 256;      // at least 256 rows per workgroup
-    if (parts > 512) parts = 512;
+    if (parts > 1024) parts = 1024;
     return (int)(parts < 1 ? 1 : parts);
 }
 
@@ -163,7 +166,7 @@ int bias_grad(long long N, int K, long long PQ, int dtype, int layout, const voi
         }
     }
     if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
-    hipLaunchKernelGGL(bias_grad_sum_kernel, dim3((unsigned)((K + 31) / 32)), dim3(BG_THREADS), 0, st, partial, db, K, parts);
+    hipLaunchKernelGGL(bias_grad_sum_kernel, dim3((unsigned)((K + 31) / 32)), dim3(BG_SUM_THREADS), 0, st, partial, db, K, parts);
     return ok();
 }
 

@@ -62,6 +62,9 @@ int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
 // launches the register-resident MFMA loop; *flops = floating-point operations the launch performs
 int probe_mfma(int workgroups, int iters, float *out, double *flops, hipStream_t st);
 
+// ---- update.hip: SGD with momentum and weight decay on fp32 master weights -------------
+int sgd_update(size_t n, float *w, const float *g, float *v, void *w_copy, float lr, float momentum, float wd, hipStream_t st);
+
 // ---- bias.hip: bias gradient ------------------------------------------------------------
 int bias_grad_parts(long long N, int K, long long PQ, int layout);      // partial vectors of K floats the call needs as scratch
 int bias_grad(long long N, int K, long long PQ, int dtype, int layout, const void *dy, float *db, float *partial, hipStream_t st);

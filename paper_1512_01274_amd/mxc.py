@@ -43,6 +43,9 @@ _lib.mxc_conv2d_bwd_data_relu.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP, _VP, _
 _lib.mxc_conv2d_bwd_data_relu.restype = _I
 _lib.mxc_bias_grad.argtypes = [_I] * 6 + [_VP, _VP, _VP, _SZ, _VP]
 _lib.mxc_bias_grad.restype = _I
+_F = ctypes.c_float
+_lib.mxc_sgd_update.argtypes = [_SZ, _VP, _VP, _VP, _VP, _F, _F, _F, _VP]
+_lib.mxc_sgd_update.restype = _I
 _lib.mxc_probe_mfma.argtypes = [_I, _I, _VP, _SZ, ctypes.POINTER(ctypes.c_double), _VP]
 _lib.mxc_probe_mfma.restype = _I
 
@@ -140,6 +143,13 @@ def mxc_conv2d_bwd_data_relu(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy
 def mxc_bias_grad(N, K, P, Q, dtype, layout, dy, db, workspace=None, stream=None):
     ws_ptr, ws_bytes = _ws(workspace)
     rc = _lib.mxc_bias_grad(N, K, P, Q, dtype, layout, _ptr(dy), _ptr(db), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_sgd_update(w, g, v, w_bf16, lr, momentum, wd, stream=None):
+    """In-place update of the fp32 tensors w (and v, may be None); optional bf16 copy of the new w."""
+    rc = _lib.mxc_sgd_update(w.numel(), _ptr(w), _ptr(g), _ptr(v), _ptr(w_bf16), lr, momentum, wd, _stream(stream))
     if rc != MXC_OK:
         raise MxcError(rc)
 

@@ -308,3 +308,30 @@ def test_grouped_operations_network_layers(mxc, oracle, cfg_idx):
         db = torch.empty(K, dtype=torch.float32, device="cuda")
         mxc.mxc_bias_grad(N, K, L.P, L.Q, run.dt, run.lay, run._in(dy), db, run._ws(mxc.MXC_BIAS_GRAD))
         assert util.metric(db.cpu().numpy().astype(np.float64), ref, den) <= util.TOL["f32"], L.name
+
+
+# ---- weight update ------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n", [1, 3, 1024, 4099, 884736 + 3])
+@pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 1e-4)])
+def test_sgd_update(mxc, oracle, n, momentum, wd):
+    rng = np.random.Generator(np.random.Philox(key=gen.SEED + n))
+    w0 = rng.standard_normal(n).astype(np.float32)
+    gs = [rng.standard_normal(n).astype(np.float32) for _ in range(3)]
+    w = torch.from_numpy(w0).cuda()
+    v = torch.zeros(n, dtype=torch.float32, device="cuda") if momentum else None
+    wb = torch.full((n,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    rw, rv = w0.astype(np.float64), None
+    for g in gs:
+        mxc.mxc_sgd_update(w, torch.from_numpy(g).cuda(), v, wb, 0.05, momentum, wd)
+        rw, rv = oracle.sgd_update(rw, g, rv, 0.05, momentum, wd)
+    torch.cuda.synchronize()
+    got = w.cpu().numpy().astype(np.float64)
+    scale = np.abs(rw) + sum(0.05 * np.abs(g.astype(np.float64)) for g in gs) + 1e-30
+    assert np.max(np.abs(got - rw) / scale) <= 1e-6          # a handful of fp32 roundings per step
+    if momentum:
+        assert np.max(np.abs(v.cpu().numpy() - rv) / scale) <= 1e-6
+    # the bf16 copy is the fp32 master rounded to nearest even, bit for bit
+    assert np.array_equal(gen.to_host_f64(wb), gen.round_to_bf16(w.cpu().numpy()).astype(np.float64))
+    with pytest.raises(mxc.MxcError):
+        mxc.mxc_sgd_update(w, torch.from_numpy(gs[0]).cuda(), None, None, 0.05, 0.9, 0.0)    # momentum without velocity
