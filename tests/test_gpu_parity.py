@@ -90,6 +90,11 @@ SWEEP = [
     (1, 4, 10, 12, 8, 3, 3, 2, 0),      # ... one class
     (2, 1, 9, 16, 8, 5, 5, 4, 2),       # ... C == 1, stride 4: two classes
     (1, 2, 8, 8, 16, 3, 3, 2, 1),       # ... C == 2
+    (2, 16, 9, 9, 64, 3, 3, 2, 1),      # K % 64 == 0: backward-data reads the filter in place (transposed tiles), stride 2
+    (1, 24, 7, 7, 128, 1, 1, 1, 0),     # ... 1x1
+    (2, 8, 10, 10, 64, 5, 5, 1, 2),     # ... 5x5
+    (1, 40, 8, 9, 192, 3, 3, 3, 0),     # ... stride 3, ragged output columns
+    (1, 264, 6, 6, 320, 3, 3, 1, 1),    # ... several column tiles, ragged
 ]
 
 
