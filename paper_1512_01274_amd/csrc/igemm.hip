@@ -48,6 +48,7 @@ struct IgemmParams {
     int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
     int m_tiles, n_tiles;
     unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
+    int tap_inner;       // reduction order (Ci % BKT == 0 only): 1 = all taps of a channel block before the next block
     // applied to the accumulators before the store (all optional)
     const float *bias;   // + bias[co]
     int relu;            // max(0, .)
@@ -213,15 +214,28 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
             const int bad = (__builtin_bit_cast(int, hw) | __builtin_bit_cast(int, d)) & (int)0x80008000;
             va[i] = bad == 0 ? (unsigned)(a_off[i] + tap_e.x + ci2) : OOB;
         } else {
-            const bool k_ok = kd2 < Kd2;
+            if (p.tap_inner) {
+                // Order (channel block, tap): the pixels a workgroup reads for one channel block serve all
+                // its taps back to back, so they are still in the XCD's L2 when the next tap asks for them.
+                const bool k_ok = tap < T;
+                const unsigned kd = (unsigned)(tap * Ci2 + ci2);
 #pragma unroll
-            for (int i = 0; i < B_LD; ++i) vb[i] = k_ok ? b_off[i] + (unsigned)kd2 : OOB;
-            // advance (tap, ci) and kd by one stage
-            kd2 += BKT * 2;
-            ci2 += kr2;
-            const int carry = ci2 >= Ci2 ? 1 : 0;
-            ci2 -= carry ? Ci2 : 0;
-            tap += kq + carry;
+                for (int i = 0; i < B_LD; ++i) vb[i] = k_ok ? b_off[i] + kd : OOB;
+                const int last = tap + 1 >= T ? 1 : 0;           // wrap to the next channel block
+                tap = last ? 0 : tap + 1;
+                ci2 += last ? BKT * 2 : 0;
+                tap = ci2 >= Ci2 ? T : tap;                       // past the last block: the sentinel tap, for good
+            } else {
+                const bool k_ok = kd2 < Kd2;
+#pragma unroll
+                for (int i = 0; i < B_LD; ++i) vb[i] = k_ok ? b_off[i] + (unsigned)kd2 : OOB;
+                // advance (tap, ci) and kd by one stage
+                kd2 += BKT * 2;
+                ci2 += kr2;
+                const int carry = ci2 >= Ci2 ? 1 : 0;
+                ci2 -= carry ? Ci2 : 0;
+                tap += kq + carry;
+            }
         }
     };
     constexpr int N_ADDR = A_LD + 2;
@@ -419,6 +433,8 @@ int launch(IgemmParams p, hipStream_t st)
     p.m_tiles = (int)mt;
     p.in_bytes = (unsigned)((long long)p.N * p.Hi * p.Wi * p.pix * 2);
     p.wm_bytes = (unsigned)((long long)p.Co * p.TR * p.TS * p.Ci * 2);
+    // MXC_TAP_OUTER=1 (tuning only) keeps the filter's own order, all channels of a tap before the next tap
+    p.tap_inner = (p.Ci % BKT == 0 && p.TR * p.TS > 1 && !getenv("MXC_TAP_OUTER")) ? 1 : 0;
     p.linear_out = (p.out_mul_h == 1 && p.out_mul_w == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
     const int total = p.m_tiles * p.n_tiles;
     const int grid = ((total + 7) / 8) * 8;
