@@ -48,6 +48,7 @@ struct IgemmParams {
     int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
     int m_tiles, n_tiles;
     unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
+    int tap_row_inner;   // tap t = (column step)*TR + (row step) instead of (row step)*TS + (column step)
     int tap_inner;       // reduction order (Ci % BKT == 0 only): 1 = all taps of a channel block before the next block
     // applied to the accumulators before the store (all optional)
     const float *bias;   // + bias[co]
@@ -147,7 +148,8 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     for (int t = tid; t <= T; t += NT) {
         int2 e;
         if (t < T) {
-            const int dh = (t / p.TS) * p.tstep_h, dv = (t % p.TS) * p.tstep_w;
+            const int dh = (p.tap_row_inner ? t % p.TR : t / p.TS) * p.tstep_h;
+            const int dv = (p.tap_row_inner ? t / p.TR : t % p.TS) * p.tstep_w;
             e.x = ((dh * p.Wi + dv) * p.pix) * 2;
             e.y = (dh & 0xFFFF) | (dv << 16);
         } else {
@@ -699,9 +701,12 @@ __global__ __launch_bounds__(256) void smallc_bwd_pack_w_kernel(const bf16_t *__
         gid -= sz;
     }
     if (ph == stride) return;
+    // reduction order (u, j, k): the row taps of one dy column are consecutive stages, so the dy row a
+    // GEMM row reads at row tap j is the one its neighbour one image row down reads at j+1, one stage
+    // later, while it is still in the L2 (with j outermost the reuse came 10 stages later and missed)
     const int k = gid % K; int t = gid / K;
-    const int u = t % U; t /= U;
     const int j = t % TRp; t /= TRp;
+    const int u = t % U; t /= U;
     const int c = t & 3, g = t >> 2;
     const int r = ph + stride * j;
     const int sidx = g + pad - stride * (u + uoff);
@@ -768,7 +773,7 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, voi
         IgemmParams p{};
         p.in = (const bf16_t *)dy; p.wm = (const bf16_t *)w2 + w2_off; p.out = (bf16_t *)dx4;
         p.N = s.N; p.Hi = s.P; p.Wi = s.Q; p.Ci = s.K; p.pix = s.K; p.Co = g.G * 4;
-        p.TR = TR; p.TS = g.U; p.tstep_h = -1; p.tstep_w = 1;
+        p.TR = TR; p.TS = g.U; p.tstep_h = -1; p.tstep_w = 1; p.tap_row_inner = 1;
         p.Mh = Mh; p.Mw = g.Wg;
         p.in_mul_h = 1; p.in_mul_w = g.G / s.stride; p.in_off_h = hh0; p.in_off_w = g.uoff;
         p.Ho = s.H; p.Wo = g.Wg; p.out_mul_h = s.stride; p.out_mul_w = 1; p.out_off_h = h_first; p.out_off_w = 0;
