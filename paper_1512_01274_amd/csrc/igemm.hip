@@ -481,7 +481,12 @@ int launch_choice(int idx, const IgemmParams &p, hipStream_t st)
 // MXC_FORCE_VARIANT=<name> (tuning sweeps only) overrides it.
 int choose_tile(long long M, int Co, int Kd)
 {
-    (void)Kd;
+    // Reductions of one or two stages (first layers): a workgroup's fixed cost (launch, pipeline fill,
+    // epilogue: about 4 us, shared by the workgroups resident on the CU) outweighs its matrix work, so
+    // fewer, larger tiles win.  In the model's units (tile area x stages at 256x256 speed) that cost
+    // is about 150000.
+    const int KT = (Kd + 63) / 64;
+    const double fixed = KT <= 2 ? 150000.0 : 0.0;
     if (const char *f = getenv("MXC_FORCE_VARIANT"))
         for (int i = 0; i < N_TILE_CHOICES; ++i)
             if (!strcmp(f, kTiles[i].name)) return i;
@@ -493,7 +498,7 @@ int choose_tile(long long M, int Co, int Kd)
         const long long per_cu = (tiles + 255) / 256;
         const double resident = per_cu < t.slots ? (double)per_cu : (double)t.slots;
         const double util = t.util * (0.6 + 0.4 * resident / t.slots);
-        const double time = (double)per_cu * t.bm * t.bn / util;
+        const double time = (double)per_cu * ((double)t.bm * t.bn / util * KT + fixed / resident);
         if (time < best_t) { best_t = time; best = i; }
     }
     return best;
