@@ -95,6 +95,9 @@ SWEEP = [
     (2, 8, 10, 10, 64, 5, 5, 1, 2),     # ... 5x5
     (1, 40, 8, 9, 192, 3, 3, 3, 0),     # ... stride 3, ragged output columns
     (1, 264, 6, 6, 320, 3, 3, 1, 1),    # ... several column tiles, ragged
+    (2, 64, 9, 10, 64, 3, 3, 1, 1),     # C % 64 == 0: channel-block-major reduction order, one block
+    (1, 128, 8, 8, 64, 3, 3, 2, 1),     # ... two blocks, stride 2 (backward-data classes with 1, 2 and 4 taps)
+    (2, 192, 6, 6, 32, 5, 5, 1, 2),     # ... three blocks, 25 taps
 ]
 
 
