@@ -457,6 +457,7 @@ const TileChoice kTiles[] = {
     {256, 64, 2, 0.60f, "igemm_256x64_k32s3_w4"},
     {128, 32, 4, 0.33f, "igemm_128x32_k64s2_w4"},
     {256, 32, 2, 0.33f, "igemm_256x32_k64s2_w4"},
+    {256, 192, 1, 1.05f, "igemm_256x192_k64s2_w8"},
 };
 constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -470,7 +471,8 @@ int launch_choice(int idx, const IgemmParams &p, hipStream_t st)
     case 4: return launch<128, 64, 64, 2, 2, 2>(p, st);
     case 5: return launch<256, 64, 32, 3, 4, 1>(p, st);
     case 6: return launch<128, 32, 64, 2, 4, 1>(p, st);
-    default: return launch<256, 32, 64, 2, 4, 1>(p, st);
+    case 7: return launch<256, 32, 64, 2, 4, 1>(p, st);
+    default: return launch<256, 192, 64, 2, 4, 2>(p, st);
     }
 }
 
