@@ -89,3 +89,52 @@ def test_workspace_query_is_consistent(mxc):
     need = mxc.mxc_conv2d_workspace_bytes(mxc.MXC_FWD, *GOOD, mxc.MXC_F32, mxc.MXC_NCHW)
     assert lib.mxc_conv2d_fwd(*GOOD, mxc.MXC_F32, mxc.MXC_NCHW, 4096, 8192, 16384, 32768, need - 1, None) \
         == mxc.MXC_ERR_WORKSPACE
+
+
+def test_workspace_query_over_random_shapes(mxc):
+    """Host logic only: every pass answers the size query for a spread of shapes (all kernel families'
+    geometry code runs in its dry mode), sizes are multiples of the carve-out alignment, and the
+    grouped backward-data never needs less than the plain one."""
+    import numpy as np
+    rng = np.random.Generator(np.random.Philox(key=7))
+    passes = (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT, mxc.MXC_BWD_DATA_RELU, mxc.MXC_BIAS_GRAD)
+    for _ in range(300):
+        C = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 24, 64, 96, 192, 512]))
+        K = int(rng.choice([1, 7, 8, 16, 40, 64, 96, 256, 520]))
+        R = int(rng.choice([1, 2, 3, 5, 7, 11]))
+        S = int(rng.choice([1, 2, 3, 5, 7, 11]))
+        st = int(rng.integers(1, 5))
+        pad = int(rng.integers(0, R + 1))
+        H = int(rng.integers(max(1, R - 2 * pad), 64)) + R
+        W = int(rng.integers(max(1, S - 2 * pad), 64)) + S
+        N = int(rng.integers(1, 5))
+        dims = (N, C, H, W, K, R, S, st, pad)
+        for dt in (mxc.MXC_F32, mxc.MXC_BF16):
+            for lay in (mxc.MXC_NCHW, mxc.MXC_NHWC):
+                sizes = {p: mxc.mxc_conv2d_workspace_bytes(p, *dims, dt, lay) for p in passes}
+                assert all(v % 256 == 0 and v < 2 ** 40 for v in sizes.values()), (dims, sizes)
+                assert sizes[mxc.MXC_BWD_DATA_RELU] >= sizes[mxc.MXC_BWD_DATA], dims
+                assert sizes[mxc.MXC_BIAS_GRAD] > 0
+
+
+def test_grouped_entry_points_validate_on_the_host(mxc):
+    lib = mxc.raw()
+    big = 1 << 30
+    # relu outside {0, 1}
+    assert lib.mxc_conv2d_fwd_bias_act(*GOOD, 0, 0, 4096, 8192, None, 2, 16384, 32768, big, None) == mxc.MXC_ERR_UNSUPPORTED
+    # misaligned bias
+    assert lib.mxc_conv2d_fwd_bias_act(*GOOD, 0, 0, 4096, 8192, 4098, 1, 16384, 32768, big, None) == mxc.MXC_ERR_ALIGN
+    # missing mask
+    assert lib.mxc_conv2d_bwd_data_relu(*GOOD, 0, 0, 4096, 8192, None, 16384, 32768, big, None) == mxc.MXC_ERR_NULL
+    # bias gradient: shape, null, workspace
+    assert lib.mxc_bias_grad(0, 8, 4, 4, 0, 1, 4096, 8192, 16384, big, None) == mxc.MXC_ERR_SHAPE
+    assert lib.mxc_bias_grad(2, 8, 4, 4, 0, 1, None, 8192, 16384, big, None) == mxc.MXC_ERR_NULL
+    assert lib.mxc_bias_grad(2, 8, 4, 4, 0, 1, 4096, 8192, 16384, 4, None) == mxc.MXC_ERR_WORKSPACE
+    # update: empty, null, momentum without velocity
+    assert lib.mxc_sgd_update(0, 4096, 8192, None, None, 0.1, 0.0, 0.0, None) == mxc.MXC_ERR_SHAPE
+    assert lib.mxc_sgd_update(16, None, 8192, None, None, 0.1, 0.0, 0.0, None) == mxc.MXC_ERR_NULL
+    assert lib.mxc_sgd_update(16, 4096, 8192, None, None, 0.1, 0.9, 0.0, None) == mxc.MXC_ERR_NULL
+    assert lib.mxc_sgd_update(16, 4100, 8192, None, None, 0.1, 0.0, 0.0, None) == mxc.MXC_ERR_ALIGN
+    # probe
+    assert lib.mxc_probe_mfma(0, 10, 4096, 1 << 20, ctypes.byref(ctypes.c_double()), None) == mxc.MXC_ERR_SHAPE
+    assert lib.mxc_probe_mfma(4, 10, 4096, 16, ctypes.byref(ctypes.c_double()), None) == mxc.MXC_ERR_WORKSPACE
