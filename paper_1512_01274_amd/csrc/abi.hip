@@ -74,8 +74,10 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
 {
     const char *v = "";
     if (dtype == MXC_BF16 && s.C % 8 == 0 && igemm_fwd_supported(s)) {
+        const size_t split_bytes = igemm_fwd_split_bytes(s);
+        void *split_ws = split_bytes ? ws.take(split_bytes) : nullptr;
         if (dry) return MXC_OK;
-        const int rc = igemm_fwd(s, x, w, y, st, &v, post);
+        const int rc = igemm_fwd(s, x, w, y, st, &v, post, split_ws);
         set_variant("fwd", v);
         return rc;
     }

@@ -16,6 +16,7 @@
 // steps of BKT (32 or 64) through a ring of NS LDS stages that are filled by direct global->LDS
 // loads issued NS stages ahead of their use; 16-byte chunks are XOR-swizzled by row so that the
 // ds_read_b128 operand fetches are bank-conflict free.
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -48,6 +49,11 @@ struct IgemmParams {
     int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
     int m_tiles, n_tiles;
     unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
+    // split reduction (few tiles, long reduction): workgroup (tile, z) runs stages [z*split_stages, (z+1)*split_stages)
+    // and stores its fp32 accumulators to partial[z][m][co]; a second kernel adds the splits in ascending z and
+    // applies bias / ReLU / mask.  splits <= 1: off.
+    float *partial;
+    int splits, split_stages;
     int tap_row_inner;   // tap t = (column step)*TR + (row step) instead of (row step)*TS + (column step)
     int tap_inner;       // reduction order (Ci % BKT == 0 only): 1 = all taps of a channel block before the next block
     // applied to the accumulators before the store (all optional)
@@ -133,9 +139,11 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     // XCD a contiguous range of tiles, n-tile fastest, so that tiles sharing an activation tile meet
     // in one L2.
     const int total = p.m_tiles * p.n_tiles;
-    const int per_xcd = (total + 7) / 8;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= total) return;
+    const int units = total * (p.splits > 1 ? p.splits : 1);
+    const int per_xcd = (units + 7) / 8;
+    const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (unit >= units) return;
+    const int logical = unit % total, split_z = unit / total;
     const int m0 = (logical / p.n_tiles) * BM, n0 = (logical % p.n_tiles) * BN;
 
     const int T = p.TR * p.TS;
@@ -196,8 +204,16 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     // Reduction position of this lane's chunk: kd = stage*BKT + ld_chunk*8 = tap*Ci + ci, kept as
     // (tap, ci) and advanced without branches: BKT = kq*Ci + kr.
     const int kq = BKT / p.Ci, kr2 = (BKT % p.Ci) * 2, Ci2 = p.Ci * 2, Kd2 = Kd * 2;
-    int kd2 = ld_chunk * 16;                       // byte offset within a filter row
-    int ci2 = (ld_chunk * 8 % p.Ci) * 2, tap = ld_chunk * 8 / p.Ci;
+    // first stage and number of stages of this workgroup (all of them unless the reduction is split)
+    const int k_lo = p.splits > 1 ? split_z * p.split_stages : 0;
+    const int k_cnt = p.splits > 1 ? min(KT - k_lo, p.split_stages) : KT;
+    const int kd0 = k_lo * BKT + ld_chunk * 8;     // this lane's reduction position in the first stage (tap-major order)
+    int kd2 = kd0 * 2;                             // byte offset within a filter row
+    int ci2 = (kd0 % p.Ci) * 2, tap = kd0 / p.Ci;
+    if (p.tap_inner) {                             // stage s = (channel block s / T, tap s % T)
+        tap = k_lo % T;
+        ci2 = (k_lo / T) * (BKT * 2) + ld_chunk * 16;
+    }
     const int lim_hw = ((p.Hi - 1) & 0xFFFF) | ((p.Wi - 1) << 16);
 
     unsigned va[A_LD], vb[B_LD];   // byte offsets of the next stage's loads
@@ -332,11 +348,11 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         });
     };
 
-    for (int kt = 0; kt < KT; kt += NS) {
+    for (int kt = 0; kt < k_cnt; kt += NS) {
         run_stage(IC<0>{});
-        if (kt + 1 < KT) run_stage(IC<1>{});
-        if constexpr (NS > 2) if (kt + 2 < KT) run_stage(IC<2>{});
-        if constexpr (NS > 3) if (kt + 3 < KT) run_stage(IC<3>{});
+        if (kt + 1 < k_cnt) run_stage(IC<1>{});
+        if constexpr (NS > 2) if (kt + 2 < k_cnt) run_stage(IC<2>{});
+        if constexpr (NS > 3) if (kt + 3 < k_cnt) run_stage(IC<3>{});
     }
     wait_vmcnt<0>();   // drain the zero-fill loads of the stages past the end before the tile's LDS is abandoned
 
@@ -348,6 +364,23 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
         return ((long long)n * p.Ho + ((int)a * p.out_mul_h + p.out_off_h)) * p.Wo + ((int)b * p.out_mul_w + p.out_off_w);
     };
+    if (p.splits > 1) {
+        // split reduction: fp32 accumulators to partial[z][m][co] (row-major like the output)
+        float *part = p.partial + (size_t)split_z * p.M * p.Co;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
+                if (m >= p.M) continue;
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int co = n0 + wave_n + j * 32 + frag_row;
+                    if (co < p.Co) part[(size_t)m * p.Co + co] = acc[i][j][e];
+                }
+            }
+        return;
+    }
     // bias of this lane's NI output columns (accumulator block j holds column j*32 + lane%32)
     float bias_j[NI];
 #pragma unroll
@@ -438,8 +471,16 @@ int launch(IgemmParams p, hipStream_t st)
     // MXC_TAP_OUTER=1 (tuning only) keeps the filter's own order, all channels of a tap before the next tap
     p.tap_inner = (p.Ci % BKT == 0 && p.TR * p.TS > 1 && !getenv("MXC_TAP_OUTER")) ? 1 : 0;
     p.linear_out = (p.out_mul_h == 1 && p.out_mul_w == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
-    const int total = p.m_tiles * p.n_tiles;
-    const int grid = ((total + 7) / 8) * 8;
+    if (p.splits > 1) {
+        // even stage ranges; the last split may be shorter, none is empty
+        const int KT = (p.TR * p.TS * p.Ci + BKT - 1) / BKT;
+        p.split_stages = (KT + p.splits - 1) / p.splits;
+        p.splits = (KT + p.split_stages - 1) / p.split_stages;
+        if (!p.linear_out || !p.partial) return MXC_ERR_UNSUPPORTED;
+    }
+    const long long total = (long long)p.m_tiles * p.n_tiles * (p.splits > 1 ? p.splits : 1);
+    if (total > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
+    const int grid = (int)((total + 7) / 8) * 8;
     hipLaunchKernelGGL((igemm_kernel<BM, BN, BKT, NS, WR, WC>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
@@ -565,13 +606,63 @@ __global__ __launch_bounds__(256) void zero_phase_kernel(bf16_t *__restrict__ dx
 
 }  // namespace
 
+namespace {
+
+// How many ways to split the reduction of a GEMM whose tiles would leave most of the chip idle
+// (FullyConnected-shaped and small-batch problems): enough workgroups to fill the slots, at least 8
+// stages per split, at most 32 splits.  1 = no split (every layer of the benchmark stacks).
+int split_count(long long M, int Co, int Kd)
+{
+    const TileChoice &t = kTiles[choose_tile(M, Co, Kd)];
+    const long long tiles = ((M + t.bm - 1) / t.bm) * ((Co + t.bn - 1) / t.bn);
+    const long long slots = 256LL * t.slots;
+    if (tiles * 2 > slots) return 1;
+    long long sp = slots / tiles;
+    const long long KT = (Kd + 63) / 64;
+    if (sp > KT / 8) sp = KT / 8;
+    if (sp > 32) sp = 32;
+    return sp >= 2 ? (int)sp : 1;
+}
+
+// out[m][co] = act(sum_z partial[z][m][co] + bias[co]) in ascending z (fixed order), 4 columns per thread
+__global__ __launch_bounds__(256) void split_finish_kernel(const float *__restrict__ partial, bf16_t *__restrict__ out, long long MC,
+                                                           int Co, int splits, const float *__restrict__ bias, int relu)
+{
+    const long long i4 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i4 >= MC) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < splits; ++z) {
+        const float4 v = *reinterpret_cast<const float4 *>(partial + (size_t)z * MC + i4);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    if (bias != nullptr) {
+        const int co = (int)(i4 % Co);          // Co % 8 == 0: the four columns share a row
+        acc.x += bias[co]; acc.y += bias[co + 1]; acc.z += bias[co + 2]; acc.w += bias[co + 3];
+    }
+    if (relu) { acc.x = fmaxf(acc.x, 0.f); acc.y = fmaxf(acc.y, 0.f); acc.z = fmaxf(acc.z, 0.f); acc.w = fmaxf(acc.w, 0.f); }
+    const uint2 o = make_uint2((uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16),
+                               (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16));
+    *reinterpret_cast<uint2 *>(out + i4) = o;
+}
+
+}  // namespace
+
+size_t igemm_fwd_split_bytes(const ConvShape &s)
+{
+    if (s.K % 8 != 0) return 0;
+    const long long M = (long long)s.N * s.P * s.Q;
+    const int sp = split_count(M, s.K, s.R * s.S * s.C);
+    return sp > 1 ? (size_t)sp * M * s.K * sizeof(float) : 0;
+}
+
 bool igemm_fwd_supported(const ConvShape &s)
 {
     return s.C % 8 == 0 && igemm_dims_ok((long long)s.N * s.H * s.W * s.C, (long long)s.K * s.R * s.S * s.C,
                                          (long long)s.N * s.P * s.Q, s.H, s.W, s.pad + s.R + s.S + s.stride, s.R * s.S);
 }
 
-int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant, const PostOp &post)
+int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant, const PostOp &post,
+              void *split_ws)
 {
     IgemmParams p{};
     p.bias = post.bias; p.relu = post.relu;
@@ -581,8 +672,28 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
     p.Mh = s.P; p.Mw = s.Q;
     p.in_mul_h = s.stride; p.in_mul_w = s.stride; p.in_off_h = -s.pad; p.in_off_w = -s.pad;
     p.Ho = s.P; p.Wo = s.Q; p.out_mul_h = 1; p.out_mul_w = 1; p.out_off_h = 0; p.out_off_w = 0;
-    const int tc = choose_tile((long long)s.N * s.P * s.Q, s.K, s.R * s.S * s.C);
+    const long long M = (long long)s.N * s.P * s.Q;
+    const int tc = choose_tile(M, s.K, s.R * s.S * s.C);
     *variant = kTiles[tc].name;
+    const int sp = (split_ws != nullptr && s.K % 8 == 0) ? split_count(M, s.K, s.R * s.S * s.C) : 1;
+    if (sp > 1) {
+        p.splits = sp;
+        p.partial = (float *)split_ws;
+        p.bias = nullptr; p.relu = 0;                 // applied by the finishing kernel
+        const int rc = launch_choice(tc, p, st);
+        if (rc != MXC_OK) return rc;
+        const long long MC = M * s.K;
+        if ((MC / 4 + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+        // the launcher may have lowered the split count: recompute it the same way
+        const int bk = tc == 5 ? 32 : 64;
+        const int KT = (s.R * s.S * s.C + bk - 1) / bk, per = (KT + sp - 1) / sp, used = (KT + per - 1) / per;
+        static thread_local char split_name[64];
+        snprintf(split_name, sizeof(split_name), "%s_split%d", kTiles[tc].name, used);
+        *variant = split_name;
+        hipLaunchKernelGGL(split_finish_kernel, dim3((unsigned)((MC / 4 + 255) / 256)), dim3(256), 0, st, (const float *)split_ws,
+                           (bf16_t *)y, MC, s.K, used, post.bias, post.relu);
+        return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+    }
     return launch_choice(tc, p, st);
 }
 

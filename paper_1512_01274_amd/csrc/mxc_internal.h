@@ -80,8 +80,10 @@ int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *
 
 // ---- igemm.hip: bf16 MFMA implicit GEMM (NHWC/KRSC) ---------------------------
 bool igemm_fwd_supported(const ConvShape &s);
+// split_ws: scratch of igemm_fwd_split_bytes(s) bytes for a split reduction (may be null: never split)
+size_t igemm_fwd_split_bytes(const ConvShape &s);
 int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStream_t st, const char **variant,
-              const PostOp &post = PostOp());
+              const PostOp &post = PostOp(), void *split_ws = nullptr);
 bool igemm_bwd_data_supported(const ConvShape &s);
 size_t igemm_bwd_data_workspace(const ConvShape &s);   // bytes for the re-packed filter
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,

@@ -343,3 +343,31 @@ def test_sgd_update(mxc, oracle, n, momentum, wd):
     assert np.array_equal(gen.to_host_f64(wb), gen.round_to_bf16(w.cpu().numpy()).astype(np.float64))
     with pytest.raises(mxc.MxcError):
         mxc.mxc_sgd_update(w, torch.from_numpy(gs[0]).cuda(), None, None, 0.05, 0.9, 0.0)    # momentum without velocity
+
+
+# ---- split reduction (few tiles, long reduction: FullyConnected-shaped and small-batch problems) -----
+
+SPLIT_SHAPES = [
+    (64, 2048, 1, 1, 256, 1, 1, 1, 0),      # FullyConnected: one row tile, 32 stages
+    (128, 1024, 1, 1, 520, 1, 1, 1, 0),     # ... ragged output columns
+    (1, 256, 14, 14, 128, 3, 3, 1, 1),      # one image: two row tiles (ragged), 36 stages, channel-block-major order
+    (2, 192, 7, 7, 64, 5, 5, 1, 2),         # 75 stages, ragged last split
+    (3, 136, 5, 5, 32, 3, 3, 1, 1),         # channel count not a multiple of 64: tap-major order
+]
+
+
+@pytest.mark.parametrize("dims", SPLIT_SHAPES)
+def test_split_reduction_forward(mxc, oracle, dims):
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy, bias = _fused_case(dims, "bf16", hash(dims) & 0xFFFF)
+    check_all_passes(mxc, oracle, dims, "bf16", "nhwc", x, w, dy, passes=("fwd",))
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    y = run.fwd(x, w, return_tensor=True)
+    assert "_split" in mxc.mxc_last_variant(), mxc.mxc_last_variant()
+    assert torch.equal(y.view(torch.int16), run.fwd(x, w, return_tensor=True).view(torch.int16))      # deterministic
+    # bias and ReLU are applied by the finishing kernel
+    ref, den = oracle.conv2d_fwd_bias_act(x, w, bias, True, st, pad)
+    y = torch.full((N * K * run.P * run.Q,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, run._in(x), run._in(w), torch.from_numpy(bias).cuda(), 1, y, run._ws(mxc.MXC_FWD))
+    got = run._out(y, (N, K, run.P, run.Q))
+    assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), dims
