@@ -145,9 +145,11 @@ int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, 
     }
     if (dtype == MXC_BF16 && igemm_bwd_data_supported(s)) {
         void *wt = ws.take(igemm_bwd_data_workspace(s));
+        const size_t split_bytes = igemm_bwd_data_split_bytes(s);
+        void *split_ws = split_bytes ? ws.take(split_bytes) : nullptr;
         if (dry) return MXC_OK;
         const char *v = "";
-        const int rc = igemm_bwd_data(s, dy, w, dx, wt, st, &v, post);
+        const int rc = igemm_bwd_data(s, dy, w, dx, wt, st, &v, post, split_ws);
         set_variant("bwd_data", v);
         return rc;
     }

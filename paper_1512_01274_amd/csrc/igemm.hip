@@ -626,7 +626,8 @@ int split_count(long long M, int Co, int Kd)
 
 // out[m][co] = act(sum_z partial[z][m][co] + bias[co]) in ascending z (fixed order), 4 columns per thread
 __global__ __launch_bounds__(256) void split_finish_kernel(const float *__restrict__ partial, bf16_t *__restrict__ out, long long MC,
-                                                           int Co, int splits, const float *__restrict__ bias, int relu)
+                                                           int Co, int splits, const float *__restrict__ bias, int relu,
+                                                           const bf16_t *__restrict__ mask)
 {
     const long long i4 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (i4 >= MC) return;
@@ -640,12 +641,47 @@ __global__ __launch_bounds__(256) void split_finish_kernel(const float *__restri
         acc.x += bias[co]; acc.y += bias[co + 1]; acc.z += bias[co + 2]; acc.w += bias[co + 3];
     }
     if (relu) { acc.x = fmaxf(acc.x, 0.f); acc.y = fmaxf(acc.y, 0.f); acc.z = fmaxf(acc.z, 0.f); acc.w = fmaxf(acc.w, 0.f); }
-    const uint2 o = make_uint2((uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16),
-                               (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16));
+    uint2 o = make_uint2((uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16),
+                         (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16));
+    if (mask != nullptr) {
+        const uint2 mk = *reinterpret_cast<const uint2 *>(mask + i4);
+        o = make_uint2(mask_bf16x2(o.x, mk.x), mask_bf16x2(o.y, mk.y));
+    }
     *reinterpret_cast<uint2 *>(out + i4) = o;
 }
 
+// One GEMM (output pixels numbered like the GEMM rows, Co % 8 == 0) run as `sp` splits of the reduction
+// plus the finishing kernel, which applies `post`.
+int launch_split(int tc, IgemmParams p, long long M, int sp, void *split_ws, void *out, const PostOp &post, hipStream_t st,
+                 const char **variant)
+{
+    p.splits = sp;
+    p.partial = (float *)split_ws;
+    p.bias = nullptr; p.relu = 0; p.mask = nullptr;      // applied by the finishing kernel
+    const int rc = launch_choice(tc, p, st);
+    if (rc != MXC_OK) return rc;
+    const long long MC = M * p.Co;
+    if ((MC / 4 + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+    // the launcher evens out the stage ranges, which can lower the split count: recompute it the same way
+    const int bk = tc == 5 ? 32 : 64;
+    const int KT = (p.TR * p.TS * p.Ci + bk - 1) / bk, per = (KT + sp - 1) / sp, used = (KT + per - 1) / per;
+    static thread_local char split_name[64];
+    snprintf(split_name, sizeof(split_name), "%s_split%d", kTiles[tc].name, used);
+    *variant = split_name;
+    hipLaunchKernelGGL(split_finish_kernel, dim3((unsigned)((MC / 4 + 255) / 256)), dim3(256), 0, st, (const float *)split_ws,
+                       (bf16_t *)out, MC, p.Co, used, post.bias, post.relu, (const bf16_t *)post.mask);
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
 }  // namespace
+
+size_t igemm_bwd_data_split_bytes(const ConvShape &s)
+{
+    if (s.stride != 1 || s.C % 8 != 0) return 0;       // one residue class, output numbered like the GEMM rows
+    const long long M = (long long)s.N * s.H * s.W;
+    const int sp = split_count(M, s.C, s.R * s.S * s.K);
+    return sp > 1 ? (size_t)sp * M * s.C * sizeof(float) : 0;
+}
 
 size_t igemm_fwd_split_bytes(const ConvShape &s)
 {
@@ -676,24 +712,7 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
     const int tc = choose_tile(M, s.K, s.R * s.S * s.C);
     *variant = kTiles[tc].name;
     const int sp = (split_ws != nullptr && s.K % 8 == 0) ? split_count(M, s.K, s.R * s.S * s.C) : 1;
-    if (sp > 1) {
-        p.splits = sp;
-        p.partial = (float *)split_ws;
-        p.bias = nullptr; p.relu = 0;                 // applied by the finishing kernel
-        const int rc = launch_choice(tc, p, st);
-        if (rc != MXC_OK) return rc;
-        const long long MC = M * s.K;
-        if ((MC / 4 + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
-        // the launcher may have lowered the split count: recompute it the same way
-        const int bk = tc == 5 ? 32 : 64;
-        const int KT = (s.R * s.S * s.C + bk - 1) / bk, per = (KT + sp - 1) / sp, used = (KT + per - 1) / per;
-        static thread_local char split_name[64];
-        snprintf(split_name, sizeof(split_name), "%s_split%d", kTiles[tc].name, used);
-        *variant = split_name;
-        hipLaunchKernelGGL(split_finish_kernel, dim3((unsigned)((MC / 4 + 255) / 256)), dim3(256), 0, st, (const float *)split_ws,
-                           (bf16_t *)y, MC, s.K, used, post.bias, post.relu);
-        return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
-    }
+    if (sp > 1) return launch_split(tc, p, M, sp, split_ws, y, post, st, variant);
     return launch_choice(tc, p, st);
 }
 
@@ -733,12 +752,18 @@ bool igemm_bwd_data_supported(const ConvShape &s)
 size_t igemm_bwd_data_workspace(const ConvShape &s) { return (size_t)s.K * s.R * s.S * s.C * sizeof(bf16_t); }
 
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
-                   const char **variant, const PostOp &post)
+                   const char **variant, const PostOp &post, void *split_ws)
 {
-    const int total = s.K * s.R * s.S * s.C;
-    hipLaunchKernelGGL(repack_bwd_data_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       (const bf16_t *)w, (bf16_t *)wt, s.K, s.C, s.R, s.S, s.stride);
-    if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
+    if (s.R == 1 && s.S == 1) {
+        // 1x1: the single class's matrix [C][K] is the transpose of w[K][C] (tiled transpose through LDS)
+        const int rc = launch_transpose(w, wt, 1, s.K, s.C, 2, st);
+        if (rc != MXC_OK) return rc;
+    } else {
+        const int total = s.K * s.R * s.S * s.C;
+        hipLaunchKernelGGL(repack_bwd_data_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           (const bf16_t *)w, (bf16_t *)wt, s.K, s.C, s.R, s.S, s.stride);
+        if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
+    }
     size_t wt_off = 0;
     int tc = 0;
     for (int ph = 0; ph < s.stride; ++ph) {
@@ -772,6 +797,10 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
                 continue;
             }
             tc = choose_tile((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
+            if (split_ws != nullptr && s.stride == 1 && s.C % 8 == 0) {
+                const int sp = split_count((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
+                if (sp > 1) return launch_split(tc, p, (long long)s.N * Mh * Mw, sp, split_ws, dx, post, st, variant);
+            }
             const int rc = launch_choice(tc, p, st);
             if (rc != MXC_OK) return rc;
         }

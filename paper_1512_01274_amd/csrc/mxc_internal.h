@@ -86,8 +86,9 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
               const PostOp &post = PostOp(), void *split_ws = nullptr);
 bool igemm_bwd_data_supported(const ConvShape &s);
 size_t igemm_bwd_data_workspace(const ConvShape &s);   // bytes for the re-packed filter
+size_t igemm_bwd_data_split_bytes(const ConvShape &s);   // scratch for a split reduction (0: never split)
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
-                   const char **variant, const PostOp &post = PostOp());
+                   const char **variant, const PostOp &post = PostOp(), void *split_ws = nullptr);
 
 // backward-data for C <= 4: G output columns form one GEMM row (see igemm.hip)
 bool igemm_bwd_data_smallc_supported(const ConvShape &s);

@@ -371,3 +371,20 @@ def test_split_reduction_forward(mxc, oracle, dims):
     mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, run._in(x), run._in(w), torch.from_numpy(bias).cuda(), 1, y, run._ws(mxc.MXC_FWD))
     got = run._out(y, (N, K, run.P, run.Q))
     assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), dims
+
+
+@pytest.mark.parametrize("dims", [(64, 256, 1, 1, 2048, 1, 1, 1, 0), (128, 520, 1, 1, 1024, 1, 1, 1, 0)] + SPLIT_SHAPES[2:4])
+def test_split_reduction_backward_data(mxc, oracle, dims):
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy, _ = _fused_case(dims, "bf16", (hash(dims) + 5) & 0xFFFF)
+    check_all_passes(mxc, oracle, dims, "bf16", "nhwc", x, w, dy, passes=("bwd_data",))
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    a = run.bwd_data(dy, w, return_tensor=True)
+    assert "_split" in mxc.mxc_last_variant(), mxc.mxc_last_variant()
+    assert torch.equal(a.view(torch.int16), run.bwd_data(dy, w, return_tensor=True).view(torch.int16))
+    ref, den = oracle.conv2d_bwd_data_relu(dy, w, x, st, pad)
+    dx = torch.full((N * C * H * W,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    mxc.mxc_conv2d_bwd_data_relu(*dims, run.dt, run.lay, run._in(dy), run._in(w), run._in(x), dx, run._ws(mxc.MXC_BWD_DATA_RELU))
+    got = run._out(dx, (N, C, H, W))
+    assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), dims
+    assert not got[x <= 0].any()
