@@ -206,3 +206,38 @@ def sgd_update(w, g, v, lr, momentum, wd):
     v = np.zeros_like(w) if v is None else np.asarray(v, dtype=np.float64)
     v2 = momentum * v - lr * (g + wd * w)
     return w + v2, v2
+
+
+# ---- FullyConnected (the layer of the paper's running example, Section 2.1) ---------------------
+# y[n, k] = sum_c x[n, c] * w[k, c] (+ bias[k], optional ReLU) and its derivatives, written as the
+# matrix products they are, in float64.  Each returns (value, D) with D the sum of |a||b| of the
+# same terms (plus |bias| forward).
+
+def fc_fwd(x, w, bias=None, relu=False):
+    x = np.asarray(x, dtype=np.float64); w = np.asarray(w, dtype=np.float64)
+    if x.ndim != 2 or w.ndim != 2 or x.shape[1] != w.shape[1]:
+        raise ValueError("x must be [N, C], w [K, C]")
+    z = x @ w.T
+    den = np.abs(x) @ np.abs(w).T
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64)
+        z = z + b[None, :]
+        den = den + np.abs(b)[None, :]
+    return (np.maximum(z, 0.0) if relu else z), den
+
+
+def fc_bwd_data(dy, w, x_mask=None):
+    """dx = dy @ w; with x_mask (the layer's input, a ReLU output) dx is 0 where x_mask <= 0."""
+    dy = np.asarray(dy, dtype=np.float64); w = np.asarray(w, dtype=np.float64)
+    g = dy @ w
+    den = np.abs(dy) @ np.abs(w)
+    if x_mask is not None:
+        keep = np.asarray(x_mask) > 0
+        g = np.where(keep, g, 0.0); den = np.where(keep, den, 0.0)
+    return g, den
+
+
+def fc_bwd_weight(x, dy):
+    """dw[k, c] = sum_n dy[n, k] * x[n, c]."""
+    x = np.asarray(x, dtype=np.float64); dy = np.asarray(dy, dtype=np.float64)
+    return dy.T @ x, np.abs(dy).T @ np.abs(x)

@@ -431,3 +431,35 @@ def test_sgd_update_closed_forms(oracle):
     for _ in range(7):
         w, _ = oracle.sgd_update(w, np.zeros_like(w0), None, 0.5, 0.0, 0.25)
     np.testing.assert_allclose(w, w0 * (1 - 0.5 * 0.25) ** 7, rtol=1e-13)
+
+
+# ---- FullyConnected --------------------------------------------------------------------------------
+
+def test_fc_is_a_1x1_convolution_on_a_1x1_image(oracle):
+    """The matrix-product forms against the seven-loop convolution nests on H = W = R = S = 1, which
+    share nothing with numpy's matmul; plus torch's linear layer and its autograd."""
+    torch = pytest.importorskip("torch")
+    N, C, K = 5, 7, 4
+    x, w, dy = _rand((N, C), 71), _rand((K, C), 72), _rand((N, K), 73)
+    bias = _rand((K,), 74)
+    y, den = oracle.fc_fwd(x, w)
+    assert np.array_equal(y, oracle.conv2d_fwd(x.reshape(N, C, 1, 1), w.reshape(K, C, 1, 1), 1, 0).reshape(N, K))
+    assert np.array_equal(den, oracle.conv2d_fwd(np.abs(x).reshape(N, C, 1, 1), np.abs(w).reshape(K, C, 1, 1), 1, 0).reshape(N, K))
+    dx, _ = oracle.fc_bwd_data(dy, w)
+    assert np.array_equal(dx, oracle.conv2d_bwd_data(dy.reshape(N, K, 1, 1), w.reshape(K, C, 1, 1), (N, C, 1, 1), 1, 0).reshape(N, C))
+    dw, _ = oracle.fc_bwd_weight(x, dy)
+    assert np.array_equal(dw, oracle.conv2d_bwd_weight(x.reshape(N, C, 1, 1), dy.reshape(N, K, 1, 1), (K, C, 1, 1), 1, 0).reshape(K, C))
+    tx = torch.tensor(np.maximum(x, 0), dtype=torch.float64)
+    pre = torch.tensor(np.where(x > 0, x, -1.0), dtype=torch.float64, requires_grad=True)
+    tw = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    tb = torch.tensor(bias, dtype=torch.float64)
+    out = torch.relu(torch.nn.functional.linear(torch.relu(pre), tw, tb))
+    a, _ = oracle.fc_fwd(np.maximum(x, 0), w, bias, True)
+    np.testing.assert_allclose(a, out.detach().numpy(), rtol=1e-13, atol=1e-13)
+    lin = torch.nn.functional.linear(torch.relu(pre), tw, tb)
+    lin.backward(torch.tensor(dy, dtype=torch.float64))
+    g, _ = oracle.fc_bwd_data(dy, w, np.maximum(x, 0))
+    np.testing.assert_allclose(g, pre.grad.numpy(), rtol=1e-13, atol=1e-13)
+    gw, _ = oracle.fc_bwd_weight(np.maximum(x, 0), dy)
+    np.testing.assert_allclose(gw, tw.grad.numpy(), rtol=1e-13, atol=1e-13)
+    assert tx.shape == (N, C)
