@@ -138,6 +138,26 @@ int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * FullyConnected (the layer of the paper's running example, Section 2.1), run through the same
+ * matrix-core GEMM as the convolutions: it is the convolution with H = W = R = S = 1, for which NCHW
+ * and NHWC coincide.  x: [N][C], w: [K][C], y / dy: [N][K], all of `dtype`; dw: [K][C] fp32.
+ *   forward:         y[n,k]  = act( sum_c x[n,c] * w[k,c] + bias[k] )     (bias may be NULL; relu 0 or 1)
+ *   backward-data:   dx[n,c] = sum_k dy[n,k] * w[k,c],  set to 0 where x_mask[n,c] <= 0 if x_mask != NULL
+ *                    (x_mask: the layer's input when that is a ReLU output)
+ *   backward-weight: dw[k,c] = sum_n dy[n,k] * x[n,c]
+ * Problems of a few hundred rows split their long reduction over workgroups (fp32 partial sums added
+ * in a fixed order: deterministic).  Workspace: mxc_conv2d_workspace_bytes(pass, N, C, 1, 1, K, 1, 1,
+ * 1, 0, dtype, MXC_NHWC, ...) with pass MXC_FWD, MXC_BWD_DATA_RELU (with or without mask) or
+ * MXC_BWD_WEIGHT.  Ownership, stream and error behaviour as the convolution entry points.
+ */
+int mxc_fc_fwd(int N, int C, int K, int dtype, const void *x, const void *w, const float *bias, int relu, void *y,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+int mxc_fc_bwd_data(int N, int C, int K, int dtype, const void *dy, const void *w, const void *x_mask, void *dx,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+int mxc_fc_bwd_weight(int N, int C, int K, int dtype, const void *x, const void *dy, void *dw,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The weight update that consumes dw (the paper's  w = w - eta*g  of Section 2.2, with the
  * momentum and weight decay of its Section 4 experiment; the paper does not print the momentum
  * form, the classic one is used):

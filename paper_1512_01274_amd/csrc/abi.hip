@@ -359,6 +359,27 @@ int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout, const void 
     return bias_grad(N, K, (long long)P * Q, dtype, layout, dy, db, (float *)workspace, (hipStream_t)hip_stream);
 }
 
+int mxc_fc_fwd(int N, int C, int K, int dtype, const void *x, const void *w, const float *bias, int relu, void *y,
+               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return mxc_conv2d_fwd_bias_act(N, C, 1, 1, K, 1, 1, 1, 0, dtype, MXC_NHWC, x, w, bias, relu, y, workspace, workspace_bytes,
+                                   hip_stream);
+}
+
+int mxc_fc_bwd_data(int N, int C, int K, int dtype, const void *dy, const void *w, const void *x_mask, void *dx,
+                    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    PostOp post;
+    post.mask = x_mask;
+    return entry(MXC_BWD_DATA, N, C, 1, 1, K, 1, 1, 1, 0, dtype, MXC_NHWC, dy, w, dx, post, workspace, workspace_bytes, hip_stream);
+}
+
+int mxc_fc_bwd_weight(int N, int C, int K, int dtype, const void *x, const void *dy, void *dw,
+                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return mxc_conv2d_bwd_weight(N, C, 1, 1, K, 1, 1, 1, 0, dtype, MXC_NHWC, x, dy, dw, workspace, workspace_bytes, hip_stream);
+}
+
 int mxc_sgd_update(size_t n, float *w, const float *g, float *v, void *w_bf16, float lr, float momentum, float wd, void *hip_stream)
 {
     if (n == 0) return MXC_ERR_SHAPE;

@@ -43,6 +43,12 @@ _lib.mxc_conv2d_bwd_data_relu.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP, _VP, _
 _lib.mxc_conv2d_bwd_data_relu.restype = _I
 _lib.mxc_bias_grad.argtypes = [_I] * 6 + [_VP, _VP, _VP, _SZ, _VP]
 _lib.mxc_bias_grad.restype = _I
+_lib.mxc_fc_fwd.argtypes = [_I] * 4 + [_VP, _VP, _VP, _I, _VP, _VP, _SZ, _VP]
+_lib.mxc_fc_fwd.restype = _I
+_lib.mxc_fc_bwd_data.argtypes = [_I] * 4 + [_VP, _VP, _VP, _VP, _VP, _SZ, _VP]
+_lib.mxc_fc_bwd_data.restype = _I
+_lib.mxc_fc_bwd_weight.argtypes = [_I] * 4 + [_VP, _VP, _VP, _VP, _SZ, _VP]
+_lib.mxc_fc_bwd_weight.restype = _I
 _F = ctypes.c_float
 _lib.mxc_sgd_update.argtypes = [_SZ, _VP, _VP, _VP, _VP, _F, _F, _F, _VP]
 _lib.mxc_sgd_update.restype = _I
@@ -143,6 +149,27 @@ def mxc_conv2d_bwd_data_relu(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy
 def mxc_bias_grad(N, K, P, Q, dtype, layout, dy, db, workspace=None, stream=None):
     ws_ptr, ws_bytes = _ws(workspace)
     rc = _lib.mxc_bias_grad(N, K, P, Q, dtype, layout, _ptr(dy), _ptr(db), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_fc_fwd(N, C, K, dtype, x, w, bias, relu, y, workspace=None, stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_fc_fwd(N, C, K, dtype, _ptr(x), _ptr(w), _ptr(bias), int(relu), _ptr(y), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_fc_bwd_data(N, C, K, dtype, dy, w, x_mask, dx, workspace=None, stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_fc_bwd_data(N, C, K, dtype, _ptr(dy), _ptr(w), _ptr(x_mask), _ptr(dx), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_fc_bwd_weight(N, C, K, dtype, x, dy, dw, workspace=None, stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_fc_bwd_weight(N, C, K, dtype, _ptr(x), _ptr(dy), _ptr(dw), ws_ptr, ws_bytes, _stream(stream))
     if rc != MXC_OK:
         raise MxcError(rc)
 

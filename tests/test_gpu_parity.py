@@ -388,3 +388,45 @@ def test_split_reduction_backward_data(mxc, oracle, dims):
     got = run._out(dx, (N, C, H, W))
     assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), dims
     assert not got[x <= 0].any()
+
+
+# ---- FullyConnected entry points --------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,C,K", [(128, 1024, 512), (64, 2048, 264), (5, 24, 40), (32, 136, 72), (256, 64, 16)])
+def test_fully_connected(mxc, oracle, N, C, K, dtype):
+    rng = np.random.Generator(np.random.Philox(key=gen.SEED + N * C + K))
+    rnd = lambda *shape: (gen.round_to_bf16(rng.standard_normal(shape).astype(np.float32)) if dtype == "bf16"
+                          else rng.standard_normal(shape).astype(np.float32))
+    x = np.maximum(rnd(N, C), 0.0).astype(np.float32)
+    w, dy = rnd(K, C) * np.float32(0.125), rnd(N, K)
+    w = gen.round_to_bf16(w) if dtype == "bf16" else w
+    bias = rng.standard_normal(K).astype(np.float32)
+    dt = mxc.MXC_BF16 if dtype == "bf16" else mxc.MXC_F32
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dims = (N, C, 1, 1, K, 1, 1, 1, 0)
+    ws = lambda op: mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *dims, dt, mxc.MXC_NHWC))
+    dev = lambda a: gen.to_device(a, dtype)
+    out_bf16 = dtype == "bf16"
+
+    y = torch.full((N * K,), float("nan"), dtype=td, device="cuda")
+    mxc.mxc_fc_fwd(N, C, K, dt, dev(x), dev(w), torch.from_numpy(bias).cuda(), 1, y, ws(mxc.MXC_FWD))
+    ref, den = oracle.fc_fwd(x, w, bias, True)
+    got = gen.to_host_f64(y).reshape(N, K)
+    assert util.metric(got, ref, den) <= util.TOL[dtype]
+    assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, dtype, out_bf16))
+
+    for mask in (None, x):
+        dx = torch.full((N * C,), float("nan"), dtype=td, device="cuda")
+        mxc.mxc_fc_bwd_data(N, C, K, dt, dev(dy), dev(w), None if mask is None else dev(mask), dx, ws(mxc.MXC_BWD_DATA_RELU))
+        ref, den = oracle.fc_bwd_data(dy, w, mask)
+        got = gen.to_host_f64(dx).reshape(N, C)
+        assert util.metric(got, ref, den) <= util.TOL[dtype]
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, dtype, out_bf16))
+
+    dw = torch.full((K * C,), float("nan"), dtype=torch.float32, device="cuda")
+    mxc.mxc_fc_bwd_weight(N, C, K, dt, dev(x), dev(dy), dw, ws(mxc.MXC_BWD_WEIGHT))
+    ref, den = oracle.fc_bwd_weight(x, dy)
+    got = dw.cpu().numpy().astype(np.float64).reshape(K, C)
+    assert util.metric(got, ref, den) <= util.TOL[dtype]
+    assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, dtype, False))
