@@ -241,3 +241,20 @@ def fc_bwd_weight(x, dy):
     """dw[k, c] = sum_n dy[n, k] * x[n, c]."""
     x = np.asarray(x, dtype=np.float64); dy = np.asarray(dy, dtype=np.float64)
     return dy.T @ x, np.abs(dy).T @ np.abs(x)
+
+
+# ---- Softmax output layer (the last layer of the paper's running example, Section 2.1) ---------------
+# Forward: p[n, k] = exp(z[n, k]) / sum_j exp(z[n, j]).  As an output (loss) layer its gradient with
+# respect to z for the cross-entropy against integer labels is (p - onehot(label)) * scale.
+
+def softmax_fwd(z):
+    z = np.asarray(z, dtype=np.float64)
+    e = np.exp(z - z.max(axis=1, keepdims=True))
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def softmax_xent_bwd(p, labels, scale=1.0):
+    p = np.asarray(p, dtype=np.float64)
+    g = p.copy()
+    g[np.arange(p.shape[0]), np.asarray(labels, dtype=np.int64)] -= 1.0
+    return g * scale

@@ -463,3 +463,22 @@ def test_fc_is_a_1x1_convolution_on_a_1x1_image(oracle):
     gw, _ = oracle.fc_bwd_weight(np.maximum(x, 0), dy)
     np.testing.assert_allclose(gw, tw.grad.numpy(), rtol=1e-13, atol=1e-13)
     assert tx.shape == (N, C)
+
+
+# ---- Softmax output layer ----------------------------------------------------------------------------
+
+def test_softmax_closed_forms_and_torch(oracle):
+    torch = pytest.importorskip("torch")
+    z = _rand((6, 9), 81).astype(np.float64) * 3
+    p = oracle.softmax_fwd(z)
+    np.testing.assert_allclose(p.sum(axis=1), 1.0, rtol=1e-15)
+    np.testing.assert_allclose(oracle.softmax_fwd(z + 1000.0), p, rtol=1e-12)              # shift invariance, no overflow
+    np.testing.assert_allclose(oracle.softmax_fwd(np.zeros((2, 8))), 1.0 / 8)              # uniform
+    two = oracle.softmax_fwd(np.array([[0.75, -0.5]]))
+    np.testing.assert_allclose(two[0, 0], 1.0 / (1.0 + np.exp(-1.25)), rtol=1e-15)         # two classes: the logistic function
+    np.testing.assert_allclose(p, torch.softmax(torch.tensor(z), dim=1).numpy(), rtol=1e-13)
+    labels = np.array([0, 8, 3, 3, 5, 1])
+    tz = torch.tensor(z, requires_grad=True)
+    torch.nn.functional.cross_entropy(tz, torch.tensor(labels), reduction="sum").backward()
+    np.testing.assert_allclose(oracle.softmax_xent_bwd(p, labels), tz.grad.numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(oracle.softmax_xent_bwd(p, labels, 0.25).sum(axis=1), 0.0, atol=1e-15)   # rows of the gradient sum to 0
