@@ -158,6 +158,17 @@ int mxc_fc_bwd_weight(int N, int C, int K, int dtype, const void *x, const void 
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Softmax output layer (the last layer of the paper's running example, Section 2.1).
+ *   forward:   p[n,k] = exp(z[n,k] - max_j z[n,j]) / sum_j exp(z[n,j] - max_j z[n,j])      z, p: [N][K] of `dtype`
+ *   backward:  dz[n,k] = (p[n,k] - (k == labels[n])) * scale        the gradient of the cross-entropy against integer
+ *              labels (device int32, values in [0, K); a value outside selects no class), times `scale` (e.g. 1/N)
+ * Arithmetic in fp32, one rounding to `dtype`.  No workspace.  Errors: MXC_ERR_SHAPE, MXC_ERR_UNSUPPORTED,
+ * MXC_ERR_NULL, MXC_ERR_ALIGN (16 bytes for tensors, 4 for labels), MXC_ERR_LAUNCH.
+ */
+int mxc_softmax_fwd(int N, int K, int dtype, const void *z, void *p, void *hip_stream);
+int mxc_softmax_xent_bwd(int N, int K, int dtype, const void *p, const int *labels, float scale, void *dz, void *hip_stream);
+
+/*
  * The weight update that consumes dw (the paper's  w = w - eta*g  of Section 2.2, with the
  * momentum and weight decay of its Section 4 experiment; the paper does not print the momentum
  * form, the classic one is used):

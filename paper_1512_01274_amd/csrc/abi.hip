@@ -380,6 +380,24 @@ int mxc_fc_bwd_weight(int N, int C, int K, int dtype, const void *x, const void 
     return mxc_conv2d_bwd_weight(N, C, 1, 1, K, 1, 1, 1, 0, dtype, MXC_NHWC, x, dy, dw, workspace, workspace_bytes, hip_stream);
 }
 
+int mxc_softmax_fwd(int N, int K, int dtype, const void *z, void *p, void *hip_stream)
+{
+    if (N <= 0 || K <= 0) return MXC_ERR_SHAPE;
+    if (dtype != MXC_F32 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
+    if (!z || !p) return MXC_ERR_NULL;
+    if (misaligned(z) || misaligned(p)) return MXC_ERR_ALIGN;
+    return softmax_fwd(N, K, dtype, z, p, (hipStream_t)hip_stream);
+}
+
+int mxc_softmax_xent_bwd(int N, int K, int dtype, const void *p, const int *labels, float scale, void *dz, void *hip_stream)
+{
+    if (N <= 0 || K <= 0) return MXC_ERR_SHAPE;
+    if (dtype != MXC_F32 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
+    if (!p || !labels || !dz) return MXC_ERR_NULL;
+    if (misaligned(p) || misaligned(dz) || ((uintptr_t)labels & 3u)) return MXC_ERR_ALIGN;
+    return softmax_xent_bwd(N, K, dtype, p, labels, dz, scale, (hipStream_t)hip_stream);
+}
+
 int mxc_sgd_update(size_t n, float *w, const float *g, float *v, void *w_bf16, float lr, float momentum, float wd, void *hip_stream)
 {
     if (n == 0) return MXC_ERR_SHAPE;

@@ -65,6 +65,10 @@ int probe_mfma(int workgroups, int iters, float *out, double *flops, hipStream_t
 // ---- update.hip: SGD with momentum and weight decay on fp32 master weights -------------
 int sgd_update(size_t n, float *w, const float *g, float *v, void *w_copy, float lr, float momentum, float wd, hipStream_t st);
 
+// ---- softmax.hip: softmax output layer --------------------------------------------------
+int softmax_fwd(int N, int K, int dtype, const void *z, void *p, hipStream_t st);
+int softmax_xent_bwd(int N, int K, int dtype, const void *p, const int *labels, void *dz, float scale, hipStream_t st);
+
 // ---- bias.hip: bias gradient ------------------------------------------------------------
 int bias_grad_parts(long long N, int K, long long PQ, int layout);      // partial vectors of K floats the call needs as scratch
 int bias_grad(long long N, int K, long long PQ, int dtype, int layout, const void *dy, float *db, float *partial, hipStream_t st);

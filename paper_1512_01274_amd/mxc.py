@@ -49,6 +49,10 @@ _lib.mxc_fc_bwd_data.argtypes = [_I] * 4 + [_VP, _VP, _VP, _VP, _VP, _SZ, _VP]
 _lib.mxc_fc_bwd_data.restype = _I
 _lib.mxc_fc_bwd_weight.argtypes = [_I] * 4 + [_VP, _VP, _VP, _VP, _SZ, _VP]
 _lib.mxc_fc_bwd_weight.restype = _I
+_lib.mxc_softmax_fwd.argtypes = [_I, _I, _I, _VP, _VP, _VP]
+_lib.mxc_softmax_fwd.restype = _I
+_lib.mxc_softmax_xent_bwd.argtypes = [_I, _I, _I, _VP, _VP, ctypes.c_float, _VP, _VP]
+_lib.mxc_softmax_xent_bwd.restype = _I
 _F = ctypes.c_float
 _lib.mxc_sgd_update.argtypes = [_SZ, _VP, _VP, _VP, _VP, _F, _F, _F, _VP]
 _lib.mxc_sgd_update.restype = _I
@@ -170,6 +174,18 @@ def mxc_fc_bwd_data(N, C, K, dtype, dy, w, x_mask, dx, workspace=None, stream=No
 def mxc_fc_bwd_weight(N, C, K, dtype, x, dy, dw, workspace=None, stream=None):
     ws_ptr, ws_bytes = _ws(workspace)
     rc = _lib.mxc_fc_bwd_weight(N, C, K, dtype, _ptr(x), _ptr(dy), _ptr(dw), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_softmax_fwd(N, K, dtype, z, p, stream=None):
+    rc = _lib.mxc_softmax_fwd(N, K, dtype, _ptr(z), _ptr(p), _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_softmax_xent_bwd(N, K, dtype, p, labels, scale, dz, stream=None):
+    rc = _lib.mxc_softmax_xent_bwd(N, K, dtype, _ptr(p), _ptr(labels), scale, _ptr(dz), _stream(stream))
     if rc != MXC_OK:
         raise MxcError(rc)
 

@@ -430,3 +430,29 @@ def test_fully_connected(mxc, oracle, N, C, K, dtype):
     got = dw.cpu().numpy().astype(np.float64).reshape(K, C)
     assert util.metric(got, ref, den) <= util.TOL[dtype]
     assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, dtype, False))
+
+
+# ---- softmax output layer -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,K", [(1, 1), (3, 10), (128, 1000), (7, 4099)])
+def test_softmax(mxc, oracle, N, K, dtype):
+    rng = np.random.Generator(np.random.Philox(key=gen.SEED + 13 * N + K))
+    z = (rng.standard_normal((N, K)) * 4).astype(np.float32)
+    if dtype == "bf16":
+        z = gen.round_to_bf16(z)
+    labels = rng.integers(0, K, size=N).astype(np.int32)
+    dt = mxc.MXC_BF16 if dtype == "bf16" else mxc.MXC_F32
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    p = torch.full((N * K,), float("nan"), dtype=td, device="cuda")
+    mxc.mxc_softmax_fwd(N, K, dt, gen.to_device(z, dtype), p)
+    got = gen.to_host_f64(p).reshape(N, K)
+    ref = oracle.softmax_fwd(z)
+    # fp32 exp and a sum of K terms, then one rounding to the storage type
+    tol = 2.0 ** -8 if dtype == "bf16" else 1e-5
+    assert np.all(np.abs(got - ref) <= tol * ref + 1e-30)
+    dz = torch.full((N * K,), float("nan"), dtype=td, device="cuda")
+    mxc.mxc_softmax_xent_bwd(N, K, dt, p, torch.from_numpy(labels).cuda(), 0.5, dz)
+    gotg = gen.to_host_f64(dz).reshape(N, K)
+    refg = oracle.softmax_xent_bwd(got, labels, 0.5)          # from the probabilities the GPU stored
+    assert np.all(np.abs(gotg - refg) <= (2.0 ** -8 if dtype == "bf16" else 1e-6) * np.abs(refg) + 1e-30)
