@@ -488,17 +488,17 @@ int launch(IgemmParams p, hipStream_t st)
 // A tile shape the launcher can pick: output tile, workgroups that fit one CU at a time (LDS and
 // register budget) and the matrix-pipe utilisation it reaches relative to the 256x256 tile when the
 // chip is full (fitted to per-layer times of the AlexNet- and VGG-style stacks run back to back).
-struct TileChoice { int bm, bn, slots; float util; const char *name; };
+struct TileChoice { int bm, bn, bk, slots; float util; const char *name; };   // bk: reduction elements per stage
 const TileChoice kTiles[] = {
-    {128, 128, 2, 0.91f, "igemm_128x128_k64s2_w4"},
-    {256, 256, 1, 1.15f, "igemm_256x256_k64s2_w8"},
-    {256, 128, 1, 0.86f, "igemm_256x128_k64s3_w8"},
-    {128, 256, 1, 0.82f, "igemm_128x256_k64s3_w8"},
-    {128, 64, 3, 0.65f, "igemm_128x64_k64s2_w4"},
-    {256, 64, 2, 0.60f, "igemm_256x64_k32s3_w4"},
-    {128, 32, 4, 0.33f, "igemm_128x32_k64s2_w4"},
-    {256, 32, 2, 0.33f, "igemm_256x32_k64s2_w4"},
-    {256, 192, 1, 1.05f, "igemm_256x192_k64s2_w8"},
+    {128, 128, 64, 2, 0.91f, "igemm_128x128_k64s2_w4"},
+    {256, 256, 64, 1, 1.15f, "igemm_256x256_k64s2_w8"},
+    {256, 128, 64, 1, 0.86f, "igemm_256x128_k64s3_w8"},
+    {128, 256, 64, 1, 0.82f, "igemm_128x256_k64s3_w8"},
+    {128, 64, 64, 3, 0.65f, "igemm_128x64_k64s2_w4"},
+    {256, 64, 32, 2, 0.60f, "igemm_256x64_k32s3_w4"},
+    {128, 32, 64, 4, 0.33f, "igemm_128x32_k64s2_w4"},
+    {256, 32, 64, 2, 0.33f, "igemm_256x32_k64s2_w4"},
+    {256, 192, 64, 1, 1.05f, "igemm_256x192_k64s2_w8"},
 };
 constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -663,7 +663,7 @@ int launch_split(int tc, IgemmParams p, long long M, int sp, void *split_ws, voi
     const long long MC = M * p.Co;
     if ((MC / 4 + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
     // the launcher evens out the stage ranges, which can lower the split count: recompute it the same way
-    const int bk = tc == 5 ? 32 : 64;
+    const int bk = kTiles[tc].bk;
     const int KT = (p.TR * p.TS * p.Ci + bk - 1) / bk, per = (KT + sp - 1) / sp, used = (KT + per - 1) / per;
     static thread_local char split_name[64];
     snprintf(split_name, sizeof(split_name), "%s_split%d", kTiles[tc].name, used);
