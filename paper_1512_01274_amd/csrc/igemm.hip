@@ -30,6 +30,8 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
 
 constexpr int MAX_TAPS = 127;   // tap table capacity (11x11 = 121 fits)
 
@@ -49,6 +51,9 @@ struct IgemmParams {
     int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
     int m_tiles, n_tiles;
     unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
+    // BT kernels (1x1 stride-1 backward-data straight from the filter, no transposed copy): wm = w[K][Co];
+    // reduction index k reads filter row k, whose Co output columns are contiguous.  Needs Ci % 64 == 0.
+    unsigned bt_w_bytes; // size of the filter
     // split reduction (few tiles, long reduction): workgroup (tile, z) runs stages [z*split_stages, (z+1)*split_stages)
     // and stores its fp32 accumulators to partial[z][m][co]; a second kernel adds the splits in ascending z and
     // applies bias / ReLU / mask.  splits <= 1: off.
@@ -80,13 +85,24 @@ __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcn
 __device__ __forceinline__ void pin() { __builtin_amdgcn_sched_barrier(0); }   // nothing is scheduled across
 
 template <int I> using IC = std::integral_constant<int, I>;
+
+// Transposed filter tiles (BT kernels): XOR applied to the chunk index of tile row `row` (RC chunks of
+// 16 bytes per row) so that the four rows touched by one transposing read fall into different banks.
+template <int RC> __device__ __forceinline__ int bt_row_swz(int row)
+{
+    if constexpr (RC >= 16) return (row & 3) << 2;
+    else if constexpr (RC == 8) return ((row >> 1) & 1) << 2;
+    else return 0;
+}
 template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) { (f(IC<I>{}), ...); }
 template <int N, class F> __device__ __forceinline__ void static_for(F &&f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
 
 // BM x BN output tile, BKT reduction elements per stage, NS stages, WR x WC waves.  The register
 // budget is set for two waves per SIMD when the workgroup has 4 waves and its LDS lets two of them
 // share a CU.
-template <int BM, int BN, int BKT, int NS, int WR, int WC>
+// BT = true: the filter operand is read transposed, straight from w[K][Co] (1x1 filters): its LDS tile is
+// [reduction row][BN output columns] and its MFMA fragments come from ds_read_b64_tr_b16.
+template <int BM, int BN, int BKT, int NS, int WR, int WC, bool BT>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT * 2 <= 80 * 1024) ? 2 : 1) void igemm_kernel(
     const IgemmParams p)
 {
@@ -106,6 +122,9 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     static_assert(NW % 2 == 0 && BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "tile/wave mismatch");
     static_assert(L * (NS - 1) < 64, "vmcnt range");
     static_assert(KS % 2 == 0, "fragment ping-pong assumes an even number of k-steps");
+    constexpr int RCB = BN / 8;                   // BT: 16-byte chunks per filter-tile row
+    constexpr int RPLB = 64 / RCB;                // BT: filter-tile rows filled by one wave-wide load
+    static_assert(!BT || (BKT == 64 && RCB >= 4 && RCB <= 32 && BKT % (RPLB * NW) == 0 && BKT / RPLB / NW == B_LD), "BT tile/wave mismatch");
 
     // Every stage is its own LDS object (not one array indexed by the stage): the compiler can then
     // see that the direct loads filling one stage never alias the operand reads of another and does
@@ -196,10 +215,19 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         }
     }
     unsigned b_off[B_LD];   // byte offset of the filter row, OOB for rows past Co
+    // BT: lane -> row RPLB*i' + lane/RCB of the stage's 64 reduction rows, output-column chunk lane%RCB (swizzled);
+    // b_off = byte offset of (row, column chunk) relative to the stage's first filter row
+    [[maybe_unused]] const int lb_sub = lane / RCB;
+    [[maybe_unused]] const int lb_chunk = (lane % RCB) ^ bt_row_swz<RCB>(RPLB * wave + lb_sub);   // RPLB*NW*i never changes the swizzle
+    [[maybe_unused]] const bool bt_col_ok = n0 + lb_chunk * 8 < p.Co;
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
-        const int co = n0 + RPL * (wave + NW * i) + ld_sub;
-        b_off[i] = co < p.Co ? (unsigned)co * (unsigned)Kd * 2u : OOB;
+        if constexpr (BT) {
+            b_off[i] = (unsigned)((RPLB * (wave + NW * i) + lb_sub) * p.Co * 2 + (n0 + lb_chunk * 8) * 2);
+        } else {
+            const int co = n0 + RPL * (wave + NW * i) + ld_sub;
+            b_off[i] = co < p.Co ? (unsigned)co * (unsigned)Kd * 2u : OOB;
+        }
     }
     // Reduction position of this lane's chunk: kd = stage*BKT + ld_chunk*8 = tap*Ci + ci, kept as
     // (tap, ci) and advanced without branches: BKT = kq*Ci + kr.
@@ -232,7 +260,18 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
             const int bad = (__builtin_bit_cast(int, hw) | __builtin_bit_cast(int, d)) & (int)0x80008000;
             va[i] = bad == 0 ? (unsigned)(a_off[i] + tap_e.x + ci2) : OOB;
         } else {
-            if (p.tap_inner) {
+            if constexpr (BT) {
+                // one tap: stage s covers filter rows 64*s .. 64*s+63; kd2 tracks this lane's byte offset 2*(64*s + chunk*8)
+                const bool ok = bt_col_ok && kd2 < Kd2;
+                const unsigned base = (unsigned)((kd2 - ld_chunk * 16) / 2) * (unsigned)(p.Co * 2);
+#pragma unroll
+                for (int i = 0; i < B_LD; ++i) vb[i] = ok ? b_off[i] + base : OOB;
+                kd2 += BKT * 2;
+                ci2 += kr2;
+                const int carry = ci2 >= Ci2 ? 1 : 0;
+                ci2 -= carry ? Ci2 : 0;
+                tap += kq + carry;
+            } else if (p.tap_inner) {
                 // Order (channel block, tap): the pixels a workgroup reads for one channel block serve all
                 // its taps back to back, so they are still in the XCD's L2 when the next tap asks for them.
                 const bool k_ok = tap < T;
@@ -260,7 +299,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     auto load_task = [&](auto t, bf16_t *dst_a, bf16_t *dst_b) {
         constexpr int Tk = decltype(t)::value;
         if constexpr (Tk < A_LD) load16_to_lds(rs_in, va[Tk], dst_a + (wave + NW * Tk) * RPL * BKT);
-        else load16_to_lds(rs_wm, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * RPL * BKT);
+        else load16_to_lds(rs_wm, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * (BT ? RPLB * BN : RPL * BKT));
     };
 
     f32x16 acc[MI][NI];
@@ -276,12 +315,31 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     const int frag_swz = (frag_row / RB) % CH;     // block bases are multiples of 32 rows
     const int a_lane = (wave_m + frag_row) * BKT, b_lane = (wave_n + frag_row) * BKT;
 
+    // BT: transposing-read geometry (16-lane group g, lane j16 within it; one read covers 4 reduction rows x
+    // 16 output columns): element offsets of the two reads of a 16-row k-step for each of the NI column blocks
+    [[maybe_unused]] int bt_lo[NI], bt_hi[NI];
+    if constexpr (BT) {
+        const int g = lane >> 4, j16 = lane & 15;
+        const int tr_row = (g >> 1) * 8 + (j16 >> 2);
+        const int tr_ch = (g & 1) * 16 + (j16 & 3) * 4;
+        auto tr_off = [&](int ch_base, int row) {
+            const int ch = ch_base + tr_ch;
+            return row * BN + (((ch >> 3) ^ bt_row_swz<RCB>(row)) << 3) + (ch & 7);
+        };
+#pragma unroll
+        for (int j = 0; j < NI; ++j) { bt_lo[j] = tr_off(wave_n + j * 32, tr_row); bt_hi[j] = tr_off(wave_n + j * 32, tr_row + 4); }
+    }
     struct Frags { bf16x8 a[MI], b[NI]; };
     auto read_task = [&](auto t, Frags &f, const bf16_t *src_a, const bf16_t *src_b, int ks) {
         constexpr int Tk = decltype(t)::value;
         const int pos = ((ks * 2 + frag_kg) ^ frag_swz) << 3;
         if constexpr (Tk < MI) f.a[Tk] = *reinterpret_cast<const bf16x8 *>(src_a + a_lane + Tk * 32 * BKT + pos);
-        else f.b[Tk - MI] = *reinterpret_cast<const bf16x8 *>(src_b + b_lane + (Tk - MI) * 32 * BKT + pos);
+        else if constexpr (BT) {
+            const bf16_t *q = src_b + ks * 16 * BN;
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(q + bt_lo[Tk - MI]));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(q + bt_hi[Tk - MI]));
+            f.b[Tk - MI] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        } else f.b[Tk - MI] = *reinterpret_cast<const bf16x8 *>(src_b + b_lane + (Tk - MI) * 32 * BKT + pos);
     };
     constexpr int N_READ = MI + NI;
 
@@ -457,7 +515,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     }
 }
 
-template <int BM, int BN, int BKT, int NS, int WR, int WC>
+template <int BM, int BN, int BKT, int NS, int WR, int WC, bool BT = false>
 int launch(IgemmParams p, hipStream_t st)
 {
     const long long M = (long long)p.N * p.Mh * p.Mw;
@@ -467,7 +525,7 @@ int launch(IgemmParams p, hipStream_t st)
     p.M = (int)M;
     p.m_tiles = (int)mt;
     p.in_bytes = (unsigned)((long long)p.N * p.Hi * p.Wi * p.pix * 2);
-    p.wm_bytes = (unsigned)((long long)p.Co * p.TR * p.TS * p.Ci * 2);
+    p.wm_bytes = BT ? p.bt_w_bytes : (unsigned)((long long)p.Co * p.TR * p.TS * p.Ci * 2);
     // MXC_TAP_OUTER=1 (tuning only) keeps the filter's own order, all channels of a tap before the next tap
     p.tap_inner = (p.Ci % BKT == 0 && p.TR * p.TS > 1 && !getenv("MXC_TAP_OUTER")) ? 1 : 0;
     p.linear_out = (p.out_mul_h == 1 && p.out_mul_w == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
@@ -481,7 +539,7 @@ int launch(IgemmParams p, hipStream_t st)
     const long long total = (long long)p.m_tiles * p.n_tiles * (p.splits > 1 ? p.splits : 1);
     if (total > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
     const int grid = (int)((total + 7) / 8) * 8;
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, BKT, NS, WR, WC>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
+    hipLaunchKernelGGL((igemm_kernel<BM, BN, BKT, NS, WR, WC, BT>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
 
@@ -502,8 +560,19 @@ const TileChoice kTiles[] = {
 };
 constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
 
-int launch_choice(int idx, const IgemmParams &p, hipStream_t st)
+// the tiles that also exist reading a 1x1 filter in place (transposed tiles)
+bool has_bt(int idx) { return idx == 0 || idx == 1 || idx == 4; }
+
+int launch_choice(int idx, const IgemmParams &p, hipStream_t st, bool bt = false)
 {
+    if (bt) {
+        switch (idx) {
+        case 0: return launch<128, 128, 64, 2, 2, 2, true>(p, st);
+        case 1: return launch<256, 256, 64, 2, 2, 4, true>(p, st);
+        case 4: return launch<128, 64, 64, 2, 2, 2, true>(p, st);
+        default: return MXC_ERR_UNSUPPORTED;
+        }
+    }
     switch (idx) {
     case 0: return launch<128, 128, 64, 2, 2, 2>(p, st);
     case 1: return launch<256, 256, 64, 2, 2, 4>(p, st);
@@ -653,12 +722,12 @@ __global__ __launch_bounds__(256) void split_finish_kernel(const float *__restri
 // One GEMM (output pixels numbered like the GEMM rows, Co % 8 == 0) run as `sp` splits of the reduction
 // plus the finishing kernel, which applies `post`.
 int launch_split(int tc, IgemmParams p, long long M, int sp, void *split_ws, void *out, const PostOp &post, hipStream_t st,
-                 const char **variant)
+                 const char **variant, bool bt = false)
 {
     p.splits = sp;
     p.partial = (float *)split_ws;
     p.bias = nullptr; p.relu = 0; p.mask = nullptr;      // applied by the finishing kernel
-    const int rc = launch_choice(tc, p, st);
+    const int rc = launch_choice(tc, p, st, bt);
     if (rc != MXC_OK) return rc;
     const long long MC = M * p.Co;
     if ((MC / 4 + 255) / 256 > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
@@ -666,7 +735,7 @@ int launch_split(int tc, IgemmParams p, long long M, int sp, void *split_ws, voi
     const int bk = kTiles[tc].bk;
     const int KT = (p.TR * p.TS * p.Ci + bk - 1) / bk, per = (KT + sp - 1) / sp, used = (KT + per - 1) / per;
     static thread_local char split_name[64];
-    snprintf(split_name, sizeof(split_name), "%s_split%d", kTiles[tc].name, used);
+    snprintf(split_name, sizeof(split_name), "%s%s_split%d", kTiles[tc].name, bt ? "_inplace" : "", used);
     *variant = split_name;
     hipLaunchKernelGGL(split_finish_kernel, dim3((unsigned)((MC / 4 + 255) / 256)), dim3(256), 0, st, (const float *)split_ws,
                        (bf16_t *)out, MC, p.Co, used, post.bias, post.relu, (const bf16_t *)post.mask);
@@ -754,7 +823,12 @@ size_t igemm_bwd_data_workspace(const ConvShape &s) { return (size_t)s.K * s.R *
 int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
                    const char **variant, const PostOp &post, void *split_ws)
 {
-    if (s.R == 1 && s.S == 1) {
+    // A large 1x1 filter at stride 1 (FullyConnected) is read in place, as transposed tiles, when the chosen
+    // tile has that variant: copying it would cost more than the slower operand fetch.
+    const bool bt = s.R == 1 && s.S == 1 && s.stride == 1 && s.K % 64 == 0 && (long long)s.K * s.C * 2 >= (4ll << 20) &&
+                    has_bt(choose_tile((long long)s.N * s.H * s.W, s.C, s.K));
+    if (bt) {
+    } else if (s.R == 1 && s.S == 1) {
         // 1x1: the single class's matrix [C][K] is the transpose of w[K][C] (tiled transpose through LDS)
         const int rc = launch_transpose(w, wt, 1, s.K, s.C, 2, st);
         if (rc != MXC_OK) return rc;
@@ -777,8 +851,9 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
             const int Mh = h_first < s.H ? (s.H - 1 - h_first) / s.stride + 1 : 0;
             const int Mw = v_first < s.W ? (s.W - 1 - v_first) / s.stride + 1 : 0;
             IgemmParams p{};
-            p.in = (const bf16_t *)dy; p.wm = (const bf16_t *)wt + wt_off; p.out = (bf16_t *)dx;
+            p.in = (const bf16_t *)dy; p.wm = bt ? (const bf16_t *)w : (const bf16_t *)wt + wt_off; p.out = (bf16_t *)dx;
             p.mask = (const bf16_t *)post.mask;
+            p.bt_w_bytes = (unsigned)((long long)s.K * s.C * 2);
             p.N = s.N; p.Hi = s.P; p.Wi = s.Q; p.Ci = s.K; p.pix = s.K; p.Co = s.C;
             p.TR = TR; p.TS = TS; p.tstep_h = -1; p.tstep_w = -1;
             p.Mh = Mh; p.Mw = Mw;
@@ -799,9 +874,9 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
             tc = choose_tile((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
             if (split_ws != nullptr && s.stride == 1 && s.C % 8 == 0) {
                 const int sp = split_count((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
-                if (sp > 1) return launch_split(tc, p, (long long)s.N * Mh * Mw, sp, split_ws, dx, post, st, variant);
+                if (sp > 1) return launch_split(tc, p, (long long)s.N * Mh * Mw, sp, split_ws, dx, post, st, variant, bt);
             }
-            const int rc = launch_choice(tc, p, st);
+            const int rc = launch_choice(tc, p, st, bt);
             if (rc != MXC_OK) return rc;
         }
     }

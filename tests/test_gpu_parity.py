@@ -373,7 +373,10 @@ def test_split_reduction_forward(mxc, oracle, dims):
     assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), dims
 
 
-@pytest.mark.parametrize("dims", [(64, 256, 1, 1, 2048, 1, 1, 1, 0), (128, 520, 1, 1, 1024, 1, 1, 1, 0)] + SPLIT_SHAPES[2:4])
+@pytest.mark.parametrize("dims", [(64, 256, 1, 1, 2048, 1, 1, 1, 0), (128, 520, 1, 1, 1024, 1, 1, 1, 0),
+                                  (64, 2048, 1, 1, 1024, 1, 1, 1, 0),       # 4 MB filter: read in place (transposed tiles)
+                                  (32, 2056, 1, 1, 1024, 1, 1, 1, 0)]       # ... ragged output columns
+                         + SPLIT_SHAPES[2:4])
 def test_split_reduction_backward_data(mxc, oracle, dims):
     N, C, H, W, K, R, S, st, pad = dims
     x, w, dy, _ = _fused_case(dims, "bf16", (hash(dims) + 5) & 0xFFFF)
@@ -393,7 +396,7 @@ def test_split_reduction_backward_data(mxc, oracle, dims):
 # ---- FullyConnected entry points --------------------------------------------------------------
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("N,C,K", [(128, 1024, 512), (64, 2048, 264), (5, 24, 40), (32, 136, 72), (256, 64, 16)])
+@pytest.mark.parametrize("N,C,K", [(128, 1024, 512), (64, 2048, 264), (5, 24, 40), (32, 136, 72), (256, 64, 16), (128, 4096, 512)])
 def test_fully_connected(mxc, oracle, N, C, K, dtype):
     rng = np.random.Generator(np.random.Philox(key=gen.SEED + N * C + K))
     rnd = lambda *shape: (gen.round_to_bf16(rng.standard_normal(shape).astype(np.float32)) if dtype == "bf16"
