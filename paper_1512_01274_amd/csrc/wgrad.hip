@@ -530,10 +530,15 @@ int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *p
     p.dy_bytes = (unsigned)((long long)p.M * g.K * 2);
     const long long tiles = (long long)pl.k_tiles * pl.n_tiles;
     if (tiles * p.splits > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
-    const int rc = launch_choice(pl.tile, p, (int)tiles, st);
-    if (rc != MXC_OK) return rc;
     const int total = g.K * g.R * g.S * g.C;
     const bool identity = g.s2d == 1 && g.col_s == g.C && g.col_r == g.S * g.C && p.ncols == g.R * g.S * g.C;
+    // one split whose columns are already in KRSC order: the "partial" tensor is dw itself, nothing to reduce
+    const bool direct = p.splits == 1 && identity;
+    if (direct) p.partial = dw;
+    const int rc = launch_choice(pl.tile, p, (int)tiles, st);
+    if (rc != MXC_OK) return rc;
+    *variant = tc.name;
+    if (direct) return MXC_OK;
     if (p.splits > 16 && total < 256 * 1024)
         hipLaunchKernelGGL(wgrad_reduce_wide_kernel, dim3((unsigned)((total + 63) / 64)), dim3(1024), 0, st, partial, dw, total,
                            p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq,
