@@ -101,8 +101,18 @@ CONFIGS: List[Config] = [
 ]
 
 
+# Beyond the benchmark's five configurations: the FullyConnected head of the AlexNet-style network
+# (1x1 "images": the layer is the convolution with H = W = R = S = 1), He-normal weights.
+EXTRA_CONFIGS: List[Config] = [
+    Config(5, "alexnet_head_b128", "bf16", "normal", (
+        _L("fc6", 128, 9216, 1, 4096, 1, 1, 0),
+        _L("fc7", 128, 4096, 1, 4096, 1, 1, 0),
+        _L("fc8", 128, 4096, 1, 1000, 1, 1, 0))),
+]
+
+
 def config_by_name(name: str) -> Config:
-    for c in CONFIGS:
+    for c in CONFIGS + EXTRA_CONFIGS:
         if c.name == name:
             return c
     raise KeyError(name)

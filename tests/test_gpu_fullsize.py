@@ -18,6 +18,8 @@ N_RANDOM = 8192
 WGRAD_MAC_BUDGET = 3e9      # oracle multiply-adds spent on one layer's backward-weight samples
 
 LAYERS = [(ci, li) for ci in (1, 2, 3, 4) for li in range(len(gen.CONFIGS[ci].layers))]
+HEAD = gen.config_by_name("alexnet_head_b128")            # FullyConnected head: split reductions, in-place filter reads
+LAYERS += [(HEAD.index, li) for li in range(len(HEAD.layers))]
 
 
 @pytest.fixture(scope="module")
@@ -68,7 +70,7 @@ def _check(name, got, ref, den, out_is_bf16, L):
 
 @pytest.mark.parametrize("ci,li", LAYERS)
 def test_full_size_sampled(mxc, oracle, ci, li):
-    cfg = gen.CONFIGS[ci]
+    cfg = gen.CONFIGS[ci] if ci < len(gen.CONFIGS) else HEAD
     L, t = gen.layer_inputs(cfg, li)
     x, w, dy = t["x"], t["w"], t["dy"]
     N, C, H, W, K, R, S, st, pad = L.dims()
