@@ -16,6 +16,13 @@
 // steps of BKT (32 or 64) through a ring of NS LDS stages that are filled by direct global->LDS
 // loads issued NS stages ahead of their use; 16-byte chunks are XOR-swizzled by row so that the
 // ds_read_b128 operand fetches are bank-conflict free.
+//
+// Reduction order: tap-major as the filter matrix is laid out, or, when Ci is a multiple of the
+// step, channel-block-major (all taps of a 64-channel block back to back: better L2 reuse).
+// Problems with few tiles and a long reduction (FullyConnected shapes) split the reduction over
+// workgroups into fp32 partial tiles that a finishing kernel adds in a fixed order.  A large 1x1
+// filter can be read in place for backward-data (BT kernels: transposed LDS tiles).  The epilogue
+// can add a bias, apply ReLU, and zero results under a mask.
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
