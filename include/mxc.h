@@ -33,7 +33,9 @@
  *     mxc_conv2d_workspace_bytes for the same arguments (may be NULL when that
  *     size is 0).  Its contents are undefined afterwards.  Two calls that share
  *     a workspace must be ordered on one stream.
- *   - Return value: MXC_OK or an error code; on error nothing was launched.
+ *   - Return value: MXC_OK or an error code.  Argument errors (every code but
+ *     MXC_ERR_LAUNCH) are found before anything is launched; after MXC_ERR_LAUNCH
+ *     some of the call's kernels may already be queued and the output is undefined.
  *     No call throws, aborts or exits.  Shapes are checked before pointers.
  */
 #ifndef MXC_H
