@@ -459,3 +459,4 @@ def test_softmax(mxc, oracle, N, K, dtype):
     gotg = gen.to_host_f64(dz).reshape(N, K)
     refg = oracle.softmax_xent_bwd(got, labels, 0.5)          # from the probabilities the GPU stored
     assert np.all(np.abs(gotg - refg) <= (2.0 ** -8 if dtype == "bf16" else 1e-6) * np.abs(refg) + 1e-30)
+
