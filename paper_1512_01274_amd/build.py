@@ -13,8 +13,11 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmxc.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# Packed-fp32 VALU forms (v_pk_fma_f32 and its like) are kept off for every HIP file of this library.
+# The device pass honours the feature switch (a float2 fma compiles to v_pk_fma_f32 without it and to two
+# v_fma_f32 with it); the host pass of the same hipcc line does not know the feature and says so in a
+# warning, which is left in the log as it is.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         # packed-fp32 VALU forms are kept off for every HIP file of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
@@ -35,10 +38,8 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
-        noise = "'-packed-fp32-ops' is not a recognized feature"
-        err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
-        if verbose and err.strip():
-            print(err, flush=True)
+        if verbose and r.stderr.strip():
+            print(r.stderr, flush=True)
 
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(srcs)))) as ex:
         list(ex.map(compile_one, zip(srcs, objs)))

@@ -79,17 +79,14 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 constexpr unsigned OOB = 0x80000000u;   // a buffer offset no operand reaches: the load returns zeros
 
-// One wave-wide direct global->LDS transfer through a buffer descriptor: lane l's 16 bytes land at
-// lds_base + 16*l.  Lanes whose byte offset is outside the buffer (OOB) deposit zeros, which is how
-// padding, ragged tile edges and the tail of the reduction are filled.
-__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off, bf16_t *lds_base_uniform)
-{
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_vptr)lds_base_uniform, 16, byte_off, 0, 0, 0);
-}
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void pin() { __builtin_amdgcn_sched_barrier(0); }   // nothing is scheduled across
+// Workgroup barrier of the ring: the bare instruction, with the counters it needs waited for by hand just before
+// it.  __syncthreads() would add a release fence, which the compiler turns into a wait for every outstanding
+// global->LDS load (vmcnt(0)) - that empties a ring of more than two stages at every stage.
+__device__ __forceinline__ void ring_barrier() { pin(); __builtin_amdgcn_s_barrier(); pin(); }
 
 template <int I> using IC = std::integral_constant<int, I>;
 
@@ -109,10 +106,13 @@ template <int N, class F> __device__ __forceinline__ void static_for(F &&f) { st
 // share a CU.
 // BT = true: the filter operand is read transposed, straight from w[K][Co] (1x1 filters): its LDS tile is
 // [reduction row][BN output columns] and its MFMA fragments come from ds_read_b64_tr_b16.
-template <int BM, int BN, int BKT, int NS, int WR, int WC, bool BT>
+// TI = true: channel-block-major reduction order (needs Ci % BKT == 0); a compile-time choice so that the
+// stage body is one basic block and the pinned interleave of address work and MFMAs survives.
+template <int BM, int BN, int BKT, int NS, int WR, int WC, bool BT, bool TI>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT * 2 <= 80 * 1024) ? 2 : 1) void igemm_kernel(
     const IgemmParams p)
 {
+    static_assert(!(BT && TI), "the in-place filter variant has one tap");
     constexpr int NW = WR * WC, NT = 64 * NW;
     constexpr int WM = BM / WR, WN = BN / WC;     // wave tile
     constexpr int MI = WM / 32, NI = WN / 32;     // 32x32 MFMA blocks per wave
@@ -147,11 +147,11 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     __shared__ __attribute__((aligned(1024))) bf16_t sb3[NS > 3 ? SZB : 8];
     // per tap: .x = byte offset of the tap relative to tap 0, .y = (dh, dv) packed as two int16
     __shared__ int2 tap_tab[MAX_TAPS + 1];
-    auto stage_a = [&](auto s) -> bf16_t * {
+    auto stage_a = [&](auto s) __attribute__((always_inline)) -> bf16_t * {
         constexpr int S = decltype(s)::value;
         if constexpr (S == 0) return sa0; else if constexpr (S == 1) return sa1; else if constexpr (S == 2) return sa2; else return sa3;
     };
-    auto stage_b = [&](auto s) -> bf16_t * {
+    auto stage_b = [&](auto s) __attribute__((always_inline)) -> bf16_t * {
         constexpr int S = decltype(s)::value;
         if constexpr (S == 0) return sb0; else if constexpr (S == 1) return sb1; else if constexpr (S == 2) return sb2; else return sb3;
     };
@@ -202,8 +202,8 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     const int ld_sub = lane / CH;
     const int ld_chunk = (lane % CH) ^ (((RPL / RB) * wave + ld_sub / RB) % CH);
 
-    const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_wm = __builtin_amdgcn_make_buffer_rsrc((void *)p.wm, 0, (int)p.wm_bytes, 0x00020000);
+    const buf_rsrc_t rs_in = make_buf_rsrc(p.in, p.in_bytes);
+    const buf_rsrc_t rs_wm = make_buf_rsrc(p.wm, p.wm_bytes);
 
     int a_off[A_LD];     // byte offset of (n, base_h, base_w, 0) in `in` (may be negative)
     int a_hw[A_LD];      // base_h (low 16 bits) and base_w (high 16), signed; invalid row: h = -16384
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     const int kd0 = k_lo * BKT + ld_chunk * 8;     // this lane's reduction position in the first stage (tap-major order)
     int kd2 = kd0 * 2;                             // byte offset within a filter row
     int ci2 = (kd0 % p.Ci) * 2, tap = kd0 / p.Ci;
-    if (p.tap_inner) {                             // stage s = (channel block s / T, tap s % T)
+    if constexpr (TI) {                            // stage s = (channel block s / T, tap s % T)
         tap = k_lo % T;
         ci2 = (k_lo / T) * (BKT * 2) + ld_chunk * 16;
     }
@@ -253,15 +253,16 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
 
     unsigned va[A_LD], vb[B_LD];   // byte offsets of the next stage's loads
 
-    // address generation for the next stage, split in A_LD + 2 small tasks so that it can be spread
-    // between MFMAs
-    int2 tap_e;
-    auto addr_task = [&](auto t) {
+    // address generation for the next stage, split in A_LD + 1 small tasks so that it can be spread
+    // between MFMAs.  tap_e is the tap-table entry of the stage the addresses are for; the last task
+    // advances the reduction position and fetches the entry of the stage after, a whole stage before
+    // the first task that reads it.
+    int2 tap_e = make_int2(0, 0);
+    auto fetch_tap = [&]() __attribute__((always_inline)) { tap_e = tap_tab[tap < T ? tap : T]; };
+    auto addr_task = [&](auto t) __attribute__((always_inline)) {
         constexpr int Tk = decltype(t)::value;
-        if constexpr (Tk == 0) {
-            tap_e = tap_tab[tap < T ? tap : T];
-        } else if constexpr (Tk <= A_LD) {
-            constexpr int i = Tk - 1;
+        if constexpr (Tk < A_LD) {
+            constexpr int i = Tk;
             const s16x2 hw = __builtin_bit_cast(s16x2, a_hw[i]) + __builtin_bit_cast(s16x2, tap_e.y);
             const s16x2 d = __builtin_bit_cast(s16x2, lim_hw) - hw;
             const int bad = (__builtin_bit_cast(int, hw) | __builtin_bit_cast(int, d)) & (int)0x80008000;
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
                 const int carry = ci2 >= Ci2 ? 1 : 0;
                 ci2 -= carry ? Ci2 : 0;
                 tap += kq + carry;
-            } else if (p.tap_inner) {
+            } else if constexpr (TI) {
                 // Order (channel block, tap): the pixels a workgroup reads for one channel block serve all
                 // its taps back to back, so they are still in the XCD's L2 when the next tap asks for them.
                 const bool k_ok = tap < T;
@@ -300,13 +301,14 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
                 ci2 -= carry ? Ci2 : 0;
                 tap += kq + carry;
             }
+            fetch_tap();
         }
     };
-    constexpr int N_ADDR = A_LD + 2;
-    auto load_task = [&](auto t, bf16_t *dst_a, bf16_t *dst_b) {
+    constexpr int N_ADDR = A_LD + 1;
+    auto load_task = [&](auto t, bf16_t *dst_a, bf16_t *dst_b) __attribute__((always_inline)) {
         constexpr int Tk = decltype(t)::value;
-        if constexpr (Tk < A_LD) load16_to_lds(rs_in, va[Tk], dst_a + (wave + NW * Tk) * RPL * BKT);
-        else load16_to_lds(rs_wm, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * (BT ? RPLB * BN : RPL * BKT));
+        if constexpr (Tk < A_LD) lds_dma16(rs_in, va[Tk], dst_a + (wave + NW * Tk) * RPL * BKT);
+        else lds_dma16(rs_wm, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * (BT ? RPLB * BN : RPL * BKT));
     };
 
     f32x16 acc[MI][NI];
@@ -329,7 +331,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         const int g = lane >> 4, j16 = lane & 15;
         const int tr_row = (g >> 1) * 8 + (j16 >> 2);
         const int tr_ch = (g & 1) * 16 + (j16 & 3) * 4;
-        auto tr_off = [&](int ch_base, int row) {
+        auto tr_off = [&](int ch_base, int row) __attribute__((always_inline)) {
             const int ch = ch_base + tr_ch;
             return row * BN + (((ch >> 3) ^ bt_row_swz<RCB>(row)) << 3) + (ch & 7);
         };
@@ -337,7 +339,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         for (int j = 0; j < NI; ++j) { bt_lo[j] = tr_off(wave_n + j * 32, tr_row); bt_hi[j] = tr_off(wave_n + j * 32, tr_row + 4); }
     }
     struct Frags { bf16x8 a[MI], b[NI]; };
-    auto read_task = [&](auto t, Frags &f, const bf16_t *src_a, const bf16_t *src_b, int ks) {
+    auto read_task = [&](auto t, Frags &f, const bf16_t *src_a, const bf16_t *src_b, int ks) __attribute__((always_inline)) {
         constexpr int Tk = decltype(t)::value;
         const int pos = ((ks * 2 + frag_kg) ^ frag_swz) << 3;
         if constexpr (Tk < MI) f.a[Tk] = *reinterpret_cast<const bf16x8 *>(src_a + a_lane + Tk * 32 * BKT + pos);
@@ -354,13 +356,13 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     // the matrix pipe executes one MFMA while the wave issues the side work behind it)
     // The first NFRONT tasks (operand fetches, which the next k-step waits for) go behind the first half
     // of the MFMAs, the rest behind the second half.
-    auto mfma_with = [&](const Frags &f, auto nfront, auto ntask, auto &&task) {
+    auto mfma_with = [&](const Frags &f, auto nfront, auto ntask, auto &&task) __attribute__((always_inline)) {
         constexpr int NFRONT = decltype(nfront)::value, NTASK = decltype(ntask)::value;
         constexpr int H1 = NMF > 1 ? NMF / 2 : 1, H2 = NMF - H1 > 0 ? NMF - H1 : 1;
-        static_for<NMF>([&](auto s) {
+        static_for<NMF>([&](auto s) __attribute__((always_inline)) {
             constexpr int S = decltype(s)::value;
             acc[S / NI][S % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[S / NI], f.b[S % NI], acc[S / NI][S % NI], 0, 0, 0);
-            static_for<NTASK>([&](auto t) {
+            static_for<NTASK>([&](auto t) __attribute__((always_inline)) {
                 constexpr int Tk = decltype(t)::value;
                 constexpr int slot = Tk < NFRONT ? Tk * H1 / NFRONT
                                                  : (NMF > 1 ? H1 + (Tk - NFRONT) * H2 / (NTASK - NFRONT > 0 ? NTASK - NFRONT : 1) : 0);
@@ -379,25 +381,26 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     // first operand fetch of stage kt+1 - the matrix pipe has work across the barrier.
     Frags f0, f1;
     __syncthreads();   // tap table visible
-    static_for<NS>([&](auto s) {
-        static_for<N_ADDR>([&](auto t) { addr_task(t); });
-        static_for<L>([&](auto t) { load_task(t, stage_a(s), stage_b(s)); });
+    fetch_tap();
+    static_for<NS>([&](auto s) __attribute__((always_inline)) {
+        static_for<N_ADDR>([&](auto t) __attribute__((always_inline)) { addr_task(t); });
+        static_for<L>([&](auto t) __attribute__((always_inline)) { load_task(t, stage_a(s), stage_b(s)); });
     });
     wait_vmcnt<L * (NS - 1)>();
-    __syncthreads();
-    static_for<N_READ>([&](auto t) { read_task(t, f0, sa0, sb0, 0); });
+    ring_barrier();
+    static_for<N_READ>([&](auto t) __attribute__((always_inline)) { read_task(t, f0, sa0, sb0, 0); });
 
-    auto run_stage = [&](auto s) {
+    auto run_stage = [&](auto s) __attribute__((always_inline)) {
         constexpr int S = decltype(s)::value;
         constexpr int S1 = (S + 1) % NS;
         bf16_t *ca = stage_a(s), *cb = stage_b(s);
-        static_for<KS - 1>([&](auto k) {
+        static_for<KS - 1>([&](auto k) __attribute__((always_inline)) {
             constexpr int ks = decltype(k)::value;
             Frags &cur = (ks & 1) ? f1 : f0;
             Frags &nxt = (ks & 1) ? f0 : f1;
             // this k-step's share of the address tasks, spread evenly over k-steps 0..KS-2
             constexpr int a0 = ks * N_ADDR / (KS - 1), a1 = (ks + 1) * N_ADDR / (KS - 1);
-            mfma_with(cur, IC<N_READ>{}, IC<N_READ + (a1 - a0)>{}, [&](auto t) {
+            mfma_with(cur, IC<N_READ>{}, IC<N_READ + (a1 - a0)>{}, [&](auto t) __attribute__((always_inline)) {
                 constexpr int Tk = decltype(t)::value;
                 if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<a0 + Tk - N_READ>{});
             });
@@ -405,25 +408,28 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         // the last k-step's operands are in f1; all reads of this slot must have returned before it is refilled
         wait_lgkmcnt0();
         wait_vmcnt<L * (NS - 2)>();
-        __syncthreads();
-        mfma_with(f1, IC<N_READ>{}, IC<N_READ + L>{}, [&](auto t) {
+        ring_barrier();
+        mfma_with(f1, IC<N_READ>{}, IC<N_READ + L>{}, [&](auto t) __attribute__((always_inline)) {
             constexpr int Tk = decltype(t)::value;
             if constexpr (Tk < N_READ) read_task(t, f0, stage_a(IC<S1>{}), stage_b(IC<S1>{}), 0);
             else load_task(IC<Tk - N_READ>{}, ca, cb);
         });
     };
 
-    for (int kt = 0; kt < k_cnt; kt += NS) {
-        run_stage(IC<0>{});
-        if (kt + 1 < k_cnt) run_stage(IC<1>{});
-        if constexpr (NS > 2) if (kt + 2 < k_cnt) run_stage(IC<2>{});
-        if constexpr (NS > 3) if (kt + 3 < k_cnt) run_stage(IC<3>{});
-    }
+    // Whole turns of the ring in a loop whose body is one basic block (the compiler's own wait insertion for
+    // LDS reads against in-flight global->LDS loads merges states at every control-flow join; a join inside
+    // the loop makes it wait for all loads at the loop head), then the remaining stages.
+    int kt = 0;
+    for (; kt + NS <= k_cnt; kt += NS) static_for<NS>([&](auto s) __attribute__((always_inline)) { run_stage(s); });
+    const int rem = k_cnt - kt;
+    if (rem >= 1) run_stage(IC<0>{});
+    if constexpr (NS > 2) if (rem >= 2) run_stage(IC<1>{});
+    if constexpr (NS > 3) if (rem >= 3) run_stage(IC<2>{});
     wait_vmcnt<0>();   // drain the zero-fill loads of the stages past the end before the tile's LDS is abandoned
 
     // ---- epilogue: fp32 -> bf16 (RNE), to the output pixels ------------------------------------
     // accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
-    auto out_pixel = [&](int m) -> long long {
+    auto out_pixel = [&](int m) __attribute__((always_inline)) -> long long {
         if (p.linear_out) return m;
         const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
         const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
@@ -453,7 +459,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         const int co = n0 + wave_n + j * 32 + frag_row;
         bias_j[j] = (p.bias != nullptr && co < p.Co) ? p.bias[co] : 0.f;
     }
-    auto finish = [&](float v, int j) -> bf16_t {
+    auto finish = [&](float v, int j) __attribute__((always_inline)) -> bf16_t {
         v += bias_j[j];
         if (p.relu) v = fmaxf(v, 0.f);
         return f32_to_bf16(v);
@@ -525,6 +531,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
 template <int BM, int BN, int BKT, int NS, int WR, int WC, bool BT = false>
 int launch(IgemmParams p, hipStream_t st)
 {
+    static const bool tap_outer_forced = getenv("MXC_TAP_OUTER") != nullptr;   // tuning sweeps only; read once
     const long long M = (long long)p.N * p.Mh * p.Mw;
     const long long mt = (M + BM - 1) / BM;
     p.n_tiles = (p.Co + BN - 1) / BN;
@@ -534,7 +541,7 @@ int launch(IgemmParams p, hipStream_t st)
     p.in_bytes = (unsigned)((long long)p.N * p.Hi * p.Wi * p.pix * 2);
     p.wm_bytes = BT ? p.bt_w_bytes : (unsigned)((long long)p.Co * p.TR * p.TS * p.Ci * 2);
     // MXC_TAP_OUTER=1 (tuning only) keeps the filter's own order, all channels of a tap before the next tap
-    p.tap_inner = (p.Ci % BKT == 0 && p.TR * p.TS > 1 && !getenv("MXC_TAP_OUTER")) ? 1 : 0;
+    p.tap_inner = (!BT && p.Ci % BKT == 0 && p.TR * p.TS > 1 && !tap_outer_forced) ? 1 : 0;
     p.linear_out = (p.out_mul_h == 1 && p.out_mul_w == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
     if (p.splits > 1) {
         // even stage ranges; the last split may be shorter, none is empty
@@ -546,7 +553,13 @@ int launch(IgemmParams p, hipStream_t st)
     const long long total = (long long)p.m_tiles * p.n_tiles * (p.splits > 1 ? p.splits : 1);
     if (total > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
     const int grid = (int)((total + 7) / 8) * 8;
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, BKT, NS, WR, WC, BT>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
+    if constexpr (!BT) {
+        if (p.tap_inner) {
+            hipLaunchKernelGGL((igemm_kernel<BM, BN, BKT, NS, WR, WC, false, true>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
+            return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+        }
+    }
+    hipLaunchKernelGGL((igemm_kernel<BM, BN, BKT, NS, WR, WC, BT, false>), dim3((unsigned)grid), dim3(64 * WR * WC), 0, st, p);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
 
@@ -564,6 +577,8 @@ const TileChoice kTiles[] = {
     {128, 32, 64, 4, 0.33f, "igemm_128x32_k64s2_w4"},
     {256, 32, 64, 2, 0.33f, "igemm_256x32_k64s2_w4"},
     {256, 192, 64, 1, 1.05f, "igemm_256x192_k64s2_w8"},
+    {256, 256, 32, 1, 0.01f, "igemm_256x256_k32s4_w8"},
+    {128, 128, 32, 2, 0.01f, "igemm_128x128_k32s4_w4"},
 };
 constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -589,7 +604,9 @@ int launch_choice(int idx, const IgemmParams &p, hipStream_t st, bool bt = false
     case 5: return launch<256, 64, 32, 3, 4, 1>(p, st);
     case 6: return launch<128, 32, 64, 2, 4, 1>(p, st);
     case 7: return launch<256, 32, 64, 2, 4, 1>(p, st);
-    default: return launch<256, 192, 64, 2, 4, 2>(p, st);
+    case 8: return launch<256, 192, 64, 2, 4, 2>(p, st);
+    case 9: return launch<256, 256, 32, 4, 2, 4>(p, st);
+    default: return launch<128, 128, 32, 4, 2, 2>(p, st);
     }
 }
 

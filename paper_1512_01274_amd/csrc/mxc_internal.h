@@ -49,6 +49,39 @@ __device__ __forceinline__ uint32_t mask_bf16x2(uint32_t v, uint32_t m)
 __device__ __forceinline__ bool mask_keeps(const float *m) { return *m > 0.f; }
 __device__ __forceinline__ bool mask_keeps(const bf16_t *m) { return (int16_t)*m > 0; }
 
+// ---- asynchronous global -> LDS transfers (the MFMA kernels' operand path) ---------------------------
+// A wave-wide 16-byte-per-lane buffer load whose data goes straight to LDS: lane l's 16 bytes land at
+// lds_base + 16*l, where lds_base is wave-uniform.  Lanes whose byte offset lies outside the buffer deposit
+// zeros (how padding, ragged edges and reduction tails are filled).
+//
+// Written as inline assembly on purpose.  Issued through the compiler's builtin, the transfer is known to the
+// compiler as a write to LDS, and it then guards LDS reads that it cannot prove disjoint (every read made
+// with a transposing-read builtin, every read after a control-flow join, everything once more than eight LDS
+// objects are in play) with a wait for ALL outstanding transfers, which empties a ring of stages at every
+// stage.  This way the compiler sees no LDS write at all; the kernels order the transfers against their LDS
+// reads themselves (s_waitcnt vmcnt(N) + barrier before a stage is read).  M0 holds the LDS base for the
+// instruction; nothing else in these kernels uses M0.
+typedef int buf_rsrc_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ buf_rsrc_t make_buf_rsrc(const void *base, unsigned bytes)
+{
+    const uint64_t a = (uint64_t)base;
+    buf_rsrc_t r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    r.y = __builtin_amdgcn_readfirstlane((int)((uint32_t)(a >> 32) & 0xFFFFu));   // stride 0: raw buffer
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);                              // out-of-range above this
+    r.w = 0x00020000;
+    return r;
+}
+__device__ __forceinline__ void lds_dma16(buf_rsrc_t rsrc, unsigned byte_off, const void *lds_base_uniform)
+{
+    typedef __attribute__((address_space(3))) const void *lds_cvptr;
+    const unsigned lds_addr = (unsigned)(uintptr_t)(lds_cvptr)lds_base_uniform;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(byte_off), "s"(rsrc)
+                 : "memory");
+}
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline size_t elem_size(int dtype) { return dtype == MXC_BF16 ? 2 : 4; }
 

@@ -49,13 +49,12 @@ struct WgradParams {
     unsigned x_bytes, dy_bytes;
 };
 
-__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off, bf16_t *lds_base_uniform)
-{
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_vptr)lds_base_uniform, 16, byte_off, 0, 0, 0);
-}
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void pin() { __builtin_amdgcn_sched_barrier(0); }
+// Workgroup barrier of the ring: the bare instruction, with the counters it needs waited for by hand just before
+// it (a __syncthreads() would add fences the ring does not need).
+__device__ __forceinline__ void ring_barrier() { pin(); __builtin_amdgcn_s_barrier(); pin(); }
 
 template <int I> using IC = std::integral_constant<int, I>;
 template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) { (f(IC<I>{}), ...); }
@@ -72,7 +71,8 @@ template <int RC> __device__ __forceinline__ int row_swz(int row)
 
 // BMT k-channels x BNT filter columns per tile, BP pixels per stage, NS stages, WR x WC waves.
 template <int BMT, int BNT, int BP, int NS, int WR, int WC>
-__global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p)
+__global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * BP * (BMT + BNT) * 2 <= 80 * 1024) ? 2 : 1) void wgrad_kernel(
+    const WgradParams p)
 {
     constexpr int NW = WR * WC;
     constexpr int WM = BMT / WR, WN = BNT / WC;
@@ -95,11 +95,11 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
     __shared__ __attribute__((aligned(1024))) bf16_t sb1[SZB];
     __shared__ __attribute__((aligned(1024))) bf16_t sb2[NS > 2 ? SZB : 8];
     __shared__ __attribute__((aligned(1024))) bf16_t sb3[NS > 3 ? SZB : 8];
-    auto stage_a = [&](auto s) -> bf16_t * {
+    auto stage_a = [&](auto s) __attribute__((always_inline)) -> bf16_t * {
         constexpr int S = decltype(s)::value;
         if constexpr (S == 0) return sa0; else if constexpr (S == 1) return sa1; else if constexpr (S == 2) return sa2; else return sa3;
     };
-    auto stage_b = [&](auto s) -> bf16_t * {
+    auto stage_b = [&](auto s) __attribute__((always_inline)) -> bf16_t * {
         constexpr int S = decltype(s)::value;
         if constexpr (S == 0) return sb0; else if constexpr (S == 1) return sb1; else if constexpr (S == 2) return sb2; else return sb3;
     };
@@ -121,8 +121,8 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
     const int m_end = min(m_begin + p.span, p.M);
     const int KT = m_end > m_begin ? (m_end - m_begin + BP - 1) / BP : 0;
 
-    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (int)p.dy_bytes, 0x00020000);
+    const buf_rsrc_t rs_x = make_buf_rsrc(p.x, p.x_bytes);
+    const buf_rsrc_t rs_dy = make_buf_rsrc(p.dy, p.dy_bytes);
 
     // ---- A side (dy): lane -> pixel row RPLA*i + lane/RCA of the stage, k-channel chunk fixed -------
     const int la_sub = lane / RCA;
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
 
     unsigned va[A_LD], vb[B_LD];
     // address tasks: 0..A_LD-1 = dy rows, A_LD..A_LD+B_LD-1 = x rows (each also advances its row by one stage)
-    auto addr_task = [&](auto t) {
+    auto addr_task = [&](auto t) __attribute__((always_inline)) {
         constexpr int Tk = decltype(t)::value;
         if constexpr (Tk < A_LD) {
             va[Tk] = a_m[Tk] < m_end ? (unsigned)a_m[Tk] * (unsigned)(p.K * 2) + a_col : OOB;
@@ -181,10 +181,10 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
             b_q[i] = q; b_p[i] = pr; b_n[i] += p.dn + cp;
         }
     };
-    auto load_task = [&](auto t, bf16_t *dst_a, bf16_t *dst_b) {
+    auto load_task = [&](auto t, bf16_t *dst_a, bf16_t *dst_b) __attribute__((always_inline)) {
         constexpr int Tk = decltype(t)::value;
-        if constexpr (Tk < A_LD) load16_to_lds(rs_dy, va[Tk], dst_a + (wave + NW * Tk) * RPLA * BMT);
-        else load16_to_lds(rs_x, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * RPLB * BNT);
+        if constexpr (Tk < A_LD) lds_dma16(rs_dy, va[Tk], dst_a + (wave + NW * Tk) * RPLA * BMT);
+        else lds_dma16(rs_x, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * RPLB * BNT);
     };
 
     f32x16 acc[MI][NI];
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
     const int tr_row = (g >> 1) * 8 + (j16 >> 2);        // pixel row within a 16-pixel k-step (second read: +4)
     const int tr_ch = (g & 1) * 16 + (j16 & 3) * 4;      // channel within a 32-channel block
     // element offsets of the two reads within a 16-pixel k-step, per operand, for channel block 0
-    auto tr_off = [&](auto rc, int ch_base, int row) {
+    auto tr_off = [&](auto rc, int ch_base, int row) __attribute__((always_inline)) {
         constexpr int RC = decltype(rc)::value;
         const int ch = ch_base + tr_ch;
         return row * (RC * 8) + ((((ch >> 3) ^ row_swz<RC>(row))) << 3) + (ch & 7);
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
 
     struct Frags { bf16x8 a[MI], b[NI]; };
     // the swizzle depends on row % 4 only and a k-step advances the row by 16: offsets just shift
-    auto read_task = [&](auto t, Frags &f, const bf16_t *src_a, const bf16_t *src_b, int ks) {
+    auto read_task = [&](auto t, Frags &f, const bf16_t *src_a, const bf16_t *src_b, int ks) __attribute__((always_inline)) {
         constexpr int Tk = decltype(t)::value;
         if constexpr (Tk < MI) {
             const bf16_t *q = src_a + ks * 16 * BMT;
@@ -229,12 +229,12 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
     };
     constexpr int N_READ = MI + NI;
 
-    auto mfma_with = [&](const Frags &f, auto ntask, auto &&task) {
+    auto mfma_with = [&](const Frags &f, auto ntask, auto &&task) __attribute__((always_inline)) {
         constexpr int NTASK = decltype(ntask)::value;
-        static_for<NMF>([&](auto s) {
+        static_for<NMF>([&](auto s) __attribute__((always_inline)) {
             constexpr int S = decltype(s)::value;
             acc[S / NI][S % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[S / NI], f.b[S % NI], acc[S / NI][S % NI], 0, 0, 0);
-            static_for<NTASK>([&](auto t) {
+            static_for<NTASK>([&](auto t) __attribute__((always_inline)) {
                 constexpr int Tk = decltype(t)::value;
                 if constexpr (Tk * NMF / NTASK == S) task(t);
             });
@@ -244,44 +244,45 @@ __global__ __launch_bounds__(64 * WR * WC) void wgrad_kernel(const WgradParams p
 
     // ---- pipeline (same shape as the forward kernel's) --------------------------------------------
     Frags f0, f1;
-    static_for<NS>([&](auto s) {
-        static_for<L>([&](auto t) { addr_task(t); });
-        static_for<L>([&](auto t) { load_task(t, stage_a(s), stage_b(s)); });
+    static_for<NS>([&](auto s) __attribute__((always_inline)) {
+        static_for<L>([&](auto t) __attribute__((always_inline)) { addr_task(t); });
+        static_for<L>([&](auto t) __attribute__((always_inline)) { load_task(t, stage_a(s), stage_b(s)); });
     });
     wait_vmcnt<L * (NS - 1)>();
-    __syncthreads();
-    static_for<N_READ>([&](auto t) { read_task(t, f0, sa0, sb0, 0); });
+    ring_barrier();
+    static_for<N_READ>([&](auto t) __attribute__((always_inline)) { read_task(t, f0, sa0, sb0, 0); });
 
-    auto run_stage = [&](auto s) {
+    auto run_stage = [&](auto s) __attribute__((always_inline)) {
         constexpr int S = decltype(s)::value;
         constexpr int S1 = (S + 1) % NS;
         bf16_t *ca = stage_a(s), *cb = stage_b(s);
-        static_for<KS - 1>([&](auto k) {
+        static_for<KS - 1>([&](auto k) __attribute__((always_inline)) {
             constexpr int ks = decltype(k)::value;
             Frags &cur = (ks & 1) ? f1 : f0;
             Frags &nxt = (ks & 1) ? f0 : f1;
             // this k-step's share of the address tasks, spread evenly over k-steps 0..KS-2
             constexpr int a0 = ks * L / (KS - 1), a1 = (ks + 1) * L / (KS - 1);
-            mfma_with(cur, IC<N_READ + (a1 - a0)>{}, [&](auto t) {
+            mfma_with(cur, IC<N_READ + (a1 - a0)>{}, [&](auto t) __attribute__((always_inline)) {
                 constexpr int Tk = decltype(t)::value;
                 if constexpr (Tk < N_READ) read_task(t, nxt, ca, cb, ks + 1); else addr_task(IC<a0 + Tk - N_READ>{});
             });
         });
         wait_lgkmcnt0();
         wait_vmcnt<L * (NS - 2)>();
-        __syncthreads();
-        mfma_with(f1, IC<L + N_READ>{}, [&](auto t) {
+        ring_barrier();
+        mfma_with(f1, IC<L + N_READ>{}, [&](auto t) __attribute__((always_inline)) {
             constexpr int Tk = decltype(t)::value;
             if constexpr (Tk < L) load_task(t, ca, cb);
             else read_task(IC<Tk - L>{}, f0, stage_a(IC<S1>{}), stage_b(IC<S1>{}), 0);
         });
     };
-    for (int kt = 0; kt < KT; kt += NS) {
-        run_stage(IC<0>{});
-        if (kt + 1 < KT) run_stage(IC<1>{});
-        if constexpr (NS > 2) if (kt + 2 < KT) run_stage(IC<2>{});
-        if constexpr (NS > 3) if (kt + 3 < KT) run_stage(IC<3>{});
-    }
+    // whole turns of the ring in a loop whose body is one basic block, then the remaining stages
+    int kt = 0;
+    for (; kt + NS <= KT; kt += NS) static_for<NS>([&](auto s) __attribute__((always_inline)) { run_stage(s); });
+    const int rem = KT - kt;
+    if (rem >= 1) run_stage(IC<0>{});
+    if constexpr (NS > 2) if (rem >= 2) run_stage(IC<1>{});
+    if constexpr (NS > 3) if (rem >= 3) run_stage(IC<2>{});
     wait_vmcnt<0>();
 
     // ---- fp32 partial tile -> workspace ------------------------------------------------------
@@ -397,6 +398,8 @@ const WgradTile kTiles[] = {
     {64, 64, 64, 4, 0.12f, "wgrad_64x64_p64s2_w4"},
     {64, 128, 64, 2, 0.22f, "wgrad_64x128_p64s2_w4"},
     {128, 64, 64, 2, 0.22f, "wgrad_128x64_p64s2_w4"},
+    {256, 256, 64, 1, 0.01f, "wgrad_256x256_p64s2_w8"},
+    {128, 128, 32, 2, 0.01f, "wgrad_128x128_p32s4_w4"},
 };
 constexpr int N_TILES = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -420,7 +423,9 @@ int launch_choice(int idx, const WgradParams &p, int tiles, hipStream_t st)
     case 3: return launch<128, 256, 32, 4, 2, 4>(p, tiles, st);
     case 4: return launch<64, 64, 64, 2, 2, 2>(p, tiles, st);
     case 5: return launch<64, 128, 64, 2, 2, 2>(p, tiles, st);
-    default: return launch<128, 64, 64, 2, 2, 2>(p, tiles, st);
+    case 6: return launch<128, 64, 64, 2, 2, 2>(p, tiles, st);
+    case 7: return launch<256, 256, 64, 2, 2, 4>(p, tiles, st);
+    default: return launch<128, 128, 32, 4, 2, 2>(p, tiles, st);
     }
 }
 
@@ -430,14 +435,32 @@ struct Plan { int tile, k_tiles, n_tiles, splits, span; };
 // slots (256 CUs x slots per CU) x stages each split walks x time per stage, plus the traffic of
 // writing and re-reading one fp32 partial tensor per split.  MXC_FORCE_WGRAD=<name> (tuning sweeps
 // only) fixes the tile.
+Plan search_plan(const WgradGeom &g, int forced);
+
+// The search below costs tens of microseconds; a call needs its answer up to three times (size query, workspace
+// carve-out, launch) and a training loop asks for the same few geometries over and over: keep the answers of
+// the calling thread (no locks; 32 entries, overwritten in turn).
 Plan make_plan(const WgradGeom &g)
 {
-    const int RSC = g.TR * g.TS * g.run;
-    const long long M = (long long)g.N * g.P * g.Q;
     int forced = -1;
     if (const char *f = getenv("MXC_FORCE_WGRAD"))
         for (int i = 0; i < N_TILES; ++i)
             if (!strcmp(f, kTiles[i].name)) forced = i;
+    struct Entry { WgradGeom g; int forced; Plan plan; bool used; };
+    static thread_local Entry cache[32] = {};
+    static thread_local int next = 0;
+    for (const Entry &e : cache)
+        if (e.used && e.forced == forced && !memcmp(&e.g, &g, sizeof(WgradGeom))) return e.plan;
+    Entry &slot = cache[next];
+    next = (next + 1) % 32;
+    slot.g = g; slot.forced = forced; slot.plan = search_plan(g, forced); slot.used = true;
+    return slot.plan;
+}
+
+Plan search_plan(const WgradGeom &g, int forced)
+{
+    const int RSC = g.TR * g.TS * g.run;
+    const long long M = (long long)g.N * g.P * g.Q;
     Plan best_pl{};
     double best = 1e300;
     for (int t = 0; t < N_TILES; ++t) {
