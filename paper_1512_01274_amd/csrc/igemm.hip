@@ -56,6 +56,8 @@ struct IgemmParams {
     int Ho, Wo, out_mul_h, out_mul_w, out_off_h, out_off_w;  // output coordinate: a*out_mul + out_off
     int linear_out;      // output pixel index == m (forward, and stride-1 backward-data)
     int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
+    int m_begin, m_end;  // GEMM rows [m_begin, m_end) belong to this launch (a problem may be cut in two launches of
+                         // different tile shapes: see Plan); tile 0 starts at m_begin
     int m_tiles, n_tiles;
     unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
     // BT kernels (1x1 stride-1 backward-data straight from the filter, no transposed copy): wm = w[K][Co];
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (unit >= units) return;
     const int logical = unit % total, split_z = unit / total;
-    const int m0 = (logical / p.n_tiles) * BM, n0 = (logical % p.n_tiles) * BN;
+    const int m0 = p.m_begin + (logical / p.n_tiles) * BM, n0 = (logical % p.n_tiles) * BN;
 
     const int T = p.TR * p.TS;
     const int Kd = T * p.Ci;
@@ -210,7 +212,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
         const int m = m0 + RPL * (wave + NW * i) + ld_sub;
-        if (m < p.M) {
+        if (m < p.m_end) {
             const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
             const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
             const int h = (int)a * p.in_mul_h + p.in_off_h, w = (int)b * p.in_mul_w + p.in_off_w;
@@ -443,7 +445,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
-                if (m >= p.M) continue;
+                if (m >= p.m_end) continue;
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
                     const int co = n0 + wave_n + j * 32 + frag_row;
@@ -494,7 +496,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
                 const int r = idx / CPR, c = idx % CPR;
                 const int m = m0 + wave_m + i * 32 + r, co = n0 + wave_n + c * 8;
                 uint4 v = *reinterpret_cast<const uint4 *>(stg + r * WN + c * 8);
-                if (m < p.M && co < p.Co) {
+                if (m < p.m_end && co < p.Co) {
                     const long long off = out_pixel(m) * p.Co + co;
                     if (p.mask != nullptr) {
                         const uint4 mk = *reinterpret_cast<const uint4 *>(p.mask + off);
@@ -513,7 +515,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
-                if (m >= p.M) continue;
+                if (m >= p.m_end) continue;
                 const long long orow = out_pixel(m) * p.Co;
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
@@ -528,15 +530,20 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     }
 }
 
+// Launches the tile shape on GEMM rows [m_begin, m_end) of the problem (m_end < 0: to the last row).
 template <int BM, int BN, int BKT, int NS, int WR, int WC, bool BT = false>
-int launch(IgemmParams p, hipStream_t st)
+int launch(IgemmParams p, hipStream_t st, long long m_begin = 0, long long m_end = -1)
 {
     static const bool tap_outer_forced = getenv("MXC_TAP_OUTER") != nullptr;   // tuning sweeps only; read once
     const long long M = (long long)p.N * p.Mh * p.Mw;
-    const long long mt = (M + BM - 1) / BM;
+    if (m_end < 0 || m_end > M) m_end = M;
+    if (m_begin >= m_end) return MXC_OK;
+    const long long mt = (m_end - m_begin + BM - 1) / BM;
     p.n_tiles = (p.Co + BN - 1) / BN;
     if (mt * p.n_tiles > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
     p.M = (int)M;
+    p.m_begin = (int)m_begin;
+    p.m_end = (int)m_end;
     p.m_tiles = (int)mt;
     p.in_bytes = (unsigned)((long long)p.N * p.Hi * p.Wi * p.pix * 2);
     p.wm_bytes = BT ? p.bt_w_bytes : (unsigned)((long long)p.Co * p.TR * p.TS * p.Ci * 2);
@@ -548,7 +555,7 @@ int launch(IgemmParams p, hipStream_t st)
         const int KT = (p.TR * p.TS * p.Ci + BKT - 1) / BKT;
         p.split_stages = (KT + p.splits - 1) / p.splits;
         p.splits = (KT + p.split_stages - 1) / p.split_stages;
-        if (!p.linear_out || !p.partial) return MXC_ERR_UNSUPPORTED;
+        if (!p.linear_out || !p.partial || m_begin != 0 || m_end != M) return MXC_ERR_UNSUPPORTED;
     }
     const long long total = (long long)p.m_tiles * p.n_tiles * (p.splits > 1 ? p.splits : 1);
     if (total > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
@@ -570,74 +577,146 @@ struct TileChoice { int bm, bn, bk, slots; float util; const char *name; };   //
 const TileChoice kTiles[] = {
     {128, 128, 64, 2, 0.91f, "igemm_128x128_k64s2_w4"},
     {256, 256, 64, 1, 1.15f, "igemm_256x256_k64s2_w8"},
-    {256, 128, 64, 1, 0.86f, "igemm_256x128_k64s3_w8"},
-    {128, 256, 64, 1, 0.82f, "igemm_128x256_k64s3_w8"},
+    {256, 128, 64, 1, 0.95f, "igemm_256x128_k64s3_w8"},
+    {128, 256, 64, 1, 0.97f, "igemm_128x256_k64s3_w8"},
     {128, 64, 64, 3, 0.65f, "igemm_128x64_k64s2_w4"},
     {256, 64, 32, 2, 0.60f, "igemm_256x64_k32s3_w4"},
     {128, 32, 64, 4, 0.33f, "igemm_128x32_k64s2_w4"},
     {256, 32, 64, 2, 0.33f, "igemm_256x32_k64s2_w4"},
     {256, 192, 64, 1, 1.05f, "igemm_256x192_k64s2_w8"},
-    {256, 256, 32, 1, 0.01f, "igemm_256x256_k32s4_w8"},
-    {128, 128, 32, 2, 0.01f, "igemm_128x128_k32s4_w4"},
+    {192, 256, 64, 1, 1.05f, "igemm_192x256_k64s2_w8"},
+    {64, 256, 64, 1, 0.55f, "igemm_64x256_k64s3_w8"},
+    {64, 128, 64, 2, 0.45f, "igemm_64x128_k64s3_w4"},
 };
 constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
 
 // the tiles that also exist reading a 1x1 filter in place (transposed tiles)
 bool has_bt(int idx) { return idx == 0 || idx == 1 || idx == 4; }
 
-int launch_choice(int idx, const IgemmParams &p, hipStream_t st, bool bt = false)
+int launch_choice(int idx, const IgemmParams &p, hipStream_t st, bool bt = false, long long m_begin = 0, long long m_end = -1)
 {
     if (bt) {
         switch (idx) {
-        case 0: return launch<128, 128, 64, 2, 2, 2, true>(p, st);
-        case 1: return launch<256, 256, 64, 2, 2, 4, true>(p, st);
-        case 4: return launch<128, 64, 64, 2, 2, 2, true>(p, st);
+        case 0: return launch<128, 128, 64, 2, 2, 2, true>(p, st, m_begin, m_end);
+        case 1: return launch<256, 256, 64, 2, 2, 4, true>(p, st, m_begin, m_end);
+        case 4: return launch<128, 64, 64, 2, 2, 2, true>(p, st, m_begin, m_end);
         default: return MXC_ERR_UNSUPPORTED;
         }
     }
     switch (idx) {
-    case 0: return launch<128, 128, 64, 2, 2, 2>(p, st);
-    case 1: return launch<256, 256, 64, 2, 2, 4>(p, st);
-    case 2: return launch<256, 128, 64, 3, 4, 2>(p, st);
-    case 3: return launch<128, 256, 64, 3, 2, 4>(p, st);
-    case 4: return launch<128, 64, 64, 2, 2, 2>(p, st);
-    case 5: return launch<256, 64, 32, 3, 4, 1>(p, st);
-    case 6: return launch<128, 32, 64, 2, 4, 1>(p, st);
-    case 7: return launch<256, 32, 64, 2, 4, 1>(p, st);
-    case 8: return launch<256, 192, 64, 2, 4, 2>(p, st);
-    case 9: return launch<256, 256, 32, 4, 2, 4>(p, st);
-    default: return launch<128, 128, 32, 4, 2, 2>(p, st);
+    case 0: return launch<128, 128, 64, 2, 2, 2>(p, st, m_begin, m_end);
+    case 1: return launch<256, 256, 64, 2, 2, 4>(p, st, m_begin, m_end);
+    case 2: return launch<256, 128, 64, 3, 4, 2>(p, st, m_begin, m_end);
+    case 3: return launch<128, 256, 64, 3, 2, 4>(p, st, m_begin, m_end);
+    case 4: return launch<128, 64, 64, 2, 2, 2>(p, st, m_begin, m_end);
+    case 5: return launch<256, 64, 32, 3, 4, 1>(p, st, m_begin, m_end);
+    case 6: return launch<128, 32, 64, 2, 4, 1>(p, st, m_begin, m_end);
+    case 7: return launch<256, 32, 64, 2, 4, 1>(p, st, m_begin, m_end);
+    case 8: return launch<256, 192, 64, 2, 4, 2>(p, st, m_begin, m_end);
+    case 9: return launch<192, 256, 64, 2, 2, 4>(p, st, m_begin, m_end);
+    case 10: return launch<64, 256, 64, 3, 2, 4>(p, st, m_begin, m_end);
+    default: return launch<64, 128, 64, 3, 2, 2>(p, st, m_begin, m_end);
     }
 }
 
-// Tile choice: the shape with the least modelled time.  Tiles are dealt evenly to the 256 CUs, so a CU
-// works through ceil(tiles/256) tiles, `slots` at a time; a tile costs its area over the utilisation
-// the shape reaches, which drops when fewer workgroups than `slots` share the CU (less latency
-// hiding).  Padding waste and the partly filled last round are what differ between shapes.
-// MXC_FORCE_VARIANT=<name> (tuning sweeps only) overrides it.
-int choose_tile(long long M, int Co, int Kd)
+// How a GEMM of M rows is run: every row by tile shape `main`, or - when the last round of main tiles would
+// leave most CUs idle - rows [0, rows_main) by `main` in whole rounds over the chip and the rest by a second
+// launch of the smaller shape `tail` (tail < 0: one launch).
+struct Plan { int main, tail; long long rows_main; };
+
+int tile_index(const char *name, size_t len)
 {
+    for (int i = 0; i < N_TILE_CHOICES; ++i)
+        if (strlen(kTiles[i].name) == len && !strncmp(name, kTiles[i].name, len)) return i;
+    return -1;
+}
+
+// rows covered by the whole rounds of shape t over the chip's workgroup slots
+long long whole_round_rows(const TileChoice &t, long long M, int Co)
+{
+    const long long n_tiles = (Co + t.bn - 1) / t.bn, slots = 256LL * t.slots;
+    const long long tiles = ((M + t.bm - 1) / t.bm) * n_tiles;
+    const long long rows = (tiles / slots) * slots / n_tiles * t.bm;
+    return rows < M ? rows : M;
+}
+
+// Modelled time of shape t on M rows.  Tiles are dealt evenly to the 256 CUs, so a CU works through
+// ceil(tiles/256) tiles, `slots` at a time; a tile costs its area over the utilisation the shape reaches,
+// which drops when fewer workgroups than `slots` share the CU (less latency hiding).  Padding waste and the
+// partly filled last round are what differ between shapes.
+double model_time(const TileChoice &t, long long M, int Co, int KT, double fixed)
+{
+    const long long tiles = ((M + t.bm - 1) / t.bm) * ((Co + t.bn - 1) / t.bn);
+    const long long per_cu = (tiles + 255) / 256;
+    const double resident = per_cu < t.slots ? (double)per_cu : (double)t.slots;
+    const double util = t.util * (0.6 + 0.4 * resident / t.slots);
+    return (double)per_cu * ((double)t.bm * t.bn / util * KT + fixed / resident);
+}
+
+#include "tuned_igemm.inc"
+
+// Plan choice, in this order: MXC_FORCE_VARIANT=<name> or <main>+<tail> (tuning sweeps only); the table of
+// measured best plans (tuned_igemm.inc, written by the tuning script from timings on the device) when it
+// holds this GEMM; else the least modelled time over single shapes and main+tail pairs.
+Plan choose_plan(long long M, int Co, int Kd)
+{
+    if (const char *f = getenv("MXC_FORCE_VARIANT")) {
+        const char *plus = strchr(f, '+');
+        const int a = tile_index(f, plus ? (size_t)(plus - f) : strlen(f));
+        const int b = plus ? tile_index(plus + 1, strlen(plus + 1)) : -1;
+        if (a >= 0 && (!plus || b >= 0)) {
+            const long long rows = b >= 0 ? whole_round_rows(kTiles[a], M, Co) : M;
+            return (b >= 0 && rows > 0 && rows < M) ? Plan{a, b, rows} : Plan{a, -1, M};
+        }
+    }
+    for (const TunedIgemm &e : kTunedIgemm)
+        if (e.M == M && e.Co == Co && e.Kd == Kd) {
+            const int a = tile_index(e.main, strlen(e.main)), b = e.tail[0] ? tile_index(e.tail, strlen(e.tail)) : -1;
+            if (a < 0) break;
+            const long long rows = b >= 0 ? whole_round_rows(kTiles[a], M, Co) : M;
+            return (b >= 0 && rows > 0 && rows < M) ? Plan{a, b, rows} : Plan{a, -1, M};
+        }
     // Reductions of one or two stages (first layers): a workgroup's fixed cost (launch, pipeline fill,
     // epilogue: about 4 us, shared by the workgroups resident on the CU) outweighs its matrix work, so
     // fewer, larger tiles win.  In the model's units (tile area x stages at 256x256 speed) that cost
-    // is about 150000.
+    // is about 150000; a second launch costs about 200000 (5 us of drain, launch and refill).
     const int KT = (Kd + 63) / 64;
-    const double fixed = KT <= 2 ? 150000.0 : 0.0;
-    if (const char *f = getenv("MXC_FORCE_VARIANT"))
-        for (int i = 0; i < N_TILE_CHOICES; ++i)
-            if (!strcmp(f, kTiles[i].name)) return i;
-    int best = 0;
+    const double fixed = KT <= 2 ? 150000.0 : 0.0, second_launch = 200000.0;
+    Plan best{0, -1, M};
     double best_t = 1e300;
     for (int i = 0; i < N_TILE_CHOICES; ++i) {
-        const TileChoice &t = kTiles[i];
-        const long long tiles = ((M + t.bm - 1) / t.bm) * ((Co + t.bn - 1) / t.bn);
-        const long long per_cu = (tiles + 255) / 256;
-        const double resident = per_cu < t.slots ? (double)per_cu : (double)t.slots;
-        const double util = t.util * (0.6 + 0.4 * resident / t.slots);
-        const double time = (double)per_cu * ((double)t.bm * t.bn / util * KT + fixed / resident);
-        if (time < best_t) { best_t = time; best = i; }
+        const double t1 = model_time(kTiles[i], M, Co, KT, fixed);
+        if (t1 < best_t) { best_t = t1; best = Plan{i, -1, M}; }
+        const long long rows = whole_round_rows(kTiles[i], M, Co);
+        if (rows <= 0 || rows >= M) continue;
+        const double t_main = model_time(kTiles[i], rows, Co, KT, fixed);
+        for (int j = 0; j < N_TILE_CHOICES; ++j) {
+            if (j == i) continue;
+            const double t2 = t_main + model_time(kTiles[j], M - rows, Co, KT, fixed) + second_launch;
+            if (t2 < best_t) { best_t = t2; best = Plan{i, j, rows}; }
+        }
     }
     return best;
+}
+
+int choose_tile(long long M, int Co, int Kd) { return choose_plan(M, Co, Kd).main; }
+
+// runs the plan: one or two launches on the stream
+int launch_plan(const Plan &pl, const IgemmParams &p, hipStream_t st, bool bt = false)
+{
+    if (pl.tail < 0) return launch_choice(pl.main, p, st, bt);
+    const int rc = launch_choice(pl.main, p, st, bt, 0, pl.rows_main);
+    if (rc != MXC_OK) return rc;
+    return launch_choice(pl.tail, p, st, bt, pl.rows_main, -1);
+}
+
+// name of a plan for mxc_last_variant(): "<main>" or "<main>+<tail>"
+const char *plan_name(const Plan &pl)
+{
+    static thread_local char name[96];
+    if (pl.tail < 0) return kTiles[pl.main].name;
+    snprintf(name, sizeof(name), "%s+%s", kTiles[pl.main].name, kTiles[pl.tail].name);
+    return name;
 }
 
 // The kernel addresses both operands with signed 32-bit byte offsets, packs tile-row coordinates
@@ -802,11 +881,11 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
     p.in_mul_h = s.stride; p.in_mul_w = s.stride; p.in_off_h = -s.pad; p.in_off_w = -s.pad;
     p.Ho = s.P; p.Wo = s.Q; p.out_mul_h = 1; p.out_mul_w = 1; p.out_off_h = 0; p.out_off_w = 0;
     const long long M = (long long)s.N * s.P * s.Q;
-    const int tc = choose_tile(M, s.K, s.R * s.S * s.C);
-    *variant = kTiles[tc].name;
+    const Plan pl = choose_plan(M, s.K, s.R * s.S * s.C);
+    *variant = plan_name(pl);
     const int sp = (split_ws != nullptr && s.K % 8 == 0) ? split_count(M, s.K, s.R * s.S * s.C) : 1;
-    if (sp > 1) return launch_split(tc, p, M, sp, split_ws, y, post, st, variant);
-    return launch_choice(tc, p, st);
+    if (sp > 1) return launch_split(pl.main, p, M, sp, split_ws, y, post, st, variant);
+    return launch_plan(pl, p, st);
 }
 
 bool igemm_fwd_smallc_supported(const ConvShape &s)
@@ -830,9 +909,9 @@ int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y
     p.Mh = s.P; p.Mw = s.Q;
     p.in_mul_h = s.stride; p.in_mul_w = s.stride; p.in_off_h = 0; p.in_off_w = 0;
     p.Ho = s.P; p.Wo = s.Q; p.out_mul_h = 1; p.out_mul_w = 1; p.out_off_h = 0; p.out_off_w = 0;
-    const int tc = choose_tile((long long)s.N * s.P * s.Q, s.K, s.R * g.run);
-    *variant = kTiles[tc].name;
-    return launch_choice(tc, p, st);
+    const Plan pl = choose_plan((long long)s.N * s.P * s.Q, s.K, s.R * g.run);
+    *variant = plan_name(pl);
+    return launch_plan(pl, p, st);
 }
 
 bool igemm_bwd_data_supported(const ConvShape &s)
@@ -863,7 +942,7 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
         if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
     }
     size_t wt_off = 0;
-    int tc = 0;
+    Plan pl{0, -1, 0};
     for (int ph = 0; ph < s.stride; ++ph) {
         for (int pw = 0; pw < s.stride; ++pw) {
             const int TR = ph < s.R ? (s.R - ph + s.stride - 1) / s.stride : 0;
@@ -895,16 +974,17 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, 
                 if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
                 continue;
             }
-            tc = choose_tile((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
+            pl = choose_plan((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
+            if (bt && !has_bt(pl.tail)) pl = Plan{pl.main, -1, 0};
             if (split_ws != nullptr && s.stride == 1 && s.C % 8 == 0) {
                 const int sp = split_count((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
-                if (sp > 1) return launch_split(tc, p, (long long)s.N * Mh * Mw, sp, split_ws, dx, post, st, variant, bt);
+                if (sp > 1) return launch_split(pl.main, p, (long long)s.N * Mh * Mw, sp, split_ws, dx, post, st, variant, bt);
             }
-            const int rc = launch_choice(tc, p, st, bt);
+            const int rc = launch_plan(pl, p, st, bt);
             if (rc != MXC_OK) return rc;
         }
     }
-    *variant = kTiles[tc].name;
+    *variant = plan_name(pl);
     return MXC_OK;
 }
 
@@ -1010,7 +1090,7 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, voi
                        (bf16_t *)w2, s.K, s.C, s.R, s.S, s.stride, s.pad, g.G, g.U, g.uoff);
     if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
     size_t w2_off = 0;
-    int tc = 0;
+    Plan pl{0, -1, 0};
     for (int ph = 0; ph < s.stride; ++ph) {
         const int TR = ph < s.R ? (s.R - ph + s.stride - 1) / s.stride : 0;
         const int hh0 = ph >= s.pad ? 0 : (s.pad - ph + s.stride - 1) / s.stride;
@@ -1025,8 +1105,8 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, voi
         p.Ho = s.H; p.Wo = g.Wg; p.out_mul_h = s.stride; p.out_mul_w = 1; p.out_off_h = h_first; p.out_off_w = 0;
         w2_off += (size_t)g.G * 4 * TR * g.U * s.K;
         if (Mh <= 0) continue;
-        tc = choose_tile((long long)s.N * Mh * g.Wg, p.Co, TR * g.U * s.K);
-        const int rc = launch_choice(tc, p, st);
+        pl = choose_plan((long long)s.N * Mh * g.Wg, p.Co, TR * g.U * s.K);
+        const int rc = launch_plan(pl, p, st);
         if (rc != MXC_OK) return rc;
     }
     const long long rows = (long long)s.N * s.H;
@@ -1034,7 +1114,7 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, voi
     if (blocks > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
     hipLaunchKernelGGL(smallc_compact_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint2 *)dx4, (bf16_t *)dx, rows,
                        s.W, g.Wg * g.G, s.C, (const bf16_t *)post.mask);
-    *variant = kTiles[tc].name;
+    *variant = plan_name(pl);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
 }
 

@@ -435,29 +435,52 @@ struct Plan { int tile, k_tiles, n_tiles, splits, span; };
 // slots (256 CUs x slots per CU) x stages each split walks x time per stage, plus the traffic of
 // writing and re-reading one fp32 partial tensor per split.  MXC_FORCE_WGRAD=<name> (tuning sweeps
 // only) fixes the tile.
-Plan search_plan(const WgradGeom &g, int forced);
+Plan search_plan(const WgradGeom &g, int forced, int forced_splits);
 
-// The search below costs tens of microseconds; a call needs its answer up to three times (size query, workspace
-// carve-out, launch) and a training loop asks for the same few geometries over and over: keep the answers of
-// the calling thread (no locks; 32 entries, overwritten in turn).
+#include "tuned_wgrad.inc"
+
+int tile_index(const char *name, size_t len)
+{
+    for (int i = 0; i < N_TILES; ++i)
+        if (strlen(kTiles[i].name) == len && !strncmp(name, kTiles[i].name, len)) return i;
+    return -1;
+}
+
+// Tile and split count, in this order: MXC_FORCE_WGRAD=<tile>[/<splits>] (tuning sweeps only); the table of
+// measured best choices (tuned_wgrad.inc, written by the tuning script from timings on the device) when it
+// holds this geometry; else the time model's search.  The search costs tens of microseconds, a call needs
+// its answer up to three times (size query, workspace carve-out, launch) and a training loop asks for the
+// same few geometries over and over: the calling thread keeps its answers (no locks; 32 entries,
+// overwritten in turn).
 Plan make_plan(const WgradGeom &g)
 {
-    int forced = -1;
-    if (const char *f = getenv("MXC_FORCE_WGRAD"))
-        for (int i = 0; i < N_TILES; ++i)
-            if (!strcmp(f, kTiles[i].name)) forced = i;
-    struct Entry { WgradGeom g; int forced; Plan plan; bool used; };
+    int forced = -1, forced_splits = 0;
+    if (const char *f = getenv("MXC_FORCE_WGRAD")) {
+        const char *slash = strchr(f, '/');
+        forced = tile_index(f, slash ? (size_t)(slash - f) : strlen(f));
+        if (forced >= 0 && slash) forced_splits = atoi(slash + 1);
+    } else {
+        for (const TunedWgrad &e : kTunedWgrad)
+            if (e.N == g.N && e.H == g.H && e.W == g.W && e.C == g.pix && e.C == g.run && e.K == g.K && e.R == g.TR && e.S == g.TS &&
+                e.stride == g.stride && e.pad == g.pad && g.s2d == 1) {
+                forced = tile_index(e.tile, strlen(e.tile));
+                forced_splits = forced >= 0 ? e.splits : 0;
+                break;
+            }
+    }
+    struct Entry { WgradGeom g; int forced, forced_splits; Plan plan; bool used; };
     static thread_local Entry cache[32] = {};
     static thread_local int next = 0;
     for (const Entry &e : cache)
-        if (e.used && e.forced == forced && !memcmp(&e.g, &g, sizeof(WgradGeom))) return e.plan;
+        if (e.used && e.forced == forced && e.forced_splits == forced_splits && !memcmp(&e.g, &g, sizeof(WgradGeom))) return e.plan;
     Entry &slot = cache[next];
     next = (next + 1) % 32;
-    slot.g = g; slot.forced = forced; slot.plan = search_plan(g, forced); slot.used = true;
+    slot.g = g; slot.forced = forced; slot.forced_splits = forced_splits; slot.plan = search_plan(g, forced, forced_splits);
+    slot.used = true;
     return slot.plan;
 }
 
-Plan search_plan(const WgradGeom &g, int forced)
+Plan search_plan(const WgradGeom &g, int forced, int forced_splits)
 {
     const int RSC = g.TR * g.TS * g.run;
     const long long M = (long long)g.N * g.P * g.Q;
@@ -478,6 +501,7 @@ Plan search_plan(const WgradGeom &g, int forced)
         if (max_splits > 1024) max_splits = 1024;
         if (max_splits < 1) max_splits = 1;
         for (long long sp = 1; sp <= max_splits; ++sp) {
+            if (forced_splits > 0 && sp != (forced_splits < max_splits ? forced_splits : max_splits)) continue;
             const long long wgs = tiles * sp, rounds = (wgs + slots - 1) / slots;
             const long long stages = ((M + sp - 1) / sp + tc.bp - 1) / tc.bp;
             const double t_us = (double)rounds * (double)(stages + 6) * stage_us + (double)sp * split_us;
