@@ -100,6 +100,26 @@ int mxc_conv2d_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int s
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * mxc_conv2d_bwd_weight for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * computation, kernels and results as mxc_conv2d_bwd_weight, with the split-reduction partial sums
+ * (and, for MXC_NCHW, the converted operands) held in a 64 MiB array that is part of the library's
+ * device code - one copy per GPU, kept until the process ends.  The call allocates nothing.  x, dy,
+ * dw as in mxc_conv2d_bwd_weight, still caller-owned.
+ *   - Problems whose scratch need (what mxc_conv2d_workspace_bytes reports for MXC_BWD_WEIGHT)
+ *     exceeds 64 MiB are rejected with MXC_ERR_WORKSPACE before anything is launched.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different
+ *     streams, or several host threads) race on it; order them on one stream.  The array keeps the
+ *     last call's contents; no call depends on them.
+ *   - The first call on a device looks up the array's device address (hipGetSymbolAddress): make
+ *     that call outside any stream capture.  If the lookup fails: MXC_ERR_LAUNCH, nothing launched.
+ * Other errors as mxc_conv2d_bwd_weight.
+ */
+int mxc_conv2d_bwd_weight_static(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                 int dtype, int layout,
+                                 const void *x, const void *dy, void *dw, void *hip_stream);
+
+/*
  * Convolution grouped with the operations that follow it (the paper groups operators into a
  * single call where it can, Section 3.1 "Graph Optimization", and chains layers as
  * layer => Activation(relu) => layer, Section 2.1):

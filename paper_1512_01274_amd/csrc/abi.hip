@@ -2,6 +2,7 @@
 // and kernel selection.  See include/mxc.h for the contract of every call.
 #include <string.h>
 
+#include <mutex>
 #include <string>
 
 #include "mxc_internal.h"
@@ -286,6 +287,38 @@ int entry(int pass, int N, int C, int H, int W, int K, int R, int S, int stride,
 }  // namespace
 }  // namespace mxc
 
+// ---- scratch of the entry point that allocates nothing ------------------------------------------
+// One array per GPU, part of the loaded code object: it exists on every device the library runs on
+// from the first use of the library there until the process ends.  In host code the name below is
+// only a handle for hipGetSymbolAddress; kernels and copies get the device address it returns.
+#define MXC_STATIC_SCRATCH_BYTES (64u << 20)
+static __device__ __align__(256) unsigned char scratch[MXC_STATIC_SCRATCH_BYTES];
+
+namespace mxc {
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up once per device, with that device current).
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return MXC_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return MXC_ERR_LAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MXC_OK;
+}
+
+}  // namespace
+}  // namespace mxc
+
 using namespace mxc;
 
 extern "C" {
@@ -311,6 +344,24 @@ int mxc_conv2d_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int s
 {
     return entry(MXC_BWD_WEIGHT, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, PostOp(), workspace,
                  workspace_bytes, hip_stream);
+}
+
+int mxc_conv2d_bwd_weight_static(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                                 const void *x, const void *dy, void *dw, void *hip_stream)
+{
+    // argument errors first, as the other entry points report them; then the size against the array
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (!x || !dy || !dw) return MXC_ERR_NULL;
+    if (misaligned(x) || misaligned(dy) || misaligned(dw)) return MXC_ERR_ALIGN;
+    Carver need(nullptr);
+    MXC_TRY(run_pass(MXC_BWD_WEIGHT, s, dtype, layout, nullptr, nullptr, nullptr, PostOp(), need, nullptr, true));
+    if (need.used > MXC_STATIC_SCRATCH_BYTES) return MXC_ERR_WORKSPACE;
+    void *ws = nullptr;
+    MXC_TRY(static_scratch(&ws));
+    // every kernel of this pass writes the part of the scratch it later reads: nothing needs clearing
+    return entry(MXC_BWD_WEIGHT, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, PostOp(), ws, MXC_STATIC_SCRATCH_BYTES,
+                 hip_stream);
 }
 
 int mxc_conv2d_fwd_bias_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,

@@ -27,6 +27,8 @@ for _name in ("mxc_conv2d_fwd", "mxc_conv2d_bwd_data", "mxc_conv2d_bwd_weight"):
     _f = getattr(_lib, _name)
     _f.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP, _SZ, _VP]
     _f.restype = _I
+_lib.mxc_conv2d_bwd_weight_static.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP]
+_lib.mxc_conv2d_bwd_weight_static.restype = _I
 _lib.mxc_conv2d_workspace_bytes.argtypes = [_I] * 12 + [ctypes.POINTER(_SZ)]
 _lib.mxc_conv2d_workspace_bytes.restype = _I
 _lib.mxc_layout_convert.argtypes = [_I] * 7 + [_VP, _VP, _VP]
@@ -126,6 +128,13 @@ def mxc_conv2d_bwd_data(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, 
 
 def mxc_conv2d_bwd_weight(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, workspace=None, stream=None):
     _call(_lib.mxc_conv2d_bwd_weight, (N, C, H, W, K, R, S, stride, pad), dtype, layout, x, dy, dw, workspace, stream)
+
+
+def mxc_conv2d_bwd_weight_static(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, stream=None):
+    rc = _lib.mxc_conv2d_bwd_weight_static(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(x), _ptr(dy), _ptr(dw),
+                                           _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
 
 
 def _ws(workspace):
