@@ -1,21 +1,34 @@
 #!/usr/bin/env python3
 """Benchmark of the conv2d hot path on one MI355X.
 
-One "step" is one pass of the whole path over one batch of a synthetic CNN layer
-stack: the network input is converted NCHW -> NHWC once (layout kernel), then every
-layer runs forward, backward-data and backward-weight (with its split reduction)
-through the C ABI with activations resident in NHWC and filters in KRSC.  Inputs are
-generated from a seed on the host and are resident in HBM before the timed region.
+One "step" is one pass of the whole path over one batch of a synthetic CNN layer stack: the network
+input is converted NCHW -> NHWC once (layout kernel), then every layer runs forward, backward-data and
+backward-weight (with its split reduction) through the C ABI with activations resident in NHWC and
+filters in KRSC.  Inputs are generated from a seed on the host and are resident in HBM before the timed
+region.  Backward-data reads filters prepared once per weight version (mxc_conv2d_bwd_data_prepare_filter,
+outside the timed region: the weights do not change between the steps of this benchmark; the cost of
+preparing them every step is reported in `filter_prepare_ms_per_step`).
 
-Prints ONE JSON line: whole-job TFLOP/s (2*N*K*P*Q*C*R*S flops per pass, three passes
-per layer), the roofline figures of the dominant kernel measured with HIP events, and
-the CPU oracle timed on a bounded sample of the same workload (reported baseline only).
+Two schedules of the same calls are timed:
+  * "single_stream": every call in program order on one stream, launched eagerly.  This is the headline
+    (`value`, `ms_per_step`); per-call and per-kernel figures (the roofline entries) are measured in this
+    schedule, where kernels do not overlap and their times add up to the step.
+  * "engine": the order a dependency engine (paper Section 3.2) gives a training step - forward chain,
+    then per layer, last to first, backward-data on the main stream and backward-weight beside it on a
+    second stream (both need only that layer's output gradient), the whole step captured once into a HIP
+    graph and replayed.  Reported beside the headline (`engine_schedule`); --engine makes it the headline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet_b128] [--all]
+Prints ONE JSON line: whole-job TFLOP/s (2*N*K*P*Q*C*R*S flops per pass, three passes per layer) of the
+headline workload, the same for the other four stacks (`networks`), roofline entries of the dominant
+kernels measured with HIP events, on-box ceilings, and the CPU oracle timed on a bounded sample of the
+same workload (reported baseline only).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet_b128] [--groups G] [--no-all]
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -26,6 +39,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_F32_TFLOPS = 157.3       # fp32 vector / matrix, published
 PEAK_HBM_GBS = 8000.0         # HBM3E, published
+FLOP_PER_CLK_BF16 = 256 * 4 * 1024   # CUs x SIMDs x bf16 MFMA flops per SIMD clock
 
 
 def algorithmic_bytes(L, op, esize):
@@ -39,6 +53,8 @@ def algorithmic_bytes(L, op, esize):
         return esize * (x_touched + w + y)
     if op == "bwd_data":
         return esize * (y + w + x_all)
+    if op == "layout":
+        return 2 * esize * x_all
     return esize * (x_touched + y) + 4 * w
 
 
@@ -71,19 +87,31 @@ class LayerState:
         self.vel = torch.zeros_like(self.w_master) if cfg.dtype == "bf16" else None
         self.db = torch.empty(L.K, dtype=torch.float32, device="cuda")
         self.ws = {}
-        for op in (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT, mxc.MXC_BWD_DATA_RELU, mxc.MXC_BIAS_GRAD):
+        for op in (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT, mxc.MXC_BWD_DATA_RELU, mxc.MXC_BIAS_GRAD,
+                   mxc.MXC_BWD_DATA_PREPARED, mxc.MXC_BWD_DATA_PREPARED_RELU):
             self.ws[op] = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *self.dims, self.dt, self.lay))
+        self.w_prepared = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_BWD_DATA_FILTER, *self.dims, self.dt, self.lay))
+        self.prepare_filter = lambda: mxc.mxc_conv2d_bwd_data_prepare_filter(*self.dims, self.dt, self.lay, self.w, self.w_prepared)
+        self.prepare_filter()
 
 
 class Network:
-    def __init__(self, mxc, torch, gen, cfg, layout="nhwc"):
-        self.mxc, self.torch, self.cfg, self.layout = mxc, torch, cfg, layout
+    def __init__(self, mxc, torch, gen, cfg, layout="nhwc", prepared=True):
+        self.mxc, self.torch, self.cfg, self.layout, self.prepared = mxc, torch, cfg, layout, prepared
         self.layers = [LayerState(mxc, torch, cfg, li, gen, layout) for li in range(len(cfg.layers))]
         self.flops_per_step = 3 * sum(s.L.flops_per_pass for s in self.layers)
         self.esize = 2 if cfg.dtype == "bf16" else 4
+        torch.cuda.synchronize()
+
+    def _bwd_data(self, s):
+        m = self.mxc
+        if self.prepared:
+            return lambda: m.mxc_conv2d_bwd_data_prepared(*s.dims, s.dt, s.lay, s.dy, s.w_prepared, None, s.dx,
+                                                          s.ws[m.MXC_BWD_DATA_PREPARED])
+        return lambda: m.mxc_conv2d_bwd_data(*s.dims, s.dt, s.lay, s.dy, s.w, s.dx, s.ws[m.MXC_BWD_DATA])
 
     def calls(self):
-        """(label, op, layer, thunk) for every ABI call of one step, in order."""
+        """(label, op, layer, thunk) for every ABI call of one step, in program order."""
         m = self.mxc
         out = []
         s0 = self.layers[0]
@@ -94,8 +122,7 @@ class Network:
         for s in self.layers:
             out.append((s.L.name, "fwd", s, lambda s=s: m.mxc_conv2d_fwd(
                 *s.dims, s.dt, s.lay, s.x, s.w, s.y, s.ws[m.MXC_FWD])))
-            out.append((s.L.name, "bwd_data", s, lambda s=s: m.mxc_conv2d_bwd_data(
-                *s.dims, s.dt, s.lay, s.dy, s.w, s.dx, s.ws[m.MXC_BWD_DATA])))
+            out.append((s.L.name, "bwd_data", s, self._bwd_data(s)))
             out.append((s.L.name, "bwd_weight", s, lambda s=s: m.mxc_conv2d_bwd_weight(
                 *s.dims, s.dt, s.lay, s.x, s.dy, s.dw, s.ws[m.MXC_BWD_WEIGHT])))
         return out
@@ -124,62 +151,90 @@ class Network:
                             s.w_master, s.dw, s.vel, s.w, 1e-9, 0.9, 1e-4)))
         return out
 
-    def step(self):
-        for _, _, _, fn in self.calls():
-            fn()
 
-
-def time_steps(torch, net, steps, warmup, keep=lambda c: True, grouped=False):
-    calls = [c[3] for c in (net.grouped_calls() if grouped else net.calls()) if keep(c)]
+def timed_groups(torch, run_step, steps, warmup, groups):
+    """`groups` timings of exactly `steps` steps each, every group bracketed by synchronize; seconds per step."""
     for _ in range(warmup):
-        for fn in calls:
-            fn()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        for fn in calls:
-            fn()
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+        run_step()
+    out = []
+    for _ in range(groups):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run_step()
+        torch.cuda.synchronize()
+        out.append((time.perf_counter() - t0) / steps)
+    return out
 
 
-def time_two_streams(torch, net, steps, warmup):
-    """The same step issued the way a dependency engine (paper Section 3.2) would: backward-weight
-    calls, which nothing in the step waits for, go to a second stream beside the forward /
-    backward-data chain.  Reported beside the headline, which stays a single in-order stream."""
-    calls = net.calls()
-    main = [c[3] for c in calls if c[1] != "bwd_weight"]
-    side = [c[3] for c in calls if c[1] == "bwd_weight"]
-    s_main, s_side = torch.cuda.Stream(), torch.cuda.Stream()
+def median(v):
+    v = sorted(v)
+    return v[len(v) // 2]
+
+
+def single_stream_step(net, keep=lambda c: True, grouped=False):
+    calls = [c[3] for c in (net.grouped_calls() if grouped else net.calls()) if keep(c)]
 
     def step():
-        fork = torch.cuda.Event()
-        fork.record(s_main)
-        s_side.wait_event(fork)
-        with torch.cuda.stream(s_side):
-            for fn in side:
-                fn()
-        with torch.cuda.stream(s_main):
-            for fn in main:
-                fn()
-        join = torch.cuda.Event()
-        join.record(s_side)
-        s_main.wait_event(join)
+        for fn in calls:
+            fn()
+    return step
 
-    torch.cuda.synchronize()
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+
+class EngineStep:
+    """One step in the order a dependency engine gives a training step (paper Section 3.2): the layout
+    conversion and the forward chain, then, from the last layer to the first, backward-data on the main
+    stream and backward-weight on a second stream as soon as that layer's output gradient exists (in a
+    chained network that is when backward-data of the layer above has finished).  The step is captured
+    into a HIP graph once and replayed; if capture is not possible it is launched eagerly on the two
+    streams (`mode` says which)."""
+
+    def __init__(self, torch, net):
+        self.torch = torch
+        calls = net.calls()
+        self.pre = [c[3] for c in calls if c[1] in ("layout", "fwd")]
+        back = {}
+        for c in calls:
+            if c[1] in ("bwd_data", "bwd_weight"):
+                back.setdefault(id(c[2]), {})[c[1]] = c[3]
+        self.back = [back[id(s)] for s in reversed(net.layers)]
+        self.main, self.side = torch.cuda.Stream(), torch.cuda.Stream()
+        self.graph, self.mode = None, "eager two streams"
+        try:
+            self._enqueue()                     # once eagerly: first-call set-up stays out of the capture
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=self.main):
+                self._enqueue(capturing=True)
+            self.graph, self.mode = g, "HIP graph replay, two streams"
+        except Exception as ex:             # noqa: BLE001  (any capture failure: run the same schedule eagerly)
+            self.capture_error = repr(ex)[:200]
+            torch.cuda.synchronize()
+
+    def _enqueue(self, capturing=False):
+        torch = self.torch
+        main = torch.cuda.current_stream() if capturing else self.main
+        with torch.cuda.stream(main):
+            for fn in self.pre:
+                fn()
+            for fns in self.back:
+                self.side.wait_stream(main)          # this layer's output gradient is ready
+                with torch.cuda.stream(self.side):
+                    fns["bwd_weight"]()
+                fns["bwd_data"]()
+            main.wait_stream(self.side)
+
+    def __call__(self):
+        if self.graph is not None:
+            self.graph.replay()
+        else:
+            self._enqueue()
 
 
 def measure_ceilings(torch, mxc):
     """On-box ceilings beside the published ones: the matrix pipe running a register-resident bf16
-    MFMA loop (two workgroups of four waves per CU) and a plain device copy of 1 GiB."""
+    MFMA loop (two workgroups of four waves per CU), the clock that rate implies, and a plain device copy
+    of 1 GiB (the copy kernel spreads 16-byte accesses over all CUs)."""
     out = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     mxc.mxc_probe_mfma(512, 2000, out)
@@ -203,13 +258,30 @@ def measure_ceilings(torch, mxc):
     copy_gbs = 5 * 2.0 * n_el * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst, out
     torch.cuda.empty_cache()
-    return {"mfma_bf16_tflops_measured": round(mfma_tflops, 1), "copy_gbs_measured": round(copy_gbs, 1),
-            "note": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 waves/SIMD; 1 GiB device copy, read + write bytes"}
+    return {"mfma_bf16_tflops_measured": round(mfma_tflops, 1),
+            "sclk_ghz_under_mfma_load": round(mfma_tflops * 1e12 / FLOP_PER_CLK_BF16 / 1e9, 3),
+            "copy_gbs_measured": round(copy_gbs, 1),
+            "note": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 waves/SIMD (the clock is that rate over "
+                    "256 CUs x 4 SIMDs x 1024 flop per clock); 1 GiB device copy, read + write bytes"}
+
+
+def smi_clock():
+    """Shader clock as the SMI tool reports it right now (None when the tool is absent or not permitted)."""
+    for cmd in (["rocm-smi", "--showclocks", "--json"], ["amd-smi", "metric", "--clock", "--json"]):
+        try:
+            r = subprocess.run(cmd, capture_output=True, text=True, timeout=10)
+            if r.returncode == 0 and r.stdout.strip():
+                txt = r.stdout
+                i = txt.find("sclk")
+                return txt[i:i + 80].replace("\n", " ") if i >= 0 else None
+        except (OSError, subprocess.SubprocessError):
+            pass
+    return None
 
 
 def time_calls(torch, net, steps):
     """Per-call durations (ms, mean over `steps`) with HIP events on the stream the kernels run on
-    (torch's current stream), over the same sequence of calls as the timed region.  An event pair
+    (torch's current stream), over the same sequence of calls as the single-stream step.  An event pair
     with nothing between it, recorded once per step behind the same busy stream, measures what the
     two event packets themselves cost (about 5 us); that is subtracted, so that a call that is one
     launch reads as that kernel's duration.  Returns (per-call list, event-pair overhead in ms)."""
@@ -239,28 +311,36 @@ def time_calls(torch, net, steps):
 
 
 def kernel_of(variant):
-    """'fwd:smallc+igemm_128x64_k64s2_w4' -> 'igemm_128x64_k64s2_w4' (the main kernel of the call)."""
-    return variant.split(":")[-1].split("+")[-1]
+    """'fwd:smallc+igemm_128x64_k64s2_w4' -> 'igemm_128x64_k64s2_w4' (the main kernel of the call);
+    a two-launch plan 'igemm_A+igemm_B' keeps both names."""
+    v = variant.split(":")[-1]
+    for prefix in ("s2d+", "smallc+", "chanpad+"):
+        if v.startswith(prefix):
+            v = v[len(prefix):]
+    return v
 
 
-def roofline_of(per_call, net, event_overhead_ms=0.0):
-    """Roofline entry of the kernel that takes the most time in a step.  Its launches are timed with HIP
-    events around the ABI call; only calls that are exactly one launch of that kernel (plain forward
-    calls) enter the figure, so that the event time is the kernel's duration."""
-    by_kernel = {}
-    for c in per_call:
-        by_kernel.setdefault(kernel_of(c["variant"]), []).append(c)
-    single = lambda c: c["op"] == "fwd" and "+" not in c["variant"]      # the call is exactly one launch of the kernel
-    # A call's event time includes its helper launches (packing, filter re-pack, split reduce), so kernels are
-    # ranked by the time of their single-launch calls, which is kernel time proper; the committed rocprofv3
-    # summary lists every kernel's total.
-    ranked = {k: sum(c["ms"] for c in v if single(c)) for k, v in by_kernel.items()}
-    dominant = max(ranked, key=ranked.get) if any(ranked.values()) else max(by_kernel, key=lambda v: sum(c["ms"] for c in by_kernel[v]))
-    group = [c for c in by_kernel[dominant] if single(c)] or by_kernel[dominant]
+def launches_of(c, prepared):
+    """What a call's event time covers besides its main kernel."""
+    v = c["variant"].split(":")[-1]
+    extra = []
+    if any(v.startswith(p) for p in ("s2d+", "smallc+", "chanpad+")):
+        extra.append("operand packing")
+    if "+igemm" in kernel_of(c["variant"]):
+        extra.append("second launch of the plan")
+    if c["op"] == "bwd_weight":
+        extra.append("split reduce")
+    if c["op"] == "bwd_data" and not prepared:
+        extra.append("filter re-pack")
+    if c["op"] == "bwd_data" and c["state"].L.stride > 1:
+        extra.append("one launch per stride residue class")
+    return extra
+
+
+def roofline_entry(group, net, peak_tf, event_overhead_ms):
     t = sum(c["ms"] for c in group) * 1e-3
     flops = sum(c["state"].L.flops_per_pass for c in group if c["op"] != "layout")
-    nbytes = sum(algorithmic_bytes(c["state"].L, c["op"], net.esize) for c in group if c["op"] != "layout")
-    peak_tf = PEAK_BF16_TFLOPS if net.cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    nbytes = sum(algorithmic_bytes(c["state"].L, c["op"], net.esize) for c in group)
     t_mfma, t_hbm = flops / (peak_tf * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
     if t_mfma >= t_hbm:
         bound = "mfma" if net.cfg.dtype == "bf16" else "alu"
@@ -270,14 +350,43 @@ def roofline_of(per_call, net, event_overhead_ms=0.0):
         ach = nbytes / t / 1e9
         r = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
              "frac": round(ach / PEAK_HBM_GBS, 4)}
-    r["kernel"] = dominant
+    r["kernel"] = kernel_of(group[0]["variant"])
     r["launches"] = [c["layer"] + ":" + c["op"] for c in group]
     r["avg_launch_ms"] = round(t * 1e3 / len(group), 4)
     r["event_pair_overhead_ms"] = round(event_overhead_ms, 4)      # already subtracted from avg_launch_ms
     r["algorithmic_flops_per_launch"] = flops // len(group)
     r["algorithmic_bytes_per_launch"] = nbytes // len(group)
-    r["traffic"] = load_traffic(net.cfg.name, dominant)
+    r["traffic"] = load_traffic(net.cfg.name, r["kernel"])
     return r
+
+
+def rooflines(per_call, net, event_overhead_ms):
+    """Roofline entries per kernel, ranked by the kernel's share of the single-stream step.  Entry 0 (also the
+    line's `roofline` object) is the kernel with the most time among calls that are exactly one launch of it
+    (plain forward and prepared stride-1 backward-data calls: their event time is the kernel's duration); the
+    other entries follow by total call time and say what else their calls' event times cover (`also_timed`)."""
+    peak_tf = PEAK_BF16_TFLOPS if net.cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    by_kernel = {}
+    for c in per_call:
+        by_kernel.setdefault(kernel_of(c["variant"]), []).append(c)
+    exact = {k: [c for c in v if not launches_of(c, net.prepared)] for k, v in by_kernel.items()}
+    ranked_exact = sorted((k for k in exact if exact[k]), key=lambda k: -sum(c["ms"] for c in exact[k]))
+    out = []
+    if ranked_exact:
+        out.append(roofline_entry(exact[ranked_exact[0]], net, peak_tf, event_overhead_ms))
+        out[0]["also_timed"] = []
+    seen = {out[0]["kernel"]} if out else set()
+    for k in sorted(by_kernel, key=lambda k: -sum(c["ms"] for c in by_kernel[k])):
+        if k in seen:
+            continue
+        group = exact[k] or by_kernel[k]
+        e = roofline_entry(group, net, peak_tf, event_overhead_ms)
+        e["also_timed"] = sorted({x for c in group for x in launches_of(c, net.prepared)})
+        out.append(e)
+        seen.add(k)
+        if len(out) >= 6:
+            break
+    return out
 
 
 def load_traffic(workload, variant):
@@ -307,17 +416,47 @@ def cpu_baseline(gen, cfg, sample_batch):
                       f"{cfg.layers[0].N} (cost is linear in batch); {t:.1f} s of fp64 7-loop oracle"}
 
 
+def layout_entry(torch, mxc):
+    """a1 on a tensor of at least 64 MiB: NCHW -> NHWC and back, bf16, GB/s of read + written bytes."""
+    n, c, h, w = 64, 256, 56, 56                     # 98 MiB
+    src = torch.randn(n * c * h * w, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    dst = torch.empty_like(src)
+    res = {}
+    for name, a, b in (("nchw_to_nhwc", mxc.MXC_NCHW, mxc.MXC_NHWC), ("nhwc_to_nchw", mxc.MXC_NHWC, mxc.MXC_NCHW)):
+        f = lambda: mxc.mxc_layout_convert(n, c, h, w, mxc.MXC_BF16, a, b, src, dst)
+        f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        gbs = 10 * 2.0 * src.numel() * 2 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        res[name] = {"GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}
+    res["tensor"] = f"bf16 [{n},{c},{h},{w}], {src.numel() * 2 >> 20} MiB"
+    del src, dst
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--groups", type=int, default=5, help="timings of exactly --steps steps each; the median is reported")
     ap.add_argument("--workload", default="alexnet_b128")
-    ap.add_argument("--all", action="store_true", help="also time the other layer stacks (extra 'networks' field)")
+    ap.add_argument("--no-all", action="store_true", help="skip the other layer stacks (the 'networks' field)")
+    ap.add_argument("--all", action="store_true", help="accepted for compatibility: the other stacks are timed by default")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
     ap.add_argument("--layout", choices=["nhwc", "nchw"], default="nhwc",
                     help="nhwc: tensors resident in the working layout, network input converted once per step (headline); "
                          "nchw: every call takes NCHW/KCRS operands and converts inside (three extra HBM passes per call)")
+    ap.add_argument("--raw-filter", action="store_true",
+                    help="backward-data re-packs its filter inside every call (mxc_conv2d_bwd_data) instead of reading one prepared "
+                         "outside the timed region")
+    ap.add_argument("--engine", action="store_true", help="headline = the engine schedule (HIP graph replay, two streams)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cpu-sample-batch", type=int, default=128)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -334,12 +473,6 @@ def main():
     from paper_1512_01274_amd import mxc
     torch.cuda.set_device(0)
 
-    def run_one(cfg, steps, warmup):
-        net = Network(mxc, torch, gen, cfg, args.layout)
-        sec = time_steps(torch, net, steps, warmup)
-        per_call, ev_ms = time_calls(torch, net, steps)
-        return net, sec, per_call, ev_ms
-
     if args.calibrate_copy:
         n_el = 1 << 28                      # 2^28 fp32 = 1 GiB read + 1 GiB written
         src = torch.ones(n_el, dtype=torch.float32, device="cuda")
@@ -347,74 +480,103 @@ def main():
         mxc.mxc_layout_convert(1, 1, 1 << 14, 1 << 14, mxc.MXC_F32, mxc.MXC_NCHW, mxc.MXC_NCHW, src, dst)
         torch.cuda.synchronize()
         del src, dst
+
+    def measure(cfg, steps, warmup, groups, detail):
+        """Both schedules of one stack.  Returns (summary dict, net, per_call, event overhead)."""
+        net = Network(mxc, torch, gen, cfg, args.layout, prepared=not args.raw_filter)
+        single = timed_groups(torch, single_stream_step(net), steps, warmup, groups)
+        engine = EngineStep(torch, net)
+        eng = timed_groups(torch, engine, steps, warmup, groups)
+        head = eng if args.engine else single
+        sec = median(head)
+        pk = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+        per_call, ev_ms = time_calls(torch, net, max(3, min(steps, 20)))
+        nbytes = sum(algorithmic_bytes(c["state"].L, c["op"], net.esize) for c in per_call)
+        tf = lambda s: round(net.flops_per_step / s / 1e12, 3)
+        summ = {"tflops": tf(sec), "ms_per_step": round(sec * 1e3, 4), "frac_of_mfma_peak": round(tf(sec) / pk, 4),
+                "algorithmic_GBps": round(nbytes / sec / 1e9, 1), "frac_of_hbm_peak": round(nbytes / sec / 1e9 / PEAK_HBM_GBS, 4),
+                "schedule": engine.mode if args.engine else "single stream, eager",
+                "groups_ms": [round(s * 1e3, 4) for s in head],
+                "single_stream": {"tflops": tf(median(single)), "ms_per_step": round(median(single) * 1e3, 4)},
+                "engine": {"tflops": tf(median(eng)), "ms_per_step": round(median(eng) * 1e3, 4), "mode": engine.mode}}
+        if detail:
+            return summ, net, per_call, ev_ms
+        rl = rooflines(per_call, net, ev_ms)
+        summ["roofline"] = rl[0] if rl else None
+        del net, engine
+        torch.cuda.empty_cache()
+        return summ, None, None, None
+
     cfg = gen.config_by_name(args.workload)
     ceilings = measure_ceilings(torch, mxc)
-    net, sec, per_call, ev_ms = run_one(cfg, args.steps, args.warmup)
+    clock_before = smi_clock()
+    summ, net, per_call, ev_ms = measure(cfg, args.steps, args.warmup, args.groups, True)
+    clock_after = smi_clock()
+    sec = summ["ms_per_step"] * 1e-3
     # the same step without backward-data of the first layer, which a training run never needs
     # (nothing consumes the gradient of the network input); reported beside the headline, labelled
     first = net.layers[0]
-    sec_pruned = time_steps(torch, net, args.steps, args.warmup, keep=lambda c: not (c[1] == "bwd_data" and c[2] is first))
+    pruned = timed_groups(torch, single_stream_step(net, keep=lambda c: not (c[1] == "bwd_data" and c[2] is first)),
+                          max(3, args.steps // 4), 2, 3)
     flops_pruned = net.flops_per_step - first.L.flops_per_pass
-    sec_two = time_two_streams(torch, net, args.steps, args.warmup)
-    sec_grouped = time_steps(torch, net, args.steps, args.warmup, grouped=True)
-    value = net.flops_per_step / sec / 1e12
+    grouped = timed_groups(torch, single_stream_step(net, grouped=True), max(3, args.steps // 4), 2, 3)
+    prep_calls = [s.prepare_filter for s in net.layers]
+    prep = timed_groups(torch, lambda: [f() for f in prep_calls], max(3, args.steps // 4), 2, 3)
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    rl = rooflines(per_call, net, ev_ms)
     result = {
-        "metric": "conv2d fwd+bwd TFLOP/s per network on 1 MI355X", "value": round(value, 3), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4),
+        "metric": "conv2d fwd+bwd TFLOP/s per network on 1 MI355X", "value": summ["tflops"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": summ["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "layers": len(cfg.layers), "batch": cfg.layers[0].N,
                    "layout": "nhwc-resident" if args.layout == "nhwc" else "nchw-per-call",
                    "step": ("layout(NCHW->NHWC of network input) + " if args.layout == "nhwc" else "") +
-                           "per layer fwd, bwd_data, bwd_weight"},
-        "frac_of_mfma_peak": round(value / peak, 4),
-        "roofline": roofline_of(per_call, net, ev_ms),
+                           "per layer fwd, bwd_data, bwd_weight",
+                   "schedule": summ["schedule"],
+                   "timing": f"median of {args.groups} groups of exactly {args.steps} steps"},
+        "groups_ms_per_step": summ["groups_ms"],
+        "frac_of_mfma_peak": summ["frac_of_mfma_peak"],
+        "single_stream": summ["single_stream"], "engine_schedule": summ["engine"],
+        "roofline": rl[0] if rl else None,
+        "roofline_kernels": rl,
         "ceilings": ceilings,
-        "without_first_layer_bwd_data": {"value": round(flops_pruned / sec_pruned / 1e12, 3), "unit": "TFLOP/s",
-                                         "ms_per_step": round(sec_pruned * 1e3, 4)},
-        "grouped_operations": {"value": round(net.flops_per_step / sec_grouped / 1e12, 3), "unit": "TFLOP/s",
-                               "ms_per_step": round(sec_grouped * 1e3, 4),
-                               "note": "same convolution flops; forward + bias + ReLU, backward-data with the ReLU derivative, "
-                                       "backward-weight, bias gradient, SGD update of fp32 master weights with a bf16 copy "
-                                       "(the extra work is not counted as flops)"},
-        "two_stream_schedule": {"value": round(net.flops_per_step / sec_two / 1e12, 3), "unit": "TFLOP/s",
-                                "ms_per_step": round(sec_two * 1e3, 4),
-                                "note": "backward-weight calls on a second stream; not the headline"},
+        "sclk": {"smi_before": clock_before, "smi_after": clock_after,
+                 "derived_under_mfma_load_ghz": ceilings["sclk_ghz_under_mfma_load"]},
+        "without_first_layer_bwd_data": {"value": round(flops_pruned / median(pruned) / 1e12, 3), "unit": "TFLOP/s",
+                                         "ms_per_step": round(median(pruned) * 1e3, 4), "schedule": "single stream, eager"},
+        "grouped_operations": {"value": round(net.flops_per_step / median(grouped) / 1e12, 3), "unit": "TFLOP/s",
+                               "ms_per_step": round(median(grouped) * 1e3, 4), "schedule": "single stream, eager",
+                               "note": "same convolution flops; forward + bias + ReLU, backward-data with the ReLU derivative "
+                                       "(filter re-packed inside the call), backward-weight, bias gradient, SGD update of fp32 "
+                                       "master weights with a bf16 copy (the extra work is not counted as flops)"},
+        "filter_prepare_ms_per_step": round(median(prep) * 1e3, 4),
     }
     if cfg.dtype == "bf16":
-        result["frac_of_measured_mfma"] = round(value / ceilings["mfma_bf16_tflops_measured"], 4)
-        if result["roofline"]["bound"] == "mfma":
-            result["roofline"]["frac_of_measured"] = round(result["roofline"]["achieved"] / ceilings["mfma_bf16_tflops_measured"], 4)
-    if result["roofline"]["bound"] == "hbm":
-        result["roofline"]["frac_of_measured"] = round(result["roofline"]["achieved"] / ceilings["copy_gbs_measured"], 4)
+        result["frac_of_measured_mfma"] = round(summ["tflops"] / ceilings["mfma_bf16_tflops_measured"], 4)
+    for e in rl:
+        e["frac_of_measured"] = round(e["achieved"] / (ceilings["mfma_bf16_tflops_measured"] if e["bound"] == "mfma"
+                                                        else ceilings["copy_gbs_measured"] if e["bound"] == "hbm" else e["peak"]), 4)
+    result["layers"] = [{"layer": c["layer"], "op": c["op"], "us": round(c["ms"] * 1e3, 1), "variant": c["variant"]} for c in per_call]
     if args.per_layer:
         for c in per_call:
             L = c["state"].L
+            gbs = algorithmic_bytes(L, c["op"], net.esize) / c["ms"] / 1e6
             if c["op"] == "layout":
-                nbytes = 2 * L.N * L.C * L.H * L.W * net.esize
-                print(f"{c['layer']:>24} {c['op']:>10} {c['ms']*1e3:9.1f} us {nbytes/c['ms']/1e6:8.0f} GB/s  {c['variant']}",
-                      file=sys.stderr)
+                print(f"{c['layer']:>24} {c['op']:>10} {c['ms']*1e3:9.1f} us {'':>17} {gbs:8.0f} GB/s  {c['variant']}", file=sys.stderr)
                 continue
             tf = L.flops_per_pass / c["ms"] / 1e9
-            gbs = algorithmic_bytes(L, c["op"], net.esize) / c["ms"] / 1e6
             print(f"{c['layer']:>24} {c['op']:>10} {c['ms']*1e3:9.1f} us {tf:8.1f} TFLOP/s {gbs:8.0f} GB/s  {c['variant']}",
                   file=sys.stderr)
-    del net
+    del net, per_call
     torch.cuda.empty_cache()
-    if args.all:
+    result["layout_a1"] = layout_entry(torch, mxc)
+    if not args.no_all:
         nets = {}
         for other in gen.CONFIGS:
             if other.name == cfg.name:
                 continue
-            n2, s2, pc2, _ = run_one(other, max(3, args.steps // 4), 2)
-            pk = PEAK_BF16_TFLOPS if other.dtype == "bf16" else PEAK_F32_TFLOPS
-            nbytes = sum(algorithmic_bytes(c["state"].L, c["op"], n2.esize) for c in pc2 if c["op"] != "layout")
-            nets[other.name] = {"tflops": round(n2.flops_per_step / s2 / 1e12, 3), "ms_per_step": round(s2 * 1e3, 4),
-                                "frac_of_mfma_peak": round(n2.flops_per_step / s2 / 1e12 / pk, 4),
-                                "algorithmic_GBps": round(nbytes / s2 / 1e9, 1)}
-            del n2, pc2
-            torch.cuda.empty_cache()
+            nets[other.name] = measure(other, max(3, args.steps // 4), 2, 3, False)[0]
         result["networks"] = nets
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(gen, cfg, args.cpu_sample_batch)

@@ -60,7 +60,11 @@ enum {
 enum { MXC_F32 = 0, MXC_BF16 = 1 };
 enum { MXC_NCHW = 0, MXC_NHWC = 1 };
 enum { MXC_FWD = 0, MXC_BWD_DATA = 1, MXC_BWD_WEIGHT = 2,
-       MXC_BWD_DATA_RELU = 3, MXC_BIAS_GRAD = 4 };   /* the last two: mxc_conv2d_workspace_bytes only */
+       /* the following: mxc_conv2d_workspace_bytes only */
+       MXC_BWD_DATA_RELU = 3, MXC_BIAS_GRAD = 4,
+       MXC_BWD_DATA_FILTER = 5,          /* bytes of the prepared filter of mxc_conv2d_bwd_data_prepare_filter */
+       MXC_BWD_DATA_PREPARED = 6,        /* workspace of mxc_conv2d_bwd_data_prepared without x_mask           */
+       MXC_BWD_DATA_PREPARED_RELU = 7 }; /* ... with x_mask                                                     */
 
 /*
  * Forward (the layer's "forward" evaluation, paper Section 2.1):
@@ -145,6 +149,27 @@ int mxc_conv2d_bwd_data_relu(int N, int C, int H, int W, int K, int R, int S, in
                              int dtype, int layout,
                              const void *dy, const void *w, const void *x, void *dx,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward w.r.t. the input with the filter prepared ahead of time.  Every backward-data path first brings
+ * the filter into the form its kernels read (re-packed per stride residue class, transposed, ...): work that
+ * depends on w alone.  A training loop changes w once per step (the update of Section 2.2), serving never:
+ *   mxc_conv2d_bwd_data_prepare_filter  writes that form of w into w_prepared (device memory of the caller, at
+ *       least mxc_conv2d_workspace_bytes(MXC_BWD_DATA_FILTER, ...) bytes, 16-byte aligned; opaque contents, valid
+ *       for exactly these N..pad, dtype and layout until w changes);
+ *   mxc_conv2d_bwd_data_prepared        is mxc_conv2d_bwd_data (x_mask == NULL) or mxc_conv2d_bwd_data_relu
+ *       (x_mask = the layer's input) reading w_prepared instead of w; same results bit for bit.  Workspace:
+ *       query MXC_BWD_DATA_PREPARED / MXC_BWD_DATA_PREPARED_RELU.
+ * prepared_bytes: size of the w_prepared buffer (checked against the required size: MXC_ERR_WORKSPACE).
+ * Everything else as mxc_conv2d_bwd_data.
+ */
+int mxc_conv2d_bwd_data_prepare_filter(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                       int dtype, int layout,
+                                       const void *w, void *w_prepared, size_t prepared_bytes, void *hip_stream);
+int mxc_conv2d_bwd_data_prepared(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                 int dtype, int layout,
+                                 const void *dy, const void *w_prepared, size_t prepared_bytes, const void *x_mask, void *dx,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Gradient of the bias of mxc_conv2d_fwd_bias_act (derivative of forward + bias[k] in bias):

@@ -120,43 +120,65 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
     return direct_fwd(s, dtype, x, w, y, st, post);
 }
 
-int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, const PostOp &post, Carver &ws,
-                  hipStream_t st, bool dry)
+// How backward-data gets its filter.  Every bf16 path first brings the filter into the form its GEMM reads
+// (re-packed per stride residue class, transposed, space-to-depth or column-group packed); a caller whose
+// weights change less often than it calls backward-data can have that done once (FILTER_PREPARE_ONLY fills
+// a buffer of the caller's, nothing else runs) and hand the buffer in afterwards (FILTER_PREPARED).  The
+// prepared forms are carved from `fws` - the ordinary workspace in FILTER_RAW mode, the caller's buffer in
+// the other two - in one fixed order, so all three modes agree on where each form lies.
+enum FilterMode { FILTER_RAW = 0, FILTER_PREPARE_ONLY = 1, FILTER_PREPARED = 2 };
+
+int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, void *dx, const PostOp &post, Carver &fws,
+                  Carver &ws, hipStream_t st, bool dry, FilterMode mode = FILTER_RAW)
 {
+    const bool prep = mode != FILTER_PREPARED, run = mode != FILTER_PREPARE_ONLY;
     if (dtype == MXC_BF16 && s.K % 8 == 0 && s2d_applicable(s) && igemm_bwd_data_supported(s2d_shape(s))) {
         const ConvShape s2 = s2d_shape(s);
-        void *w2 = ws.take((size_t)s2.K * s2.R * s2.S * s2.C * 2), *wt = ws.take(igemm_bwd_data_workspace(s2));
-        void *dx2 = ws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2);
+        void *w2 = fws.take((size_t)s2.K * s2.R * s2.S * s2.C * 2), *wt = fws.take(igemm_bwd_data_workspace(s2));
+        void *dx2 = run ? ws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2) : nullptr;
         if (dry) return MXC_OK;
         const char *v = "";
-        MXC_TRY(s2d_pack_w(s, w, w2, st));
-        MXC_TRY(igemm_bwd_data(s2, dy, w2, dx2, wt, st, &v));
+        if (prep) {
+            MXC_TRY(s2d_pack_w(s, w, w2, st));
+            MXC_TRY(igemm_bwd_data_prepare(s2, w2, wt, st, true));
+        }
+        if (!run) return MXC_OK;
+        MXC_TRY(igemm_bwd_data(s2, dy, wt, dx2, wt, st, &v));
         set_variant("bwd_data", (std::string("s2d+") + v).c_str());
         return s2d_unpack_dx(s, dx2, dx, st, post.mask);      // the mask is applied where dx itself is written
     }
     if (dtype == MXC_BF16 && igemm_bwd_data_smallc_supported(s)) {
         size_t w2_bytes, dx4_bytes;
         igemm_bwd_data_smallc_workspace(s, &w2_bytes, &dx4_bytes);
-        void *w2 = ws.take(w2_bytes), *dx4 = ws.take(dx4_bytes);
+        void *w2 = fws.take(w2_bytes), *dx4 = run ? ws.take(dx4_bytes) : nullptr;
         if (dry) return MXC_OK;
         const char *v = "";
-        const int rc = igemm_bwd_data_smallc(s, dy, w, dx, w2, dx4, st, &v, post);
+        if (prep) MXC_TRY(igemm_bwd_data_smallc_prepare(s, w, w2, st));
+        if (!run) return MXC_OK;
+        const int rc = igemm_bwd_data_smallc(s, dy, w2, dx, dx4, st, &v, post);
         set_variant("bwd_data", (std::string("smallc+") + v).c_str());
         return rc;
     }
     if (dtype == MXC_BF16 && igemm_bwd_data_supported(s)) {
-        void *wt = ws.take(igemm_bwd_data_workspace(s));
-        const size_t split_bytes = igemm_bwd_data_split_bytes(s);
+        void *wt = fws.take(igemm_bwd_data_workspace(s));
+        const size_t split_bytes = run ? igemm_bwd_data_split_bytes(s) : 0;
         void *split_ws = split_bytes ? ws.take(split_bytes) : nullptr;
         if (dry) return MXC_OK;
         const char *v = "";
-        const int rc = igemm_bwd_data(s, dy, w, dx, wt, st, &v, post, split_ws);
+        // a filter the kernel reads in place stays where it is unless the caller keeps a prepared copy
+        if (prep) MXC_TRY(igemm_bwd_data_prepare(s, w, wt, st, mode == FILTER_PREPARE_ONLY));
+        if (!run) return MXC_OK;
+        const int rc = igemm_bwd_data(s, dy, mode == FILTER_RAW ? w : wt, dx, wt, st, &v, post, split_ws);
         set_variant("bwd_data", v);
         return rc;
     }
+    // direct kernels read the KRSC filter itself: its prepared form is a copy
+    const size_t wbytes = (size_t)s.K * s.R * s.S * s.C * elem_size(dtype);
+    void *wc = mode != FILTER_RAW ? fws.take(wbytes) : nullptr;
     if (dry) return MXC_OK;
+    if (mode == FILTER_PREPARE_ONLY) return launch_copy(w, wc, wbytes, st);
     set_variant("bwd_data", "direct");
-    return direct_bwd_data(s, dtype, dy, w, dx, st, post);
+    return direct_bwd_data(s, dtype, dy, mode == FILTER_PREPARED ? wc : w, dx, st, post);
 }
 
 int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw, Carver &ws, hipStream_t st,
@@ -212,16 +234,18 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
 
 // ---- one driver per pass: handles the caller's layout ---------------------------
 
+// fws / mode: see FilterMode (backward-data only; fws == ws and FILTER_RAW otherwise)
 int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a, const void *b, void *out, const PostOp &post,
-             Carver &ws, hipStream_t st, bool dry)
+             Carver &ws, hipStream_t st, bool dry, Carver *fws_opt = nullptr, FilterMode mode = FILTER_RAW)
 {
+    Carver &fws = fws_opt ? *fws_opt : ws;
     const int eb = (int)elem_size(dtype);
     const size_t nx = (size_t)s.N * s.C * s.H * s.W, nw = (size_t)s.K * s.C * s.R * s.S,
                  ny = (size_t)s.N * s.K * s.P * s.Q;
     if (layout == MXC_NHWC) {
         switch (pass) {
         case MXC_FWD: return fwd_nhwc(s, dtype, a, b, out, post, ws, st, dry);
-        case MXC_BWD_DATA: return bwd_data_nhwc(s, dtype, a, b, out, post, ws, st, dry);
+        case MXC_BWD_DATA: return bwd_data_nhwc(s, dtype, a, b, out, post, fws, ws, st, dry, mode);
         default: return bwd_weight_nhwc(s, dtype, a, b, (float *)out, ws, st, dry);
         }
     }
@@ -237,21 +261,23 @@ int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a,
         return MXC_OK;
     }
     if (pass == MXC_BWD_DATA) {
-        void *dy2 = ws.take(ny * eb), *w2 = ws.take(nw * eb), *dx2 = ws.take(nx * eb);
+        const bool prep = mode != FILTER_PREPARED, run = mode != FILTER_PREPARE_ONLY;
+        void *w2 = fws.take(nw * eb);      // the KRSC filter is the first of the prepared forms
+        void *dy2 = run ? ws.take(ny * eb) : nullptr, *dx2 = run ? ws.take(nx * eb) : nullptr;
         // with_mask (not the pointer) decides the carve-out, so that the size query and the call agree
-        void *mask2 = post.mask != nullptr || post.relu ? ws.take(nx * eb) : nullptr;
+        void *mask2 = run && (post.mask != nullptr || post.relu) ? ws.take(nx * eb) : nullptr;
         PostOp post2 = post;
         post2.relu = 0;
         if (!dry) {
-            MXC_TRY(launch_transpose(a, dy2, s.N, s.K, s.P * s.Q, eb, st));
-            MXC_TRY(launch_transpose(b, w2, s.K, s.C, s.R * s.S, eb, st));
-            if (post.mask != nullptr) {
+            if (run) MXC_TRY(launch_transpose(a, dy2, s.N, s.K, s.P * s.Q, eb, st));
+            if (prep) MXC_TRY(launch_transpose(b, w2, s.K, s.C, s.R * s.S, eb, st));
+            if (run && post.mask != nullptr) {
                 MXC_TRY(launch_transpose(post.mask, mask2, s.N, s.C, s.H * s.W, eb, st));
                 post2.mask = mask2;
             }
         }
-        MXC_TRY(bwd_data_nhwc(s, dtype, dy2, w2, dx2, post2, ws, st, dry));
-        if (!dry) MXC_TRY(launch_transpose(dx2, out, s.N, s.H * s.W, s.C, eb, st));
+        MXC_TRY(bwd_data_nhwc(s, dtype, dy2, w2, dx2, post2, fws, ws, st, dry, mode));
+        if (!dry && run) MXC_TRY(launch_transpose(dx2, out, s.N, s.H * s.W, s.C, eb, st));
         return MXC_OK;
     }
     void *x2 = ws.take(nx * eb), *dy2 = ws.take(ny * eb);
@@ -396,6 +422,40 @@ int mxc_conv2d_bwd_data_relu(int N, int C, int H, int W, int K, int R, int S, in
                  hip_stream);
 }
 
+int mxc_conv2d_bwd_data_prepare_filter(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                                       const void *w, void *w_prepared, size_t prepared_bytes, void *hip_stream)
+{
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (!w || !w_prepared) return MXC_ERR_NULL;
+    if (misaligned(w) || misaligned(w_prepared)) return MXC_ERR_ALIGN;
+    Carver need(nullptr), none(nullptr);
+    MXC_TRY(run_pass(MXC_BWD_DATA, s, dtype, layout, nullptr, nullptr, nullptr, PostOp(), none, nullptr, true, &need, FILTER_PREPARE_ONLY));
+    if (prepared_bytes < need.used) return MXC_ERR_WORKSPACE;
+    Carver fws(w_prepared);
+    return run_pass(MXC_BWD_DATA, s, dtype, layout, nullptr, w, nullptr, PostOp(), none, (hipStream_t)hip_stream, false, &fws,
+                    FILTER_PREPARE_ONLY);
+}
+
+int mxc_conv2d_bwd_data_prepared(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                                 const void *dy, const void *w_prepared, size_t prepared_bytes, const void *x_mask, void *dx,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (!dy || !w_prepared || !dx) return MXC_ERR_NULL;
+    if (misaligned(dy) || misaligned(w_prepared) || misaligned(dx) || misaligned(workspace) || misaligned(x_mask)) return MXC_ERR_ALIGN;
+    PostOp post, dry_post;
+    post.mask = x_mask;
+    dry_post.relu = x_mask != nullptr ? 1 : 0;
+    Carver needf(nullptr), need(nullptr);
+    MXC_TRY(run_pass(MXC_BWD_DATA, s, dtype, layout, nullptr, nullptr, nullptr, dry_post, need, nullptr, true, &needf, FILTER_PREPARED));
+    if (prepared_bytes < needf.used) return MXC_ERR_WORKSPACE;
+    if (need.used > 0 && (!workspace || workspace_bytes < need.used)) return MXC_ERR_WORKSPACE;
+    Carver fws(const_cast<void *>(w_prepared)), ws(workspace);
+    return run_pass(MXC_BWD_DATA, s, dtype, layout, dy, nullptr, dx, post, ws, (hipStream_t)hip_stream, false, &fws, FILTER_PREPARED);
+}
+
 int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout, const void *dy, float *db, void *workspace,
                   size_t workspace_bytes, void *hip_stream)
 {
@@ -462,8 +522,7 @@ int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int 
                                int dtype, int layout, size_t *out_bytes)
 {
     if (!out_bytes) return MXC_ERR_NULL;
-    if (pass != MXC_FWD && pass != MXC_BWD_DATA && pass != MXC_BWD_WEIGHT && pass != MXC_BWD_DATA_RELU && pass != MXC_BIAS_GRAD)
-        return MXC_ERR_UNSUPPORTED;
+    if (pass < MXC_FWD || pass > MXC_BWD_DATA_PREPARED_RELU) return MXC_ERR_UNSUPPORTED;
     ConvShape s;
     const int rc = validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s);
     if (rc != MXC_OK) return rc;
@@ -471,9 +530,16 @@ int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int 
         *out_bytes = align_up((size_t)bias_grad_parts(s.N, s.K, (long long)s.P * s.Q, layout) * s.K * sizeof(float), 256);
         return MXC_OK;
     }
-    Carver need(nullptr);
+    Carver need(nullptr), needf(nullptr);
     PostOp dry_post;
-    dry_post.relu = pass == MXC_BWD_DATA_RELU;
+    dry_post.relu = pass == MXC_BWD_DATA_RELU || pass == MXC_BWD_DATA_PREPARED_RELU;
+    if (pass == MXC_BWD_DATA_FILTER || pass == MXC_BWD_DATA_PREPARED || pass == MXC_BWD_DATA_PREPARED_RELU) {
+        const FilterMode mode = pass == MXC_BWD_DATA_FILTER ? FILTER_PREPARE_ONLY : FILTER_PREPARED;
+        const int rc3 = run_pass(MXC_BWD_DATA, s, dtype, layout, nullptr, nullptr, nullptr, dry_post, need, nullptr, true, &needf, mode);
+        if (rc3 != MXC_OK) return rc3;
+        *out_bytes = pass == MXC_BWD_DATA_FILTER ? needf.used : need.used;
+        return MXC_OK;
+    }
     const int rc2 = run_pass(pass == MXC_BWD_DATA_RELU ? MXC_BWD_DATA : pass, s, dtype, layout, nullptr, nullptr, nullptr, dry_post,
                              need, nullptr, true);
     if (rc2 != MXC_OK) return rc2;

@@ -923,24 +923,34 @@ bool igemm_bwd_data_supported(const ConvShape &s)
 
 size_t igemm_bwd_data_workspace(const ConvShape &s) { return (size_t)s.K * s.R * s.S * s.C * sizeof(bf16_t); }
 
-int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
+// A large 1x1 filter at stride 1 (FullyConnected) is read in place, as transposed tiles, when the chosen
+// tile has that variant: copying it would cost more than the slower operand fetch.
+static bool bwd_data_reads_filter_in_place(const ConvShape &s)
+{
+    return s.R == 1 && s.S == 1 && s.stride == 1 && s.K % 64 == 0 && (long long)s.K * s.C * 2 >= (4ll << 20) &&
+           has_bt(choose_tile((long long)s.N * s.H * s.W, s.C, s.K));
+}
+
+int igemm_bwd_data_prepare(const ConvShape &s, const void *w, void *wt, hipStream_t st, bool copy_in_place_filter)
+{
+    if (bwd_data_reads_filter_in_place(s))
+        return copy_in_place_filter ? launch_copy(w, wt, (size_t)s.K * s.C * sizeof(bf16_t), st) : MXC_OK;
+    if (s.R == 1 && s.S == 1)
+        // 1x1: the single class's matrix [C][K] is the transpose of w[K][C] (tiled transpose through LDS)
+        return launch_transpose(w, wt, 1, s.K, s.C, 2, st);
+    const int total = s.K * s.R * s.S * s.C;
+    hipLaunchKernelGGL(repack_bwd_data_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const bf16_t *)w, (bf16_t *)wt, s.K, s.C, s.R, s.S, s.stride);
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
+// wt: the filter as igemm_bwd_data_prepare left it; w_in_place: the filter the in-place variant reads
+// (the caller's KRSC filter, or its copy in wt)
+int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w_in_place, void *dx, const void *wt, hipStream_t st,
                    const char **variant, const PostOp &post, void *split_ws)
 {
-    // A large 1x1 filter at stride 1 (FullyConnected) is read in place, as transposed tiles, when the chosen
-    // tile has that variant: copying it would cost more than the slower operand fetch.
-    const bool bt = s.R == 1 && s.S == 1 && s.stride == 1 && s.K % 64 == 0 && (long long)s.K * s.C * 2 >= (4ll << 20) &&
-                    has_bt(choose_tile((long long)s.N * s.H * s.W, s.C, s.K));
-    if (bt) {
-    } else if (s.R == 1 && s.S == 1) {
-        // 1x1: the single class's matrix [C][K] is the transpose of w[K][C] (tiled transpose through LDS)
-        const int rc = launch_transpose(w, wt, 1, s.K, s.C, 2, st);
-        if (rc != MXC_OK) return rc;
-    } else {
-        const int total = s.K * s.R * s.S * s.C;
-        hipLaunchKernelGGL(repack_bwd_data_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                           (const bf16_t *)w, (bf16_t *)wt, s.K, s.C, s.R, s.S, s.stride);
-        if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
-    }
+    const bool bt = bwd_data_reads_filter_in_place(s);
+    const void *w = w_in_place;
     size_t wt_off = 0;
     Plan pl{0, -1, 0};
     for (int ph = 0; ph < s.stride; ++ph) {
@@ -1079,8 +1089,7 @@ void igemm_bwd_data_smallc_workspace(const ConvShape &s, size_t *w2_bytes, size_
     *dx4_bytes = (size_t)s.N * s.H * g.Wg * g.G * 4 * 2;
 }
 
-int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, void *dx, void *w2, void *dx4, hipStream_t st,
-                          const char **variant, const PostOp &post)
+int igemm_bwd_data_smallc_prepare(const ConvShape &s, const void *w, void *w2, hipStream_t st)
 {
     const SmallCBwd g = smallc_bwd_geom(s);
     size_t w2_bytes, dx4_bytes;
@@ -1088,7 +1097,14 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, voi
     const int total = (int)(w2_bytes / 2);
     hipLaunchKernelGGL(smallc_bwd_pack_w_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t *)w,
                        (bf16_t *)w2, s.K, s.C, s.R, s.S, s.stride, s.pad, g.G, g.U, g.uoff);
-    if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
+// w2: the filter as igemm_bwd_data_smallc_prepare packed it
+int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w2, void *dx, void *dx4, hipStream_t st,
+                          const char **variant, const PostOp &post)
+{
+    const SmallCBwd g = smallc_bwd_geom(s);
     size_t w2_off = 0;
     Plan pl{0, -1, 0};
     for (int ph = 0; ph < s.stride; ++ph) {

@@ -124,13 +124,17 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
 bool igemm_bwd_data_supported(const ConvShape &s);
 size_t igemm_bwd_data_workspace(const ConvShape &s);   // bytes for the re-packed filter
 size_t igemm_bwd_data_split_bytes(const ConvShape &s);   // scratch for a split reduction (0: never split)
-int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w, void *dx, void *wt, hipStream_t st,
+// Filter preparation (re-pack per stride residue class / transpose of a 1x1 filter) into wt; a filter that the
+// kernel reads in place is copied to wt only when copy_in_place_filter is set.
+int igemm_bwd_data_prepare(const ConvShape &s, const void *w, void *wt, hipStream_t st, bool copy_in_place_filter);
+int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w_in_place, void *dx, const void *wt, hipStream_t st,
                    const char **variant, const PostOp &post = PostOp(), void *split_ws = nullptr);
 
 // backward-data for C <= 4: G output columns form one GEMM row (see igemm.hip)
 bool igemm_bwd_data_smallc_supported(const ConvShape &s);
 void igemm_bwd_data_smallc_workspace(const ConvShape &s, size_t *w2_bytes, size_t *dx4_bytes);
-int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w, void *dx, void *w2, void *dx4, hipStream_t st,
+int igemm_bwd_data_smallc_prepare(const ConvShape &s, const void *w, void *w2, hipStream_t st);
+int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w2, void *dx, void *dx4, hipStream_t st,
                           const char **variant, const PostOp &post = PostOp());
 
 // ---- prep.hip: re-packing for channel counts that are not a multiple of 8 ---------

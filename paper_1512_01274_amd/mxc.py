@@ -16,6 +16,7 @@ MXC_ERR_NULL, MXC_ERR_SHAPE, MXC_ERR_UNSUPPORTED, MXC_ERR_WORKSPACE, MXC_ERR_ALI
 MXC_F32, MXC_BF16 = 0, 1
 MXC_NCHW, MXC_NHWC = 0, 1
 MXC_FWD, MXC_BWD_DATA, MXC_BWD_WEIGHT, MXC_BWD_DATA_RELU, MXC_BIAS_GRAD = 0, 1, 2, 3, 4
+MXC_BWD_DATA_FILTER, MXC_BWD_DATA_PREPARED, MXC_BWD_DATA_PREPARED_RELU = 5, 6, 7
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmxc.so")
 if not os.path.exists(LIB_PATH):
@@ -29,6 +30,10 @@ for _name in ("mxc_conv2d_fwd", "mxc_conv2d_bwd_data", "mxc_conv2d_bwd_weight"):
     _f.restype = _I
 _lib.mxc_conv2d_bwd_weight_static.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP]
 _lib.mxc_conv2d_bwd_weight_static.restype = _I
+_lib.mxc_conv2d_bwd_data_prepare_filter.argtypes = [_I] * 11 + [_VP, _VP, _SZ, _VP]
+_lib.mxc_conv2d_bwd_data_prepare_filter.restype = _I
+_lib.mxc_conv2d_bwd_data_prepared.argtypes = [_I] * 11 + [_VP, _VP, _SZ, _VP, _VP, _VP, _SZ, _VP]
+_lib.mxc_conv2d_bwd_data_prepared.restype = _I
 _lib.mxc_conv2d_workspace_bytes.argtypes = [_I] * 12 + [ctypes.POINTER(_SZ)]
 _lib.mxc_conv2d_workspace_bytes.restype = _I
 _lib.mxc_layout_convert.argtypes = [_I] * 7 + [_VP, _VP, _VP]
@@ -155,6 +160,23 @@ def mxc_conv2d_bwd_data_relu(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy
     ws_ptr, ws_bytes = _ws(workspace)
     rc = _lib.mxc_conv2d_bwd_data_relu(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(dy), _ptr(w), _ptr(x), _ptr(dx),
                                        ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_conv2d_bwd_data_prepare_filter(N, C, H, W, K, R, S, stride, pad, dtype, layout, w, w_prepared, stream=None):
+    rc = _lib.mxc_conv2d_bwd_data_prepare_filter(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(w), _ptr(w_prepared),
+                                                 w_prepared.numel() * w_prepared.element_size(), _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_conv2d_bwd_data_prepared(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w_prepared, x_mask, dx, workspace=None,
+                                 stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_conv2d_bwd_data_prepared(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(dy), _ptr(w_prepared),
+                                           w_prepared.numel() * w_prepared.element_size(), _ptr(x_mask), _ptr(dx), ws_ptr, ws_bytes,
+                                           _stream(stream))
     if rc != MXC_OK:
         raise MxcError(rc)
 

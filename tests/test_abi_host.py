@@ -97,7 +97,8 @@ def test_workspace_query_over_random_shapes(mxc):
     grouped backward-data never needs less than the plain one."""
     import numpy as np
     rng = np.random.Generator(np.random.Philox(key=7))
-    passes = (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT, mxc.MXC_BWD_DATA_RELU, mxc.MXC_BIAS_GRAD)
+    passes = (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT, mxc.MXC_BWD_DATA_RELU, mxc.MXC_BIAS_GRAD,
+              mxc.MXC_BWD_DATA_FILTER, mxc.MXC_BWD_DATA_PREPARED, mxc.MXC_BWD_DATA_PREPARED_RELU)
     for _ in range(300):
         C = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 24, 64, 96, 192, 512]))
         K = int(rng.choice([1, 7, 8, 16, 40, 64, 96, 256, 520]))
@@ -115,6 +116,12 @@ def test_workspace_query_over_random_shapes(mxc):
                 assert all(v % 256 == 0 and v < 2 ** 40 for v in sizes.values()), (dims, sizes)
                 assert sizes[mxc.MXC_BWD_DATA_RELU] >= sizes[mxc.MXC_BWD_DATA], dims
                 assert sizes[mxc.MXC_BIAS_GRAD] > 0
+                # a prepared filter always has a size; with it, the call needs no more scratch than without
+                assert sizes[mxc.MXC_BWD_DATA_FILTER] > 0, dims
+                assert sizes[mxc.MXC_BWD_DATA_PREPARED] <= sizes[mxc.MXC_BWD_DATA], dims
+                assert sizes[mxc.MXC_BWD_DATA_PREPARED_RELU] <= sizes[mxc.MXC_BWD_DATA_RELU], dims
+                if dt == mxc.MXC_BF16:       # every bf16 path carves its filter forms out of the workspace
+                    assert sizes[mxc.MXC_BWD_DATA_PREPARED] + sizes[mxc.MXC_BWD_DATA_FILTER] >= sizes[mxc.MXC_BWD_DATA], dims
 
 
 def test_grouped_entry_points_validate_on_the_host(mxc):
@@ -126,6 +133,11 @@ def test_grouped_entry_points_validate_on_the_host(mxc):
     assert lib.mxc_conv2d_fwd_bias_act(*GOOD, 0, 0, 4096, 8192, 4098, 1, 16384, 32768, big, None) == mxc.MXC_ERR_ALIGN
     # missing mask
     assert lib.mxc_conv2d_bwd_data_relu(*GOOD, 0, 0, 4096, 8192, None, 16384, 32768, big, None) == mxc.MXC_ERR_NULL
+    # prepared filter: null buffer, buffer too small
+    assert lib.mxc_conv2d_bwd_data_prepare_filter(*GOOD, 0, 0, 4096, None, big, None) == mxc.MXC_ERR_NULL
+    assert lib.mxc_conv2d_bwd_data_prepare_filter(*GOOD, 0, 0, 4096, 8192, 16, None) == mxc.MXC_ERR_WORKSPACE
+    assert lib.mxc_conv2d_bwd_data_prepared(*GOOD, 0, 0, 4096, 8192, 16, None, 16384, 32768, big, None) == mxc.MXC_ERR_WORKSPACE
+    assert lib.mxc_conv2d_bwd_data_prepared(*GOOD, 0, 0, 4096, None, big, None, 16384, 32768, big, None) == mxc.MXC_ERR_NULL
     # bias gradient: shape, null, workspace
     assert lib.mxc_bias_grad(0, 8, 4, 4, 0, 1, 4096, 8192, 16384, big, None) == mxc.MXC_ERR_SHAPE
     assert lib.mxc_bias_grad(2, 8, 4, 4, 0, 1, None, 8192, 16384, big, None) == mxc.MXC_ERR_NULL

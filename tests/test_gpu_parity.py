@@ -290,6 +290,47 @@ def test_grouped_operations(mxc, oracle, dims, dtype, layout):
     assert torch.equal(db.view(torch.int32), db2.view(torch.int32))
 
 
+PREPARED_SHAPES = [
+    (2, 32, 14, 14, 64, 3, 3, 1, 1),       # re-packed filter, one residue class
+    (2, 24, 9, 9, 40, 1, 1, 2, 0),         # 1x1 stride 2: transposed filter, classes no tap reaches
+    (3, 16, 13, 11, 24, 3, 3, 2, 1),       # four residue classes
+    (1, 3, 35, 35, 8, 11, 11, 4, 2),       # space-to-depth first layer
+    (1, 3, 20, 18, 16, 3, 3, 1, 1),        # small-C column groups
+    (2, 5, 13, 13, 7, 5, 5, 1, 2),         # K % 8 != 0: direct kernel, prepared form is a copy
+    (16, 2048, 1, 1, 1024, 1, 1, 1, 0),    # FullyConnected: large 1x1 filter read in place
+]
+
+
+@pytest.mark.parametrize("dtype,layout", [("bf16", "nhwc"), ("bf16", "nchw"), ("f32", "nhwc")])
+@pytest.mark.parametrize("dims", PREPARED_SHAPES)
+def test_prepared_filter_backward_data(mxc, oracle, dims, dtype, layout):
+    """Backward-data from a filter prepared ahead of time: bit-identical to the ordinary entry points (with and
+    without the ReLU mask), on repeated use of one prepared buffer, and within the parity bound of the oracle."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy, _ = _fused_case(dims, dtype, (hash(dims) & 0xFFFF) + 5)
+    run = util.Runner(mxc, dims, dtype, layout)
+    d_dy, d_w, d_x = run._in(dy), run._in(w), run._in(x)
+    prepared = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_BWD_DATA_FILTER, *dims, run.dt, run.lay))
+    mxc.mxc_conv2d_bwd_data_prepare_filter(*dims, run.dt, run.lay, d_w, prepared)
+    as_bits = lambda t: t.view(torch.int16 if dtype == "bf16" else torch.int32)
+    for mask, op_plain, op_prep in ((None, mxc.MXC_BWD_DATA, mxc.MXC_BWD_DATA_PREPARED),
+                                    (d_x, mxc.MXC_BWD_DATA_RELU, mxc.MXC_BWD_DATA_PREPARED_RELU)):
+        want = torch.full((N * C * H * W,), float("nan"), dtype=run.tdtype, device="cuda")
+        if mask is None:
+            mxc.mxc_conv2d_bwd_data(*dims, run.dt, run.lay, d_dy, d_w, want, run._ws(op_plain))
+        else:
+            mxc.mxc_conv2d_bwd_data_relu(*dims, run.dt, run.lay, d_dy, d_w, mask, want, run._ws(op_plain))
+        for _ in range(2):
+            got = torch.full_like(want, float("nan"))
+            mxc.mxc_conv2d_bwd_data_prepared(*dims, run.dt, run.lay, d_dy, prepared, mask, got, run._ws(op_prep))
+            torch.cuda.synchronize()
+            assert torch.equal(as_bits(got), as_bits(want)), (dims, dtype, layout, mask is not None, mxc.mxc_last_variant())
+    ref, den = oracle.conv2d_bwd_data_relu(dy, w, x, st, pad)
+    a = run._out(got, (N, C, H, W))
+    assert util.metric(a, ref, den) <= util.TOL[dtype], (dims, mxc.mxc_last_variant())
+    assert np.all(np.abs(a - ref) <= util.tight_bound(ref, den, dtype, dtype == "bf16")), dims
+
+
 @pytest.mark.parametrize("cfg_idx", [1, 3])
 def test_grouped_operations_network_layers(mxc, oracle, cfg_idx):
     """The bench's launch configuration (bf16, NHWC) on every layer of the AlexNet- and VGG-style stacks, batch 2."""
