@@ -417,8 +417,8 @@ def cpu_baseline(gen, cfg, sample_batch):
 
 
 def layout_entry(torch, mxc):
-    """a1 on a tensor of at least 64 MiB: NCHW -> NHWC and back, bf16, GB/s of read + written bytes."""
-    n, c, h, w = 64, 256, 56, 56                     # 98 MiB
+    """a1 on a tensor beyond the 256 MiB memory-side cache: NCHW -> NHWC and back, bf16, GB/s of read + written bytes."""
+    n, c, h, w = 64, 256, 112, 112                   # 392 MiB each side
     src = torch.randn(n * c * h * w, dtype=torch.float32, device="cuda").to(torch.bfloat16)
     dst = torch.empty_like(src)
     res = {}

@@ -64,7 +64,8 @@ enum { MXC_FWD = 0, MXC_BWD_DATA = 1, MXC_BWD_WEIGHT = 2,
        MXC_BWD_DATA_RELU = 3, MXC_BIAS_GRAD = 4,
        MXC_BWD_DATA_FILTER = 5,          /* bytes of the prepared filter of mxc_conv2d_bwd_data_prepare_filter */
        MXC_BWD_DATA_PREPARED = 6,        /* workspace of mxc_conv2d_bwd_data_prepared without x_mask           */
-       MXC_BWD_DATA_PREPARED_RELU = 7 }; /* ... with x_mask                                                     */
+       MXC_BWD_DATA_PREPARED_RELU = 7,   /* ... with x_mask                                                     */
+       MXC_BWD_WEIGHT_BF16 = 8 };        /* workspace of mxc_conv2d_bwd_weight_bf16                             */
 
 /*
  * Forward (the layer's "forward" evaluation, paper Section 2.1):
@@ -102,6 +103,19 @@ int mxc_conv2d_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int s
                           int dtype, int layout,
                           const void *x, const void *dy, void *dw,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward w.r.t. the filter with the gradient delivered in bf16: the same sums as mxc_conv2d_bwd_weight
+ * (fp32 accumulation, fp32 split partial sums added in a fixed order), rounded ONCE to bf16 (nearest even) by
+ * the kernel that forms the final sum - for a gradient exchange or an optimizer that takes bf16 (half the bytes
+ * of the push of paper Section 2.3).  dtype must be MXC_BF16 (else MXC_ERR_UNSUPPORTED); dw: K*C*R*S bf16
+ * values in the filter order of `layout`.  Workspace: query MXC_BWD_WEIGHT_BF16.  Otherwise as
+ * mxc_conv2d_bwd_weight.
+ */
+int mxc_conv2d_bwd_weight_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               int dtype, int layout,
+                               const void *x, const void *dy, void *dw,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * mxc_conv2d_bwd_weight for callers that cannot allocate device memory or hand over a workspace
@@ -257,6 +271,13 @@ const char *mxc_last_variant(void);
 
 /* Library version as major*10000 + minor*100 + patch. */
 int mxc_version(void);
+
+/* Tuning aid: name of the index-th tile shape the matrix-core kernels are built in (family 0: forward /
+ * backward-data implicit GEMM, family 1: backward-weight), NULL past the last.  These are the names that
+ * mxc_last_variant() reports and that the tuning hooks MXC_FORCE_VARIANT=<name>[+<name of the shape for the
+ * rows the last whole round leaves>] and MXC_FORCE_WGRAD=<name>[/<splits>] (environment, read per call) accept;
+ * the tuning script and the tests walk the list.  Static host memory. */
+const char *mxc_tile_name(int family, int index);
 
 /* Measurement aid (not part of the convolution path): enqueues one launch of a
  * register-resident loop of bf16 matrix instructions (v_mfma_f32_32x32x16_bf16, fp32

@@ -48,6 +48,14 @@ int validate_shape(int N, int C, int H, int W, int K, int R, int S, int stride, 
     if ((long double)N * C * H * W >= lim || (long double)N * K * s.P * s.Q >= lim ||
         (long double)K * C * R * S >= 2147483648.0L)
         return MXC_ERR_SHAPE;
+    // NCHW operands are converted by batched transposes whose row and column counts are ints and whose grids
+    // are bounded: refuse here, before anything is launched, what they could not run
+    if (layout == MXC_NCHW) {
+        const long long HW = (long long)H * W, PQ = (long long)s.P * s.Q, RS = (long long)R * S;
+        if (!transpose_launchable(N, C, HW) || !transpose_launchable(N, HW, C) || !transpose_launchable(N, K, PQ) ||
+            !transpose_launchable(N, PQ, K) || !transpose_launchable(K, C, RS) || !transpose_launchable(K, RS, C))
+            return MXC_ERR_SHAPE;
+    }
     *out = s;
     return MXC_OK;
 }
@@ -181,15 +189,15 @@ int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, 
     return direct_bwd_data(s, dtype, dy, mode == FILTER_PREPARED ? wc : w, dx, st, post);
 }
 
-int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw, Carver &ws, hipStream_t st,
-                    bool dry)
+int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy, void *dw, bool dw_bf16, Carver &ws,
+                    hipStream_t st, bool dry)
 {
     const char *v = "";
     if (dtype == MXC_BF16 && s.C % 8 == 0 && wgrad_supported(wgrad_geom_plain(s))) {
         const WgradGeom g = wgrad_geom_plain(s);
         float *partial = (float *)ws.take(wgrad_workspace(g));
         if (dry) return MXC_OK;
-        const int rc = wgrad(g, x, dy, dw, partial, st, &v);
+        const int rc = wgrad(g, x, dy, dw, dw_bf16, partial, st, &v);
         set_variant("bwd_weight", v);
         return rc;
     }
@@ -200,7 +208,7 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
         float *partial = (float *)ws.take(wgrad_workspace(g));
         if (dry) return MXC_OK;
         MXC_TRY(s2d_pack_x(s, x, x2, st));
-        const int rc = wgrad(g, x2, dy, dw, partial, st, &v);
+        const int rc = wgrad(g, x2, dy, dw, dw_bf16, partial, st, &v);
         set_variant("bwd_weight", (std::string("s2d+") + v).c_str());
         return rc;
     }
@@ -211,7 +219,7 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
         float *partial = (float *)ws.take(wgrad_workspace(g));
         if (dry) return MXC_OK;
         MXC_TRY(smallc_pack_x(s, x, xp, st));
-        const int rc = wgrad(g, xp, dy, dw, partial, st, &v);
+        const int rc = wgrad(g, xp, dy, dw, dw_bf16, partial, st, &v);
         set_variant("bwd_weight", (std::string("smallc+") + v).c_str());
         return rc;
     }
@@ -221,7 +229,7 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
         float *partial = (float *)ws.take(wgrad_workspace(g));
         if (dry) return MXC_OK;
         MXC_TRY(pad_channels(x, xp, (long long)s.N * s.H * s.W, s.C, st));
-        const int rc = wgrad(g, xp, dy, dw, partial, st, &v);
+        const int rc = wgrad(g, xp, dy, dw, dw_bf16, partial, st, &v);
         set_variant("bwd_weight", (std::string("chanpad+") + v).c_str());
         return rc;
     }
@@ -229,7 +237,7 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
     float *partial = (float *)ws.take((size_t)splits * s.K * s.R * s.S * s.C * sizeof(float));
     if (dry) return MXC_OK;
     set_variant("bwd_weight", "direct_splitk");
-    return direct_bwd_weight(s, dtype, x, dy, dw, partial, splits, st);
+    return direct_bwd_weight(s, dtype, x, dy, dw, dw_bf16, partial, splits, st);
 }
 
 // ---- one driver per pass: handles the caller's layout ---------------------------
@@ -246,7 +254,7 @@ int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a,
         switch (pass) {
         case MXC_FWD: return fwd_nhwc(s, dtype, a, b, out, post, ws, st, dry);
         case MXC_BWD_DATA: return bwd_data_nhwc(s, dtype, a, b, out, post, fws, ws, st, dry, mode);
-        default: return bwd_weight_nhwc(s, dtype, a, b, (float *)out, ws, st, dry);
+        default: return bwd_weight_nhwc(s, dtype, a, b, out, pass == MXC_BWD_WEIGHT_BF16, ws, st, dry);
         }
     }
     // NCHW at the boundary: convert operands into the workspace, compute, convert the result back.
@@ -280,14 +288,16 @@ int run_pass(int pass, const ConvShape &s, int dtype, int layout, const void *a,
         if (!dry && run) MXC_TRY(launch_transpose(dx2, out, s.N, s.H * s.W, s.C, eb, st));
         return MXC_OK;
     }
+    const bool dw_bf16 = pass == MXC_BWD_WEIGHT_BF16;
+    const int dwb = dw_bf16 ? 2 : 4;
     void *x2 = ws.take(nx * eb), *dy2 = ws.take(ny * eb);
-    float *dw2 = (float *)ws.take(nw * sizeof(float));
+    void *dw2 = ws.take(nw * dwb);
     if (!dry) {
         MXC_TRY(launch_transpose(a, x2, s.N, s.C, s.H * s.W, eb, st));
         MXC_TRY(launch_transpose(b, dy2, s.N, s.K, s.P * s.Q, eb, st));
     }
-    MXC_TRY(bwd_weight_nhwc(s, dtype, x2, dy2, dw2, ws, st, dry));
-    if (!dry) MXC_TRY(launch_transpose(dw2, out, s.K, s.R * s.S, s.C, 4, st));
+    MXC_TRY(bwd_weight_nhwc(s, dtype, x2, dy2, dw2, dw_bf16, ws, st, dry));
+    if (!dry) MXC_TRY(launch_transpose(dw2, out, s.K, s.R * s.S, s.C, dwb, st));
     return MXC_OK;
 }
 
@@ -369,6 +379,15 @@ int mxc_conv2d_bwd_weight(int N, int C, int H, int W, int K, int R, int S, int s
                           void *hip_stream)
 {
     return entry(MXC_BWD_WEIGHT, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, PostOp(), workspace,
+                 workspace_bytes, hip_stream);
+}
+
+int mxc_conv2d_bwd_weight_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                               const void *x, const void *dy, void *dw, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    if (dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
+    return entry(MXC_BWD_WEIGHT_BF16, N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, PostOp(), workspace,
                  workspace_bytes, hip_stream);
 }
 
@@ -522,7 +541,8 @@ int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int 
                                int dtype, int layout, size_t *out_bytes)
 {
     if (!out_bytes) return MXC_ERR_NULL;
-    if (pass < MXC_FWD || pass > MXC_BWD_DATA_PREPARED_RELU) return MXC_ERR_UNSUPPORTED;
+    if (pass < MXC_FWD || pass > MXC_BWD_WEIGHT_BF16) return MXC_ERR_UNSUPPORTED;
+    if (pass == MXC_BWD_WEIGHT_BF16 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
     ConvShape s;
     const int rc = validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s);
     if (rc != MXC_OK) return rc;
@@ -551,7 +571,9 @@ int mxc_layout_convert(int n, int c, int h, int w, int dtype, int src_layout, in
                        void *dst, void *hip_stream)
 {
     if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return MXC_ERR_SHAPE;
-    if ((long double)n * c * h * w >= 1099511627776.0L || (long long)h * w > 0x7FFFFFFFll) return MXC_ERR_SHAPE;
+    if ((long double)n * c * h * w >= 1099511627776.0L || !transpose_launchable(n, c, (long long)h * w) ||
+        !transpose_launchable(n, (long long)h * w, c))
+        return MXC_ERR_SHAPE;
     if (dtype != MXC_F32 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
     if ((src_layout != MXC_NCHW && src_layout != MXC_NHWC) || (dst_layout != MXC_NCHW && dst_layout != MXC_NHWC))
         return MXC_ERR_UNSUPPORTED;
@@ -580,7 +602,12 @@ const char *mxc_status_string(int status)
 
 const char *mxc_last_variant(void) { return g_variant; }
 
-int mxc_version(void) { return 100; }
+int mxc_version(void) { return 200; }
+
+const char *mxc_tile_name(int family, int index)
+{
+    return family == 0 ? igemm_tile_name(index) : family == 1 ? wgrad_tile_name(index) : nullptr;
+}
 
 int mxc_probe_mfma(int workgroups, int iters, void *out, size_t out_bytes, double *flops, void *hip_stream)
 {

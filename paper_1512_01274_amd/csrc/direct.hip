@@ -102,15 +102,16 @@ __global__ __launch_bounds__(256) void direct_bwd_weight_kernel(ConvShape s, con
     partial[(size_t)blockIdx.y * wtotal + gid] = acc;
 }
 
-// dw[i] = partial[0][i] + partial[1][i] + ... in that order
-__global__ __launch_bounds__(256) void sum_splits_kernel(const float *__restrict__ partial, float *__restrict__ dw,
+// dw[i] = partial[0][i] + partial[1][i] + ... in that order (OUT = bf16_t: the fp32 sum rounded once)
+template <typename OUT>
+__global__ __launch_bounds__(256) void sum_splits_kernel(const float *__restrict__ partial, OUT *__restrict__ dw,
                                                          int wtotal, int splits)
 {
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= wtotal) return;
     float acc = 0.f;
     for (int i = 0; i < splits; ++i) acc += partial[(size_t)i * wtotal + gid];
-    dw[gid] = acc;
+    store_f32(dw + gid, acc);
 }
 
 inline int ok() { return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH; }
@@ -158,7 +159,7 @@ int direct_bwd_weight_splits(const ConvShape &s)
     return (int)splits;
 }
 
-int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw, float *partial,
+int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *dy, void *dw, bool dw_bf16, float *partial,
                       int splits, hipStream_t st)
 {
     const long long wtotal_ll = (long long)s.K * s.R * s.S * s.C;
@@ -175,8 +176,12 @@ int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *
         hipLaunchKernelGGL(direct_bwd_weight_kernel<float>, grid, block, 0, st, s, (const float *)x, (const float *)dy,
                            partial, (int)pps);
     if (ok() != MXC_OK) return MXC_ERR_LAUNCH;
-    hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((wtotal + 255) / 256)), block, 0, st, partial, dw, wtotal,
-                       splits);
+    if (dw_bf16)
+        hipLaunchKernelGGL(sum_splits_kernel<bf16_t>, dim3((unsigned)((wtotal + 255) / 256)), block, 0, st, partial, (bf16_t *)dw,
+                           wtotal, splits);
+    else
+        hipLaunchKernelGGL(sum_splits_kernel<float>, dim3((unsigned)((wtotal + 255) / 256)), block, 0, st, partial, (float *)dw,
+                           wtotal, splits);
     return ok();
 }
 

@@ -847,6 +847,8 @@ int launch_split(int tc, IgemmParams p, long long M, int sp, void *split_ws, voi
 
 }  // namespace
 
+const char *igemm_tile_name(int index) { return index >= 0 && index < N_TILE_CHOICES ? kTiles[index].name : nullptr; }
+
 size_t igemm_bwd_data_split_bytes(const ConvShape &s)
 {
     if (s.stride != 1 || s.C % 8 != 0) return 0;       // one residue class, output numbered like the GEMM rows

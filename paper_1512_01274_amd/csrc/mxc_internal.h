@@ -89,6 +89,8 @@ static inline size_t elem_size(int dtype) { return dtype == MXC_BF16 ? 2 : 4; }
 // Batched 2-D transpose: src[b][rows][cols] -> dst[b][cols][rows], element size 2 or 4 bytes.
 int launch_transpose(const void *src, void *dst, int batch, int rows, int cols, int elem_bytes,
                      hipStream_t stream);
+// whether launch_transpose can run this problem (its grid holds batch x ceil(rows/64) x ceil(cols/64) workgroups)
+bool transpose_launchable(long long batch, long long rows, long long cols);
 int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
 
 // ---- probe.hip: matrix-pipe ceiling measurement -------------------------------------
@@ -112,7 +114,8 @@ int direct_bwd_data(const ConvShape &s, int dtype, const void *dy, const void *w
                     const PostOp &post = PostOp());
 // partial: fp32 scratch of direct_bwd_weight_splits(s) * K*R*S*C floats
 int direct_bwd_weight_splits(const ConvShape &s);
-int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *dy, float *dw,
+// dw: fp32, or bf16 (the fp32 sum rounded once) when dw_bf16
+int direct_bwd_weight(const ConvShape &s, int dtype, const void *x, const void *dy, void *dw, bool dw_bf16,
                       float *partial, int splits, hipStream_t st);
 
 // ---- igemm.hip: bf16 MFMA implicit GEMM (NHWC/KRSC) ---------------------------
@@ -136,6 +139,10 @@ void igemm_bwd_data_smallc_workspace(const ConvShape &s, size_t *w2_bytes, size_
 int igemm_bwd_data_smallc_prepare(const ConvShape &s, const void *w, void *w2, hipStream_t st);
 int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w2, void *dx, void *dx4, hipStream_t st,
                           const char **variant, const PostOp &post = PostOp());
+
+// names of the tile shapes the two MFMA kernel families are built in (nullptr past the last)
+const char *igemm_tile_name(int index);
+const char *wgrad_tile_name(int index);
 
 // ---- prep.hip: re-packing for channel counts that are not a multiple of 8 ---------
 // [rows][C] -> [rows][C8] (C8 = C rounded up to 8, new channels zero); bf16 only.
@@ -173,7 +180,8 @@ WgradGeom wgrad_geom_chanpad(const ConvShape &s);   // x already padded to C8 ch
 WgradGeom wgrad_geom_smallc(const ConvShape &s);    // x already packed by smallc_pack_x
 bool wgrad_supported(const WgradGeom &g);
 size_t wgrad_workspace(const WgradGeom &g);            // bytes of fp32 partial tiles
-int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *partial, hipStream_t st,
+// dw: fp32, or bf16 (the fp32 sum rounded once, by the reduce kernel) when dw_bf16
+int wgrad(const WgradGeom &g, const void *x, const void *dy, void *dw, bool dw_bf16, float *partial, hipStream_t st,
           const char **variant);
 
 }  // namespace mxc

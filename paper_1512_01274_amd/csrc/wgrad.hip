@@ -13,8 +13,9 @@
 // ahead; address generation and operand fetches are interleaved between the MFMAs.
 //
 // Split reduction: workgroup (tile, z) reduces pixels [z*span, (z+1)*span) into an fp32 partial
-// tile; a second kernel adds the partials of every element in ascending z (fixed order, so results
-// are bit-identical from run to run; no float atomics).
+// tile; a second kernel adds the partials of every element in a fixed order (lane groups of a wave take
+// interleaved splits and exchange their sums with wave-level shuffles), so results are bit-identical from
+// run to run; no float atomics.
 #include <stdlib.h>
 #include <string.h>
 
@@ -326,66 +327,72 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * BP * (BMT + BNT
     }
 }
 
-// dw[k][r][s][c] = sum over splits (ascending order) of partial[z][k][col], col = (r/d)*col_r + (s/d)*col_s +
-// ((r%d)*d + s%d)*Cq + c with d = s2d (1 for everything but space-to-depth operands, where it is the stride).
-// For plain NHWC operands (col_r = S*C, col_s = C) source and destination indices coincide; the
-// re-packed operands of odd channel counts have wider columns that are dropped here.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ partial, float *__restrict__ dw,
+// ---- split reduction: dw = sum over splits of the fp32 partial tensors -----------------------------------
+// A wave is divided into G groups of 64/G lanes.  The lanes of a group own consecutive outputs (so a group's
+// load of one split is one contiguous run); group g adds the splits g, g+G, g+2G, ... in ascending order, and
+// the G group sums are then added across the wave with a butterfly of lane exchanges (__shfl_xor over
+// 64/G, ..., 32 lanes: DPP / permute instructions, no memory).  The order of additions depends only on G and
+// the split count, so results are bit-identical from run to run.  G = 4 for ordinary split counts, 16 when
+// many splits meet a small dw (more loads in flight per output).
+__device__ __forceinline__ float4 shfl_xor4(const float4 v, int lanes)
+{
+    return make_float4(__shfl_xor(v.x, lanes), __shfl_xor(v.y, lanes), __shfl_xor(v.z, lanes), __shfl_xor(v.w, lanes));
+}
+
+// Plain NHWC operands (source index == destination index), four outputs per lane with 16-byte loads.
+// OUT = float: dw in fp32; OUT = bf16_t: the fp32 sum rounded once (nearest even) to bf16
+__device__ __forceinline__ void store4(float *dw, int i4, const float4 v) { reinterpret_cast<float4 *>(dw)[i4] = v; }
+__device__ __forceinline__ void store4(bf16_t *dw, int i4, const float4 v)
+{
+    reinterpret_cast<uint2 *>(dw)[i4] = make_uint2((uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16),
+                                                   (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16));
+}
+
+template <int G, typename OUT>
+__global__ __launch_bounds__(256) void wgrad_reduce_vec4_kernel(const float4 *__restrict__ partial, OUT *__restrict__ dw,
+                                                                int total4, int splits)
+{
+    constexpr int LPG = 64 / G;                       // lanes per group
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane / LPG;
+    const int gid = (blockIdx.x * 4 + wave) * LPG + lane % LPG;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (gid < total4)
+        for (int zz = grp; zz < splits; zz += G) {
+            const float4 v = partial[(size_t)zz * total4 + gid];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+#pragma unroll
+    for (int d = LPG; d < 64; d <<= 1) {
+        const float4 o = shfl_xor4(acc, d);
+        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+    }
+    if (grp == 0 && gid < total4) store4(dw, gid, acc);
+}
+
+// General form: dw[k][r][s][c] is read back from column (r/d)*col_r + (s/d)*col_s + ((r%d)*d + s%d)*Cq + c of
+// partial[z][k][.], d = s2d (1 for everything but space-to-depth operands, where it is the stride).  The
+// re-packed operands of odd channel counts have wider columns that are dropped here.  One output per lane.
+template <int G, typename OUT>
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ partial, OUT *__restrict__ dw,
                                                            int total, int splits, int ncols, int RSC, int SC, int C,
                                                            int col_r, int col_s, int s2d, int Cq, size_t split_stride)
 {
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (gid >= total) return;
-    const int k = gid / RSC, rem = gid % RSC;
-    const int r = rem / SC, rem2 = rem % SC;
-    const int sidx = rem2 / C, c = rem2 % C;
-    const size_t src = (size_t)k * ncols + (r / s2d) * col_r + (sidx / s2d) * col_s + ((r % s2d) * s2d + sidx % s2d) * Cq + c;
-    float acc = partial[src];
-    for (int zz = 1; zz < splits; ++zz) acc += partial[(size_t)zz * split_stride + src];
-    dw[gid] = acc;
-}
-
-// Plain NHWC operands (source index == destination index), four outputs per thread with 16-byte loads.
-__global__ __launch_bounds__(256) void wgrad_reduce_vec4_kernel(const float4 *__restrict__ partial, float4 *__restrict__ dw,
-                                                                int total4, int splits)
-{
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (gid >= total4) return;
-    float4 acc = partial[gid];
-    for (int zz = 1; zz < splits; ++zz) {
-        const float4 v = partial[(size_t)zz * total4 + gid];
-        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    }
-    dw[gid] = acc;
-}
-
-// Same sum for many splits and few outputs: a workgroup of 16 waves owns 64 consecutive outputs; wave v
-// adds the splits v, v+16, v+32, ... (lanes = outputs, so every load is a contiguous 256-byte row) and
-// the 16 wave sums are then added in wave order through LDS.  The order of additions depends only on the
-// split count, so results are reproducible.
-__global__ __launch_bounds__(1024) void wgrad_reduce_wide_kernel(const float *__restrict__ partial, float *__restrict__ dw,
-                                                                 int total, int splits, int ncols, int RSC, int SC, int C,
-                                                                 int col_r, int col_s, int s2d, int Cq, size_t split_stride)
-{
-    __shared__ float part[16][64];
+    constexpr int LPG = 64 / G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int gid = blockIdx.x * 64 + lane;
+    const int grp = lane / LPG;
+    const int gid = (blockIdx.x * 4 + wave) * LPG + lane % LPG;
     float acc = 0.f;
     if (gid < total) {
         const int k = gid / RSC, rem = gid % RSC;
         const int r = rem / SC, rem2 = rem % SC;
         const int sidx = rem2 / C, c = rem2 % C;
         const size_t src = (size_t)k * ncols + (r / s2d) * col_r + (sidx / s2d) * col_s + ((r % s2d) * s2d + sidx % s2d) * Cq + c;
-        for (int zz = wave; zz < splits; zz += 16) acc += partial[(size_t)zz * split_stride + src];
+        for (int zz = grp; zz < splits; zz += G) acc += partial[(size_t)zz * split_stride + src];
     }
-    part[wave][lane] = acc;
-    __syncthreads();
-    if (wave == 0 && gid < total) {
-        float sum = part[0][lane];
 #pragma unroll
-        for (int v = 1; v < 16; ++v) sum += part[v][lane];
-        dw[gid] = sum;
-    }
+    for (int d = LPG; d < 64; d <<= 1) acc += __shfl_xor(acc, d);
+    if (grp == 0 && gid < total) store_f32(dw + gid, acc);
 }
 
 // slots: workgroups that fit one CU; util: fraction of the CU's matrix peak the tile sustains (measured)
@@ -518,6 +525,8 @@ Plan search_plan(const WgradGeom &g, int forced, int forced_splits)
 
 }  // namespace
 
+const char *wgrad_tile_name(int index) { return index >= 0 && index < N_TILES ? kTiles[index].name : nullptr; }
+
 WgradGeom wgrad_geom_plain(const ConvShape &s)
 {
     return WgradGeom{s.N, s.H, s.W, s.C, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, s.C, s.R, s.S, s.C, s.S * s.C, s.C, 1, 0};
@@ -555,7 +564,31 @@ size_t wgrad_workspace(const WgradGeom &g)
     return (size_t)make_plan(g).splits * g.K * g.TR * g.TS * g.run * sizeof(float);
 }
 
-int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *partial, hipStream_t st,
+template <typename OUT>
+static int launch_reduce(const WgradGeom &g, const float *partial, OUT *dw, int splits, int ncols, bool identity, hipStream_t st)
+{
+    const int total = g.K * g.R * g.S * g.C;
+    // many splits of a small dw: 16 lane groups keep enough loads in flight; otherwise 4
+    const bool wide = splits >= 32 && total < 256 * 1024;
+    if (identity && total % 4 == 0) {
+        const int total4 = total / 4;
+        if (wide)
+            hipLaunchKernelGGL((wgrad_reduce_vec4_kernel<16, OUT>), dim3((unsigned)((total4 + 15) / 16)), dim3(256), 0, st,
+                               (const float4 *)partial, dw, total4, splits);
+        else
+            hipLaunchKernelGGL((wgrad_reduce_vec4_kernel<4, OUT>), dim3((unsigned)((total4 + 63) / 64)), dim3(256), 0, st,
+                               (const float4 *)partial, dw, total4, splits);
+    } else if (wide) {
+        hipLaunchKernelGGL((wgrad_reduce_kernel<16, OUT>), dim3((unsigned)((total + 15) / 16)), dim3(256), 0, st, partial, dw, total,
+                           splits, ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq, (size_t)g.K * ncols);
+    } else {
+        hipLaunchKernelGGL((wgrad_reduce_kernel<4, OUT>), dim3((unsigned)((total + 63) / 64)), dim3(256), 0, st, partial, dw, total,
+                           splits, ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq, (size_t)g.K * ncols);
+    }
+    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
+int wgrad(const WgradGeom &g, const void *x, const void *dy, void *dw, bool dw_bf16, float *partial, hipStream_t st,
           const char **variant)
 {
     const Plan pl = make_plan(g);
@@ -577,28 +610,16 @@ int wgrad(const WgradGeom &g, const void *x, const void *dy, float *dw, float *p
     p.dy_bytes = (unsigned)((long long)p.M * g.K * 2);
     const long long tiles = (long long)pl.k_tiles * pl.n_tiles;
     if (tiles * p.splits > 0x3FFFFFFFll) return MXC_ERR_SHAPE;
-    const int total = g.K * g.R * g.S * g.C;
     const bool identity = g.s2d == 1 && g.col_s == g.C && g.col_r == g.S * g.C && p.ncols == g.R * g.S * g.C;
-    // one split whose columns are already in KRSC order: the "partial" tensor is dw itself, nothing to reduce
-    const bool direct = p.splits == 1 && identity;
-    if (direct) p.partial = dw;
+    // one split whose columns are already in KRSC order and an fp32 result: the "partial" tensor is dw itself
+    const bool direct = p.splits == 1 && identity && !dw_bf16;
+    if (direct) p.partial = (float *)dw;
     const int rc = launch_choice(pl.tile, p, (int)tiles, st);
     if (rc != MXC_OK) return rc;
     *variant = tc.name;
     if (direct) return MXC_OK;
-    if (p.splits > 16 && total < 256 * 1024)
-        hipLaunchKernelGGL(wgrad_reduce_wide_kernel, dim3((unsigned)((total + 63) / 64)), dim3(1024), 0, st, partial, dw, total,
-                           p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq,
-                           (size_t)g.K * p.ncols);
-    else if (identity && total % 4 == 0)
-        hipLaunchKernelGGL(wgrad_reduce_vec4_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, st,
-                           (const float4 *)partial, (float4 *)dw, total / 4, p.splits);
-    else
-        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, dw, total,
-                           p.splits, p.ncols, g.R * g.S * g.C, g.S * g.C, g.C, g.col_r, g.col_s, g.s2d, g.Cq,
-                           (size_t)g.K * p.ncols);
-    *variant = tc.name;
-    return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+    return dw_bf16 ? launch_reduce(g, partial, (bf16_t *)dw, p.splits, p.ncols, identity, st)
+                   : launch_reduce(g, partial, (float *)dw, p.splits, p.ncols, identity, st);
 }
 
 }  // namespace mxc

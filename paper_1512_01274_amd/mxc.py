@@ -16,7 +16,7 @@ MXC_ERR_NULL, MXC_ERR_SHAPE, MXC_ERR_UNSUPPORTED, MXC_ERR_WORKSPACE, MXC_ERR_ALI
 MXC_F32, MXC_BF16 = 0, 1
 MXC_NCHW, MXC_NHWC = 0, 1
 MXC_FWD, MXC_BWD_DATA, MXC_BWD_WEIGHT, MXC_BWD_DATA_RELU, MXC_BIAS_GRAD = 0, 1, 2, 3, 4
-MXC_BWD_DATA_FILTER, MXC_BWD_DATA_PREPARED, MXC_BWD_DATA_PREPARED_RELU = 5, 6, 7
+MXC_BWD_DATA_FILTER, MXC_BWD_DATA_PREPARED, MXC_BWD_DATA_PREPARED_RELU, MXC_BWD_WEIGHT_BF16 = 5, 6, 7, 8
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmxc.so")
 if not os.path.exists(LIB_PATH):
@@ -24,7 +24,7 @@ if not os.path.exists(LIB_PATH):
 _lib = ctypes.CDLL(LIB_PATH)
 
 _I, _VP, _SZ = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
-for _name in ("mxc_conv2d_fwd", "mxc_conv2d_bwd_data", "mxc_conv2d_bwd_weight"):
+for _name in ("mxc_conv2d_fwd", "mxc_conv2d_bwd_data", "mxc_conv2d_bwd_weight", "mxc_conv2d_bwd_weight_bf16"):
     _f = getattr(_lib, _name)
     _f.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP, _SZ, _VP]
     _f.restype = _I
@@ -44,6 +44,8 @@ _lib.mxc_last_variant.argtypes = []
 _lib.mxc_last_variant.restype = ctypes.c_char_p
 _lib.mxc_version.argtypes = []
 _lib.mxc_version.restype = _I
+_lib.mxc_tile_name.argtypes = [_I, _I]
+_lib.mxc_tile_name.restype = ctypes.c_char_p
 _lib.mxc_conv2d_fwd_bias_act.argtypes = [_I] * 11 + [_VP, _VP, _VP, _I, _VP, _VP, _SZ, _VP]
 _lib.mxc_conv2d_fwd_bias_act.restype = _I
 _lib.mxc_conv2d_bwd_data_relu.argtypes = [_I] * 11 + [_VP, _VP, _VP, _VP, _VP, _SZ, _VP]
@@ -83,6 +85,22 @@ def mxc_last_variant() -> str:
 
 def mxc_version() -> int:
     return _lib.mxc_version()
+
+
+def mxc_tile_name(family: int, index: int):
+    n = _lib.mxc_tile_name(family, index)
+    return None if n is None else n.decode()
+
+
+def mxc_tile_names(family: int):
+    """Names of the tile shapes of a kernel family (0: implicit GEMM, 1: backward-weight)."""
+    out, i = [], 0
+    while True:
+        n = _lib.mxc_tile_name(family, i)
+        if n is None:
+            return out
+        out.append(n.decode())
+        i += 1
 
 
 def dtype_code(t: torch.dtype) -> int:
@@ -133,6 +151,10 @@ def mxc_conv2d_bwd_data(N, C, H, W, K, R, S, stride, pad, dtype, layout, dy, w, 
 
 def mxc_conv2d_bwd_weight(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, workspace=None, stream=None):
     _call(_lib.mxc_conv2d_bwd_weight, (N, C, H, W, K, R, S, stride, pad), dtype, layout, x, dy, dw, workspace, stream)
+
+
+def mxc_conv2d_bwd_weight_bf16(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, workspace=None, stream=None):
+    _call(_lib.mxc_conv2d_bwd_weight_bf16, (N, C, H, W, K, R, S, stride, pad), dtype, layout, x, dy, dw, workspace, stream)
 
 
 def mxc_conv2d_bwd_weight_static(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, dy, dw, stream=None):

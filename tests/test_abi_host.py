@@ -124,6 +124,23 @@ def test_workspace_query_over_random_shapes(mxc):
                     assert sizes[mxc.MXC_BWD_DATA_PREPARED] + sizes[mxc.MXC_BWD_DATA_FILTER] >= sizes[mxc.MXC_BWD_DATA], dims
 
 
+def test_nchw_limits_are_reported_before_any_launch(mxc):
+    """NCHW operands go through batched transposes with int row/column counts: what those cannot run is refused by the
+    shape check itself (the size query sees it too), while the same problem in NHWC is accepted; batch and filter
+    counts beyond 65535 are fine in both layouts."""
+    import ctypes as ct
+    out = ct.c_size_t(0)
+    lib = mxc.raw()
+    huge = (1, 1, 65536, 65536, 1, 1, 1, 1, 0)                # H*W = 2^32 elements per plane
+    assert lib.mxc_conv2d_workspace_bytes(mxc.MXC_FWD, *huge, mxc.MXC_BF16, mxc.MXC_NCHW, ct.byref(out)) == mxc.MXC_ERR_SHAPE
+    assert lib.mxc_conv2d_fwd(*huge, mxc.MXC_BF16, mxc.MXC_NCHW, 4096, 8192, 16384, None, 0, None) == mxc.MXC_ERR_SHAPE
+    assert lib.mxc_conv2d_workspace_bytes(mxc.MXC_FWD, *huge, mxc.MXC_BF16, mxc.MXC_NHWC, ct.byref(out)) == mxc.MXC_OK
+    many = (70000, 8, 4, 4, 70000, 1, 1, 1, 0)                # N and K beyond 65535
+    for lay in (mxc.MXC_NCHW, mxc.MXC_NHWC):
+        for p in (mxc.MXC_FWD, mxc.MXC_BWD_DATA, mxc.MXC_BWD_WEIGHT):
+            assert lib.mxc_conv2d_workspace_bytes(p, *many, mxc.MXC_BF16, lay, ct.byref(out)) == mxc.MXC_OK
+
+
 def test_grouped_entry_points_validate_on_the_host(mxc):
     lib = mxc.raw()
     big = 1 << 30

@@ -166,7 +166,10 @@ def test_canaries_around_outputs(mxc, dtype):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 5, 7), (3, 64, 8, 8), (2, 65, 9, 15), (1, 200, 3, 3), (2, 16, 70, 66),
-                                   (2, 3, 8, 24), (3, 4, 4, 6), (1, 2, 16, 3), (2, 3, 224, 224)])
+                                   (2, 3, 8, 24), (3, 4, 4, 6), (1, 2, 16, 3), (2, 3, 224, 224),
+                                   # rows and columns multiples of 8: the 16-byte-vector transposes, whole and ragged tiles
+                                   (2, 72, 12, 10), (1, 200, 4, 6), (3, 128, 16, 16), (2, 64, 56, 56), (1, 136, 9, 8),
+                                   (5, 2048, 1, 3), (1, 12, 28, 28)])
 def test_layout_convert(mxc, shape, dtype):
     n, c, h, w = shape
     g = np.random.Generator(np.random.Philox(key=3))

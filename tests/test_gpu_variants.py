@@ -1,0 +1,100 @@
+"""Every tile shape the matrix-core kernels are built in, forced through the library's tuning hooks and
+checked against the oracle: each implicit-GEMM shape in both reduction orders (channel-block-major needs
+C % 64 == 0, tap-major runs otherwise) for forward and backward-data on ragged and strided problems, each
+backward-weight shape with several split counts, and the two-launch plans (main shape for the whole rounds,
+a smaller shape for the remaining rows).  The test asserts that the forced shape is the one that ran."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1512_01274_amd import inputs as gen
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mxc():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1512_01274_amd import mxc as m
+    return m
+
+
+def _names(family):
+    from paper_1512_01274_amd import mxc as m
+    return m.mxc_tile_names(family)
+
+
+class forced:
+    def __init__(self, var, value):
+        self.var, self.value = var, value
+
+    def __enter__(self):
+        os.environ[self.var] = self.value
+
+    def __exit__(self, *a):
+        del os.environ[self.var]
+
+
+# N, C, H, W, K, R, S, stride, pad: ragged row and column tiles; C = 64 runs the channel-block-major order,
+# C = 72 the tap-major one
+IGEMM_SHAPES = [
+    (2, 64, 19, 17, 104, 3, 3, 1, 1),
+    (3, 72, 13, 15, 200, 3, 3, 1, 1),
+    (2, 128, 17, 17, 72, 3, 3, 2, 1),      # stride 2: backward-data runs one launch per residue class
+    (2, 192, 21, 9, 264, 1, 1, 1, 0),      # 1x1
+]
+
+
+def _check(mxc, oracle, dims, passes, expect):
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy = gen.random_case(hash(dims) & 0xFFFF, *dims, dtype="bf16", dist="normal")
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    for name in passes:
+        if name == "fwd":
+            got = run.fwd(x, w)
+            ref, den = oracle.conv2d_fwd(x, w, st, pad), oracle.conv2d_fwd(np.abs(x), np.abs(w), st, pad)
+        elif name == "bwd_data":
+            got = run.bwd_data(dy, w)
+            ref = oracle.conv2d_bwd_data(dy, w, x.shape, st, pad)
+            den = oracle.conv2d_bwd_data(np.abs(dy), np.abs(w), x.shape, st, pad)
+        else:
+            got = run.bwd_weight(x, dy)
+            ref = oracle.conv2d_bwd_weight(x, dy, w.shape, st, pad)
+            den = oracle.conv2d_bwd_weight(np.abs(x), np.abs(dy), w.shape, st, pad)
+        ran = mxc.mxc_last_variant()
+        assert ran.split(":")[-1].startswith(expect), f"{name} {dims}: wanted {expect}, ran {ran}"
+        assert util.metric(got, ref, den) <= util.TOL["bf16"], (name, dims, ran)
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", name != "bwd_weight")), (name, dims, ran)
+
+
+@pytest.mark.parametrize("dims", IGEMM_SHAPES)
+@pytest.mark.parametrize("tile", _names(0))
+def test_every_igemm_tile(mxc, oracle, tile, dims):
+    with forced("MXC_FORCE_VARIANT", tile):
+        _check(mxc, oracle, dims, ("fwd", "bwd_data"), tile)
+
+
+@pytest.mark.parametrize("splits", [1, 3, 0])
+@pytest.mark.parametrize("dims", IGEMM_SHAPES[:3])
+@pytest.mark.parametrize("tile", _names(1))
+def test_every_wgrad_tile(mxc, oracle, tile, dims, splits):
+    with forced("MXC_FORCE_WGRAD", tile + (f"/{splits}" if splits else "")):
+        _check(mxc, oracle, dims, ("bwd_weight",), tile)
+
+
+PAIRS = [
+    # main shape (one whole round of it: 256 tiles at one per CU, 512 at two), shape for the remaining rows, problem
+    ("igemm_128x128_k64s2_w4", "igemm_64x128_k64s3_w4", (5, 64, 120, 120, 64, 3, 3, 1, 1)),
+    ("igemm_256x128_k64s3_w8", "igemm_128x64_k64s2_w4", (5, 64, 120, 120, 128, 3, 3, 1, 1)),
+    ("igemm_256x256_k64s2_w8", "igemm_64x256_k64s3_w8", (5, 72, 120, 120, 256, 3, 3, 1, 1)),
+    ("igemm_256x256_k64s2_w8", "igemm_192x256_k64s2_w8", (5, 64, 120, 120, 200, 1, 1, 1, 0)),
+]
+
+
+@pytest.mark.parametrize("main,tail,dims", PAIRS)
+def test_two_launch_plans(mxc, oracle, main, tail, dims):
+    with forced("MXC_FORCE_VARIANT", main + "+" + tail):
+        _check(mxc, oracle, dims, ("fwd",), main + "+" + tail)
