@@ -152,6 +152,40 @@ class Network:
         return out
 
 
+def chained_grouped_step(net):
+    """The grouped step with consecutive layers chained on the device where their shapes allow it (the output
+    tensor of layer i is the input tensor of layer i+1, and backward-data of layer i+1 writes the output gradient
+    that layer i reads): forward chain with bias + ReLU, then from the last layer to the first backward-weight,
+    bias gradient, backward-data with the ReLU derivative, and the update.  Returns (step function, link names)."""
+    m, layers = net.mxc, net.layers
+    x_of = {id(s): s.x for s in layers}
+    dy_of = {id(s): s.dy for s in layers}
+    links = []
+    for a, b in zip(layers[:-1], layers[1:]):
+        if (a.L.N, a.L.K, a.L.P, a.L.Q) == (b.L.N, b.L.C, b.L.H, b.L.W):
+            x_of[id(b)] = a.y
+            dy_of[id(a)] = b.dx
+            links.append(f"{a.L.name}->{b.L.name}")
+    calls = []
+    s0 = layers[0]
+    if net.layout == "nhwc":
+        calls.append(lambda: m.mxc_layout_convert(s0.L.N, s0.L.C, s0.L.H, s0.L.W, s0.dt, m.MXC_NCHW, m.MXC_NHWC, s0.x_nchw, s0.x))
+    for s in layers:
+        calls.append(lambda s=s: m.mxc_conv2d_fwd_bias_act(*s.dims, s.dt, s.lay, x_of[id(s)], s.w, s.bias, 1, s.y, s.ws[m.MXC_FWD]))
+    for s in reversed(layers):
+        calls.append(lambda s=s: m.mxc_conv2d_bwd_weight(*s.dims, s.dt, s.lay, x_of[id(s)], dy_of[id(s)], s.dw, s.ws[m.MXC_BWD_WEIGHT]))
+        calls.append(lambda s=s: m.mxc_bias_grad(s.L.N, s.L.K, s.L.P, s.L.Q, s.dt, s.lay, dy_of[id(s)], s.db, s.ws[m.MXC_BIAS_GRAD]))
+        calls.append(lambda s=s: m.mxc_conv2d_bwd_data_relu(*s.dims, s.dt, s.lay, dy_of[id(s)], s.w, x_of[id(s)], s.dx,
+                                                            s.ws[m.MXC_BWD_DATA_RELU]))
+        if s.w_master is not None:
+            calls.append(lambda s=s: m.mxc_sgd_update(s.w_master, s.dw, s.vel, s.w, 1e-9, 0.9, 1e-4))
+
+    def step():
+        for fn in calls:
+            fn()
+    return step, links
+
+
 def timed_groups(torch, run_step, steps, warmup, groups):
     """`groups` timings of exactly `steps` steps each, every group bracketed by synchronize; seconds per step."""
     for _ in range(warmup):
@@ -503,6 +537,10 @@ def main():
             return summ, net, per_call, ev_ms
         rl = rooflines(per_call, net, ev_ms)
         summ["roofline"] = rl[0] if rl else None
+        if cfg.dtype == "bf16":
+            chain_step, chain_links = chained_grouped_step(net)
+            ch = median(timed_groups(torch, chain_step, steps, 2, 3))
+            summ["chained_grouped_operations"] = {"tflops": tf(ch), "ms_per_step": round(ch * 1e3, 4), "links": chain_links}
         del net, engine
         torch.cuda.empty_cache()
         return summ, None, None, None
@@ -520,6 +558,8 @@ def main():
                           max(3, args.steps // 4), 2, 3)
     flops_pruned = net.flops_per_step - first.L.flops_per_pass
     grouped = timed_groups(torch, single_stream_step(net, grouped=True), max(3, args.steps // 4), 2, 3)
+    chain_step, chain_links = chained_grouped_step(net)
+    chained = timed_groups(torch, chain_step, max(3, args.steps // 4), 2, 3)
     prep_calls = [s.prepare_filter for s in net.layers]
     prep = timed_groups(torch, lambda: [f() for f in prep_calls], max(3, args.steps // 4), 2, 3)
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
@@ -550,6 +590,11 @@ def main():
                                "note": "same convolution flops; forward + bias + ReLU, backward-data with the ReLU derivative "
                                        "(filter re-packed inside the call), backward-weight, bias gradient, SGD update of fp32 "
                                        "master weights with a bf16 copy (the extra work is not counted as flops)"},
+        "chained_grouped_operations": {"value": round(net.flops_per_step / median(chained) / 1e12, 3), "unit": "TFLOP/s",
+                                       "ms_per_step": round(median(chained) * 1e3, 4), "schedule": "single stream, eager",
+                                       "links": chain_links,
+                                       "note": "the grouped step with the listed layers chained on the device: y of one call is "
+                                               "x of the next, dx of one call is dy of the layer below"},
         "filter_prepare_ms_per_step": round(median(prep) * 1e3, 4),
     }
     if cfg.dtype == "bf16":
@@ -578,6 +623,9 @@ def main():
                 continue
             nets[other.name] = measure(other, max(3, args.steps // 4), 2, 3, False)[0]
         result["networks"] = nets
+        # the batch size of the paper's single-GPU comparison (its Section 4: batch 32), whole stack forward + backward
+        result["networks_batch32"] = {n: measure(gen.config_by_name(n), max(3, args.steps // 4), 2, 3, False)[0]
+                                      for n in ("alexnet_b32", "vgg_a_b32")}
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(gen, cfg, args.cpu_sample_batch)
     print(json.dumps(result), flush=True)

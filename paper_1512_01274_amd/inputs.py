@@ -111,6 +111,19 @@ EXTRA_CONFIGS: List[Config] = [
 ]
 
 
+def _rebatched(cfg: Config, index: int, name: str, n: int) -> Config:
+    return Config(index, name, cfg.dtype, cfg.dist, tuple(L.with_batch(n) for L in cfg.layers))
+
+
+# The batch size of the paper's own single-GPU comparison (Section 4, "Raw performance": batch 32): the
+# AlexNet- and VGG-style stacks once more at that size, drawn from the same random streams as the full-size
+# configs (a fresh draw of the smaller size, not a prefix).
+EXTRA_CONFIGS += [
+    _rebatched(CONFIGS[1], 1, "alexnet_b32", 32),
+    _rebatched(CONFIGS[3], 3, "vgg_a_b32", 32),
+]
+
+
 def config_by_name(name: str) -> Config:
     for c in CONFIGS + EXTRA_CONFIGS:
         if c.name == name:
