@@ -273,7 +273,8 @@ const char *mxc_last_variant(void);
 int mxc_version(void);
 
 /* Tuning aid: name of the index-th tile shape the matrix-core kernels are built in (family 0: forward /
- * backward-data implicit GEMM, family 1: backward-weight), NULL past the last.  These are the names that
+ * backward-data implicit GEMM, family 1: backward-weight, family 2: the streaming implicit GEMM for short
+ * reductions, which has one plan and runs only where the filter tile fits on chip), NULL past the last.  These are the names that
  * mxc_last_variant() reports and that the tuning hooks MXC_FORCE_VARIANT=<name>[+<name of the shape for the
  * rows the last whole round leaves>] and MXC_FORCE_WGRAD=<name>[/<splits>] (environment, read per call) accept;
  * the tuning script and the tests walk the list.  Static host memory. */

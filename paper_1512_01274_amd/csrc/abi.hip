@@ -606,7 +606,7 @@ int mxc_version(void) { return 200; }
 
 const char *mxc_tile_name(int family, int index)
 {
-    return family == 0 ? igemm_tile_name(index) : family == 1 ? wgrad_tile_name(index) : nullptr;
+    return family == 0 ? igemm_tile_name(index) : family == 1 ? wgrad_tile_name(index) : family == 2 ? igemm_stream_name(index) : nullptr;
 }
 
 int mxc_probe_mfma(int workgroups, int iters, void *out, size_t out_bytes, double *flops, void *hip_stream)

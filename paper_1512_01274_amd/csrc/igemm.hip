@@ -40,42 +40,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
 
-constexpr int MAX_TAPS = 127;   // tap table capacity (11x11 = 121 fits)
-
-struct IgemmParams {
-    const bf16_t *in;    // activations [N][Hi][Wi][Ci]
-    const bf16_t *wm;    // filter matrix [Co][T*Ci]
-    bf16_t *out;         // output tensor [N][Ho][Wo][Co]
-    int N, Hi, Wi;
-    int Ci;              // reduction elements per tap: a contiguous run starting at the tap's pixel
-    int pix;             // elements per pixel in memory (== Ci for plain NHWC; smaller when a run spans pixels)
-    int Co;
-    int TR, TS, tstep_h, tstep_w;   // tap grid and the direction (+1 or -1) taps advance in, per axis
-    int Mh, Mw;          // output grid of this launch (per image)
-    int in_mul_h, in_mul_w, in_off_h, in_off_w;     // input coordinate of tap 0: a*in_mul + in_off
-    int Ho, Wo, out_mul_h, out_mul_w, out_off_h, out_off_w;  // output coordinate: a*out_mul + out_off
-    int linear_out;      // output pixel index == m (forward, and stride-1 backward-data)
-    int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
-    int m_begin, m_end;  // GEMM rows [m_begin, m_end) belong to this launch (a problem may be cut in two launches of
-                         // different tile shapes: see Plan); tile 0 starts at m_begin
-    int m_tiles, n_tiles;
-    unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
-    // BT kernels (1x1 stride-1 backward-data straight from the filter, no transposed copy): wm = w[K][Co];
-    // reduction index k reads filter row k, whose Co output columns are contiguous.  Needs Ci % 64 == 0.
-    unsigned bt_w_bytes; // size of the filter
-    // split reduction (few tiles, long reduction): workgroup (tile, z) runs stages [z*split_stages, (z+1)*split_stages)
-    // and stores its fp32 accumulators to partial[z][m][co]; a second kernel adds the splits in ascending z and
-    // applies bias / ReLU / mask.  splits <= 1: off.
-    float *partial;
-    int splits, split_stages;
-    int tap_row_inner;   // tap t = (column step)*TR + (row step) instead of (row step)*TS + (column step)
-    int tap_inner;       // reduction order (Ci % BKT == 0 only): 1 = all taps of a channel block before the next block
-    // applied to the accumulators before the store (all optional)
-    const float *bias;   // + bias[co]
-    int relu;            // max(0, .)
-    const bf16_t *mask;  // indexed like `out`: the stored value is 0 where mask <= 0
-};
-
 typedef __attribute__((address_space(3))) void *lds_vptr;
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
@@ -589,6 +553,9 @@ const TileChoice kTiles[] = {
     {64, 128, 64, 2, 0.45f, "igemm_64x128_k64s3_w4"},
 };
 constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
+// plan index of the streaming kernel (stream.hip): not a tile of this file's kernel, one launch for all rows
+constexpr int STREAM_TILE = N_TILE_CHOICES;
+const char *const kStreamName = "igemm_stream";
 
 // the tiles that also exist reading a 1x1 filter in place (transposed tiles)
 bool has_bt(int idx) { return idx == 0 || idx == 1 || idx == 4; }
@@ -628,6 +595,7 @@ int tile_index(const char *name, size_t len)
 {
     for (int i = 0; i < N_TILE_CHOICES; ++i)
         if (strlen(kTiles[i].name) == len && !strncmp(name, kTiles[i].name, len)) return i;
+    if (strlen(kStreamName) == len && !strncmp(name, kStreamName, len)) return STREAM_TILE;
     return -1;
 }
 
@@ -658,13 +626,15 @@ double model_time(const TileChoice &t, long long M, int Co, int KT, double fixed
 // Plan choice, in this order: MXC_FORCE_VARIANT=<name> or <main>+<tail> (tuning sweeps only); the table of
 // measured best plans (tuned_igemm.inc, written by the tuning script from timings on the device) when it
 // holds this GEMM; else the least modelled time over single shapes and main+tail pairs.
-Plan choose_plan(long long M, int Co, int Kd)
+// allow_stream = false: callers that need a tile of this file's kernel (split reductions, in-place filters).
+Plan choose_plan(long long M, int Co, int Kd, bool allow_stream = true)
 {
     if (const char *f = getenv("MXC_FORCE_VARIANT")) {
         const char *plus = strchr(f, '+');
         const int a = tile_index(f, plus ? (size_t)(plus - f) : strlen(f));
         const int b = plus ? tile_index(plus + 1, strlen(plus + 1)) : -1;
-        if (a >= 0 && (!plus || b >= 0)) {
+        if (a == STREAM_TILE && !plus && allow_stream) return Plan{STREAM_TILE, -1, M};
+        if (a >= 0 && a != STREAM_TILE && b != STREAM_TILE && (!plus || b >= 0)) {
             const long long rows = b >= 0 ? whole_round_rows(kTiles[a], M, Co) : M;
             return (b >= 0 && rows > 0 && rows < M) ? Plan{a, b, rows} : Plan{a, -1, M};
         }
@@ -672,7 +642,8 @@ Plan choose_plan(long long M, int Co, int Kd)
     for (const TunedIgemm &e : kTunedIgemm)
         if (e.M == M && e.Co == Co && e.Kd == Kd) {
             const int a = tile_index(e.main, strlen(e.main)), b = e.tail[0] ? tile_index(e.tail, strlen(e.tail)) : -1;
-            if (a < 0) break;
+            if (a < 0 || b == STREAM_TILE || (a == STREAM_TILE && !allow_stream)) break;
+            if (a == STREAM_TILE) return Plan{STREAM_TILE, -1, M};
             const long long rows = b >= 0 ? whole_round_rows(kTiles[a], M, Co) : M;
             return (b >= 0 && rows > 0 && rows < M) ? Plan{a, b, rows} : Plan{a, -1, M};
         }
@@ -699,11 +670,19 @@ Plan choose_plan(long long M, int Co, int Kd)
     return best;
 }
 
-int choose_tile(long long M, int Co, int Kd) { return choose_plan(M, Co, Kd).main; }
+int choose_tile(long long M, int Co, int Kd) { return choose_plan(M, Co, Kd, false).main; }
+
+// the plan for one launch site: the streaming kernel only where it can run the problem
+Plan plan_for(const IgemmParams &p, long long M, int Co, int Kd, bool tiles_only = false)
+{
+    const Plan pl = choose_plan(M, Co, Kd, !tiles_only);
+    return (pl.main == STREAM_TILE && !stream_applicable(p)) ? choose_plan(M, Co, Kd, false) : pl;
+}
 
 // runs the plan: one or two launches on the stream
 int launch_plan(const Plan &pl, const IgemmParams &p, hipStream_t st, bool bt = false)
 {
+    if (pl.main == STREAM_TILE) return stream_launch(p, st);
     if (pl.tail < 0) return launch_choice(pl.main, p, st, bt);
     const int rc = launch_choice(pl.main, p, st, bt, 0, pl.rows_main);
     if (rc != MXC_OK) return rc;
@@ -714,6 +693,7 @@ int launch_plan(const Plan &pl, const IgemmParams &p, hipStream_t st, bool bt = 
 const char *plan_name(const Plan &pl)
 {
     static thread_local char name[96];
+    if (pl.main == STREAM_TILE) return kStreamName;
     if (pl.tail < 0) return kTiles[pl.main].name;
     snprintf(name, sizeof(name), "%s+%s", kTiles[pl.main].name, kTiles[pl.tail].name);
     return name;
@@ -848,6 +828,7 @@ int launch_split(int tc, IgemmParams p, long long M, int sp, void *split_ws, voi
 }  // namespace
 
 const char *igemm_tile_name(int index) { return index >= 0 && index < N_TILE_CHOICES ? kTiles[index].name : nullptr; }
+const char *igemm_stream_name(int index) { return index == 0 ? kStreamName : nullptr; }
 
 size_t igemm_bwd_data_split_bytes(const ConvShape &s)
 {
@@ -883,9 +864,9 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
     p.in_mul_h = s.stride; p.in_mul_w = s.stride; p.in_off_h = -s.pad; p.in_off_w = -s.pad;
     p.Ho = s.P; p.Wo = s.Q; p.out_mul_h = 1; p.out_mul_w = 1; p.out_off_h = 0; p.out_off_w = 0;
     const long long M = (long long)s.N * s.P * s.Q;
-    const Plan pl = choose_plan(M, s.K, s.R * s.S * s.C);
-    *variant = plan_name(pl);
     const int sp = (split_ws != nullptr && s.K % 8 == 0) ? split_count(M, s.K, s.R * s.S * s.C) : 1;
+    const Plan pl = plan_for(p, M, s.K, s.R * s.S * s.C, sp > 1);
+    *variant = plan_name(pl);
     if (sp > 1) return launch_split(pl.main, p, M, sp, split_ws, y, post, st, variant);
     return launch_plan(pl, p, st);
 }
@@ -911,7 +892,7 @@ int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y
     p.Mh = s.P; p.Mw = s.Q;
     p.in_mul_h = s.stride; p.in_mul_w = s.stride; p.in_off_h = 0; p.in_off_w = 0;
     p.Ho = s.P; p.Wo = s.Q; p.out_mul_h = 1; p.out_mul_w = 1; p.out_off_h = 0; p.out_off_w = 0;
-    const Plan pl = choose_plan((long long)s.N * s.P * s.Q, s.K, s.R * g.run);
+    const Plan pl = plan_for(p, (long long)s.N * s.P * s.Q, s.K, s.R * g.run);
     *variant = plan_name(pl);
     return launch_plan(pl, p, st);
 }
@@ -986,12 +967,11 @@ int igemm_bwd_data(const ConvShape &s, const void *dy, const void *w_in_place, v
                 if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
                 continue;
             }
-            pl = choose_plan((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
+            const int sp = (split_ws != nullptr && s.stride == 1 && s.C % 8 == 0)
+                               ? split_count((long long)s.N * Mh * Mw, s.C, TR * TS * s.K) : 1;
+            pl = plan_for(p, (long long)s.N * Mh * Mw, s.C, TR * TS * s.K, bt || sp > 1);
             if (bt && !has_bt(pl.tail)) pl = Plan{pl.main, -1, 0};
-            if (split_ws != nullptr && s.stride == 1 && s.C % 8 == 0) {
-                const int sp = split_count((long long)s.N * Mh * Mw, s.C, TR * TS * s.K);
-                if (sp > 1) return launch_split(pl.main, p, (long long)s.N * Mh * Mw, sp, split_ws, dx, post, st, variant, bt);
-            }
+            if (sp > 1) return launch_split(pl.main, p, (long long)s.N * Mh * Mw, sp, split_ws, dx, post, st, variant, bt);
             const int rc = launch_plan(pl, p, st, bt);
             if (rc != MXC_OK) return rc;
         }
@@ -1123,7 +1103,7 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w2, vo
         p.Ho = s.H; p.Wo = g.Wg; p.out_mul_h = s.stride; p.out_mul_w = 1; p.out_off_h = h_first; p.out_off_w = 0;
         w2_off += (size_t)g.G * 4 * TR * g.U * s.K;
         if (Mh <= 0) continue;
-        pl = choose_plan((long long)s.N * Mh * g.Wg, p.Co, TR * g.U * s.K);
+        pl = plan_for(p, (long long)s.N * Mh * g.Wg, p.Co, TR * g.U * s.K);
         const int rc = launch_plan(pl, p, st);
         if (rc != MXC_OK) return rc;
     }

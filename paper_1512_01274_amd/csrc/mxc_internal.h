@@ -142,7 +142,53 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w2, vo
 
 // names of the tile shapes the two MFMA kernel families are built in (nullptr past the last)
 const char *igemm_tile_name(int index);
+const char *igemm_stream_name(int index);   // names of the streaming kernel's plans (one)
 const char *wgrad_tile_name(int index);
+
+// ---- the implicit GEMM as its kernels see it (igemm.hip, stream.hip) ----------------------------------
+constexpr int MAX_TAPS = 127;   // tap table capacity (11x11 = 121 fits)
+
+// Out[m][co] = sum_{t,ci} In[pixel(m) + tap(t)][ci] * Wm[co][t*Ci + ci]; m runs over (image, row, column) of the
+// launch's output grid, t over a TR x TS grid of filter taps, ci over the channels of a tap's contiguous run.
+struct IgemmParams {
+    const bf16_t *in;    // activations [N][Hi][Wi][Ci]
+    const bf16_t *wm;    // filter matrix [Co][T*Ci]
+    bf16_t *out;         // output tensor [N][Ho][Wo][Co]
+    int N, Hi, Wi;
+    int Ci;              // reduction elements per tap: a contiguous run starting at the tap's pixel
+    int pix;             // elements per pixel in memory (== Ci for plain NHWC; smaller when a run spans pixels)
+    int Co;
+    int TR, TS, tstep_h, tstep_w;   // tap grid and the direction (+1 or -1) taps advance in, per axis
+    int Mh, Mw;          // output grid of this launch (per image)
+    int in_mul_h, in_mul_w, in_off_h, in_off_w;     // input coordinate of tap 0: a*in_mul + in_off
+    int Ho, Wo, out_mul_h, out_mul_w, out_off_h, out_off_w;  // output coordinate: a*out_mul + out_off
+    int linear_out;      // output pixel index == m (forward, and stride-1 backward-data)
+    int M;               // N*Mh*Mw (< 2^31, checked by the launcher)
+    int m_begin, m_end;  // GEMM rows [m_begin, m_end) belong to this launch (a problem may be cut in two launches of
+                         // different tile shapes: see Plan); tile 0 starts at m_begin
+    int m_tiles, n_tiles;
+    unsigned in_bytes, wm_bytes;   // sizes of the two operand buffers (< 2^31)
+    // BT kernels (1x1 stride-1 backward-data straight from the filter, no transposed copy): wm = w[K][Co];
+    // reduction index k reads filter row k, whose Co output columns are contiguous.  Needs Ci % 64 == 0.
+    unsigned bt_w_bytes; // size of the filter
+    // split reduction (few tiles, long reduction): workgroup (tile, z) runs stages [z*split_stages, (z+1)*split_stages)
+    // and stores its fp32 accumulators to partial[z][m][co]; a second kernel adds the splits in ascending z and
+    // applies bias / ReLU / mask.  splits <= 1: off.
+    float *partial;
+    int splits, split_stages;
+    int tap_row_inner;   // tap t = (column step)*TR + (row step) instead of (row step)*TS + (column step)
+    int tap_inner;       // reduction order (Ci % BKT == 0 only): 1 = all taps of a channel block before the next block
+    // applied to the accumulators before the store (all optional)
+    const float *bias;   // + bias[co]
+    int relu;            // max(0, .)
+    const bf16_t *mask;  // indexed like `out`: the stored value is 0 where mask <= 0
+};
+
+// stream.hip: the same GEMM for short reductions and few output columns (see there); whether it can run p,
+// and the launch over all rows (both take p as a launch site fills it: the fields the launcher derives -
+// M, row range, tile counts, byte sizes, linear_out, tap_inner - are ignored and recomputed).
+bool stream_applicable(const IgemmParams &p);
+int stream_launch(const IgemmParams &p, hipStream_t st);
 
 // ---- prep.hip: re-packing for channel counts that are not a multiple of 8 ---------
 // [rows][C] -> [rows][C8] (C8 = C rounded up to 8, new channels zero); bf16 only.

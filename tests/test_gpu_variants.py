@@ -2,7 +2,8 @@
 checked against the oracle: each implicit-GEMM shape in both reduction orders (channel-block-major needs
 C % 64 == 0, tap-major runs otherwise) for forward and backward-data on ragged and strided problems, each
 backward-weight shape with several split counts, and the two-launch plans (main shape for the whole rounds,
-a smaller shape for the remaining rows).  The test asserts that the forced shape is the one that ran."""
+a smaller shape for the remaining rows), and the streaming kernel for short reductions on the geometries
+its row bookkeeping and epilogue distinguish.  The test asserts that the forced shape is the one that ran."""
 import os
 
 import numpy as np
@@ -98,3 +99,62 @@ PAIRS = [
 def test_two_launch_plans(mxc, oracle, main, tail, dims):
     with forced("MXC_FORCE_VARIANT", main + "+" + tail):
         _check(mxc, oracle, dims, ("fwd",), main + "+" + tail)
+
+
+# The streaming kernel (filter tile resident on chip, persistent workgroups): 1x1 and short 3x3 reductions;
+# column tiles of 32 / 64 / 128 with ragged last tiles and more than one column tile; images smaller than a
+# row tile (a tile spans several images), strides and padding (row positions advance with wraps), reductions
+# that end inside a stage; backward-data at stride 2 writes one residue class per launch.
+STREAM_SHAPES = [
+    (3, 64, 29, 31, 64, 1, 1, 1, 0),
+    (2, 192, 28, 28, 96, 1, 1, 1, 0),
+    (5, 256, 7, 7, 40, 1, 1, 1, 0),
+    (2, 64, 30, 30, 264, 1, 1, 1, 0),
+    (2, 128, 27, 27, 128, 1, 1, 2, 0),
+    (2, 8, 33, 35, 64, 3, 3, 1, 1),
+    (2, 16, 19, 23, 32, 3, 3, 2, 1),
+    (70, 24, 5, 3, 16, 3, 3, 1, 1),
+    (1, 72, 57, 57, 24, 1, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("dims", STREAM_SHAPES)
+def test_stream_kernel(mxc, oracle, dims):
+    with forced("MXC_FORCE_VARIANT", "igemm_stream"):
+        _check(mxc, oracle, dims, ("fwd", "bwd_data"), "igemm_stream")
+
+
+def test_stream_kernel_epilogue(mxc, oracle):
+    """bias + ReLU on the forward output and the ReLU-derivative mask on the backward-data output, both applied
+    by the streaming kernel's epilogue."""
+    dims = (3, 64, 26, 22, 96, 1, 1, 1, 0)
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy = gen.random_case(77, *dims, dtype="bf16", dist="normal")
+    bias = np.linspace(-1.0, 1.0, K).astype(np.float32)
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    with forced("MXC_FORCE_VARIANT", "igemm_stream"):
+        y = torch.empty(N * K * H * W, dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, run._in(x), run._in(w), torch.from_numpy(bias).cuda(), 1, y, run._ws(mxc.MXC_FWD))
+        assert mxc.mxc_last_variant().split(":")[-1] == "igemm_stream"
+        ref, den = oracle.conv2d_fwd_bias_act(x, w, bias, True, st, pad)
+        got = run._out(y, (N, K, H, W))
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True))
+        dx = torch.empty(N * C * H * W, dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_bwd_data_relu(*dims, run.dt, run.lay, run._in(dy), run._in(w), run._in(x), dx, run._ws(mxc.MXC_BWD_DATA_RELU))
+        assert mxc.mxc_last_variant().split(":")[-1] == "igemm_stream"
+        ref, den = oracle.conv2d_bwd_data_relu(dy, w, x, st, pad)
+        got = run._out(dx, (N, C, H, W))
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True))
+        assert np.all(got[x <= 0] == 0)
+
+
+def test_stream_kernel_declines_long_reductions(mxc, oracle):
+    """A filter tile that does not fit on chip: the forced name is ignored and a tile of the other kernel runs."""
+    dims = (2, 256, 12, 12, 128, 3, 3, 1, 1)
+    x, w, dy = gen.random_case(5, *dims, dtype="bf16", dist="normal")
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    with forced("MXC_FORCE_VARIANT", "igemm_stream"):
+        got = run.fwd(x, w)
+    assert "stream" not in mxc.mxc_last_variant()
+    ref, den = oracle.conv2d_fwd(x, w, 1, 1), oracle.conv2d_fwd(np.abs(x), np.abs(w), 1, 1)
+    assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True))
