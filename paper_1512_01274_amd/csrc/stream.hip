@@ -32,7 +32,6 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 constexpr unsigned OOB = 0x80000000u;   // a buffer offset no operand reaches: the load returns zeros
 constexpr int BK = 64;                  // reduction elements per stage
-constexpr int NS = 3;                   // ring stages
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
@@ -54,9 +53,9 @@ struct StreamParams {
     int d_n, d_a, d_b;   // one row tile further = d_n images + d_a rows + d_b columns of the output grid (d_a < Mh, d_b < Mw)
 };
 
-// NC compute waves (row tile BM = 32*NC), NL loader waves, column tile BN (32, 64 or 128).
+// NC compute waves (row tile BM = 32*NC), NL loader waves, column tile BN (32, 64 or 128), NS ring stages.
 // Dynamic LDS: [filter BN x KT*64][ring NS x BM x 64][staging NC x 32 x min(BN,64)][tap table].
-template <int NC, int NL, int BN>
+template <int NC, int NL, int BN, int NS>
 __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamParams sp)
 {
     const IgemmParams &p = sp.g;
@@ -66,6 +65,7 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
     constexpr int STG_A = BM * BK;                  // elements per ring stage
     constexpr int EW = BN < 64 ? BN : 64;           // staging width (columns)
     static_assert(BM % (8 * NL) == 0 && NL % 2 == 0, "loader split");
+    static_assert(NS >= 3 && A_LD * (NS - 1) < 64, "ring depth against the range of the load counter");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     bf16_t *sB = reinterpret_cast<bf16_t *>(smem);
@@ -325,30 +325,44 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
     }
 }
 
-struct StreamConfig { int nc, nl, bn, lds; bool ok; };
+struct StreamConfig { int nc, ns, bn, lds; bool ok; };
 
-// Column tile: the smallest of 32 / 64 / 128 that holds min(Co, 128); row tile 256 (8 compute + 4 loader waves)
-// when filter, ring and staging fit the CU's 160 KB of LDS, else 128 (4 + 2 waves).
-StreamConfig stream_config(const IgemmParams &p)
+// LDS bytes of a configuration: resident filter tile, ring, per-wave staging, tap table
+long long stream_lds(int nc, int ns, int bn, int KT)
 {
-    StreamConfig c{0, 0, 0, 0, false};
-    const int Kd = p.TR * p.TS * p.Ci, KT = (Kd + BK - 1) / BK;
-    const int bn = p.Co <= 32 ? 32 : p.Co <= 64 ? 64 : 128;
     const int ew = bn < 64 ? bn : 64;
-    const long long b_bytes = (long long)bn * KT * BK * 2;
-    for (int nc : {8, 4}) {
-        const long long lds = b_bytes + (long long)NS * 32 * nc * BK * 2 + (long long)nc * 32 * ew * 2 + 128 * 8;
-        if (lds <= 160 * 1024) return StreamConfig{nc, nc / 2, bn, (int)lds, true};
-    }
-    return c;
+    return (long long)bn * KT * BK * 2 + (long long)ns * 32 * nc * BK * 2 + (long long)nc * 32 * ew * 2 + (MAX_TAPS + 1) * 8;
 }
 
-template <int NC, int NL, int BN>
+// The forms the kernel is built in, (compute waves, ring stages), in the order of preference measured on 1x1
+// layers of 56x56 and 28x28 images: eight compute waves where the filter tile leaves room for their ring (the
+// epilogue of a tile - conversion, staging, stores - is shared by more waves), else four with a deeper ring.
+// MXC_STREAM_SHAPE=<compute waves>x<stages> (tuning sweeps only) picks one.
+const int kForms[][2] = {{8, 3}, {4, 4}, {4, 3}};
+
+// Column tile: the smallest of 32 / 64 / 128 that holds min(Co, 128).
+StreamConfig stream_config(const IgemmParams &p)
+{
+    const int Kd = p.TR * p.TS * p.Ci, KT = (Kd + BK - 1) / BK;
+    const int bn = p.Co <= 32 ? 32 : p.Co <= 64 ? 64 : 128;
+    int want_nc = 0, want_ns = 0;
+    if (const char *f = getenv("MXC_STREAM_SHAPE")) {
+        if (sscanf(f, "%dx%d", &want_nc, &want_ns) != 2) want_nc = want_ns = 0;
+    }
+    for (const auto &f : kForms) {
+        if (want_nc && (f[0] != want_nc || f[1] != want_ns)) continue;
+        const long long lds = stream_lds(f[0], f[1], bn, KT);
+        if (lds <= 160 * 1024) return StreamConfig{f[0], f[1], bn, (int)lds, true};
+    }
+    return StreamConfig{0, 0, 0, 0, false};
+}
+
+template <int NC, int NL, int BN, int NS>
 int launch_stream(StreamParams sp, int lds, hipStream_t st)
 {
     static bool attr_set = false;      // raising the dynamic-LDS limit is idempotent; racing threads set the same value
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_kernel<NC, NL, BN>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_kernel<NC, NL, BN, NS>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 160 * 1024) != hipSuccess)
             return MXC_ERR_LAUNCH;
         attr_set = true;
@@ -357,8 +371,9 @@ int launch_stream(StreamParams sp, int lds, hipStream_t st)
     constexpr int BM = 32 * NC;
     p.m_tiles = (int)(((long long)p.m_end - p.m_begin + BM - 1) / BM);
     p.n_tiles = (p.Co + BN - 1) / BN;
-    // persistent grid: one workgroup per CU (two for the 6-wave form when LDS allows), shared by the column tiles
-    const int per_cu = (NC == 4 && lds * 2 <= 160 * 1024) ? 2 : 1;
+    // persistent grid: as many workgroups per CU as the LDS holds (at most 12 waves), shared by the column tiles
+    int per_cu = (160 * 1024) / lds;
+    if (per_cu > 12 / (NC + NL)) per_cu = 12 / (NC + NL);
     int n_wg_m = (256 * per_cu) / p.n_tiles;
     if (n_wg_m < 1) n_wg_m = 1;
     if (n_wg_m > p.m_tiles) n_wg_m = p.m_tiles;
@@ -371,8 +386,16 @@ int launch_stream(StreamParams sp, int lds, hipStream_t st)
     sp.d_n = BM / (p.Mh * p.Mw);
     sp.d_a = BM % (p.Mh * p.Mw) / p.Mw;
     sp.d_b = BM % p.Mw;
-    hipLaunchKernelGGL((stream_kernel<NC, NL, BN>), dim3((unsigned)(8 * sp.per_xcd)), dim3(64 * (NC + NL)), (size_t)lds, st, sp);
+    hipLaunchKernelGGL((stream_kernel<NC, NL, BN, NS>), dim3((unsigned)(8 * sp.per_xcd)), dim3(64 * (NC + NL)), (size_t)lds, st, sp);
     return hipGetLastError() == hipSuccess ? MXC_OK : MXC_ERR_LAUNCH;
+}
+
+template <int NC, int NL, int NS>
+int launch_stream_bn(const StreamParams &sp, const StreamConfig &c, hipStream_t st)
+{
+    if (c.bn == 32) return launch_stream<NC, NL, 32, NS>(sp, c.lds, st);
+    if (c.bn == 64) return launch_stream<NC, NL, 64, NS>(sp, c.lds, st);
+    return launch_stream<NC, NL, 128, NS>(sp, c.lds, st);
 }
 
 }  // namespace
@@ -406,14 +429,9 @@ int stream_launch(const IgemmParams &p, hipStream_t st)
     const int Kd = p.TR * p.TS * p.Ci;
     sp.KT = (Kd + BK - 1) / BK;
     sp.b_bytes = c.bn * sp.KT * BK * 2;
-    if (c.nc == 8) {
-        if (c.bn == 32) return launch_stream<8, 4, 32>(sp, c.lds, st);
-        if (c.bn == 64) return launch_stream<8, 4, 64>(sp, c.lds, st);
-        return launch_stream<8, 4, 128>(sp, c.lds, st);
-    }
-    if (c.bn == 32) return launch_stream<4, 2, 32>(sp, c.lds, st);
-    if (c.bn == 64) return launch_stream<4, 2, 64>(sp, c.lds, st);
-    return launch_stream<4, 2, 128>(sp, c.lds, st);
+    if (c.nc == 8) return launch_stream_bn<8, 4, 3>(sp, c, st);
+    if (c.ns == 4) return launch_stream_bn<4, 2, 4>(sp, c, st);
+    return launch_stream_bn<4, 2, 3>(sp, c, st);
 }
 
 }  // namespace mxc

@@ -3,7 +3,7 @@ stride-1 backward-data) and of the backward-weight kernel for the layers of the 
 writes the winners into csrc/tuned_igemm.inc / csrc/tuned_wgrad.inc, which the library consults
 before its time model.  Run on an MI355X, then rebuild:
 
-    python -m paper_1512_01274_amd.tune [--iters 8] [--workloads alexnet_b128,vgg_a_b64,...]
+    python -m paper_1512_01274_amd.tune [--iters 8] [--workloads alexnet_b128,vgg_a_b64,...] [--out-dir DIR]
     python -m paper_1512_01274_amd.build
 
 Candidates are forced through the library's own tuning hooks (MXC_FORCE_VARIANT=<main>[+<tail>],
@@ -44,10 +44,11 @@ def ceil_div(a, b):
 
 
 def igemm_candidates(M, Co):
-    """Single shapes whose column tile is not mostly padding, and main+tail pairs where the main shape has
-    at least one whole round and leaves rows over."""
+    """Single shapes whose column tile is not mostly padding, main+tail pairs where the main shape has
+    at least one whole round and leaves rows over, and the streaming kernel (the library declines it where
+    the filter tile does not fit on chip; such a timing is discarded)."""
     ok = [n for n, (bm, bn, _) in IGEMM_TILES.items() if bn <= 2 * max(Co, 32) and (bn <= 64 or bn * 3 <= Co * 4 or bn <= Co)]
-    out = list(ok)
+    out = list(ok) + mxc.mxc_tile_names(2)
     for a in ok:
         bm, bn, slots = IGEMM_TILES[a]
         tiles = ceil_div(M, bm) * ceil_div(Co, bn)
@@ -107,6 +108,8 @@ def tune_layer(L, timer, igemm_rows, wgrad_rows, log):
         try:
             ws = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *dims, dt, lay))
             t = timer.time(lambda: fn(ws))
+            if val.split("/")[0] not in mxc.mxc_last_variant():
+                t = float("inf")            # the library ran something else: this candidate cannot run the problem
         except mxc.MxcError:
             t = float("inf")
         finally:
@@ -139,8 +142,8 @@ def tune_layer(L, timer, igemm_rows, wgrad_rows, log):
         wgrad_rows[(L.N, L.H, L.W, L.C, L.K, L.R, L.S, L.stride, L.pad)] = (tile, int(sp), t)
 
 
-def write_tables(igemm_rows, wgrad_rows):
-    with open(os.path.join(HERE, "csrc", "tuned_igemm.inc"), "w") as f:
+def write_tables(igemm_rows, wgrad_rows, out_dir):
+    with open(os.path.join(out_dir, "tuned_igemm.inc"), "w") as f:
         f.write("// Measured best plans of the implicit-GEMM kernels, one line per GEMM (rows M, output columns Co, reduction\n"
                 "// length Kd): the shape for the whole rounds and, where a second launch pays, the shape for the rest.\n"
                 "// Written by `python -m paper_1512_01274_amd.tune` from timings on an MI355X; GEMMs not listed here are\n"
@@ -150,7 +153,7 @@ def write_tables(igemm_rows, wgrad_rows):
         for (M, Co, Kd), (main, tail, t) in sorted(igemm_rows.items()):
             f.write(f"    {{{M}, {Co}, {Kd}, \"{main}\", \"{tail}\"}},   // {t:.1f} us\n")
         f.write("};\n")
-    with open(os.path.join(HERE, "csrc", "tuned_wgrad.inc"), "w") as f:
+    with open(os.path.join(out_dir, "tuned_wgrad.inc"), "w") as f:
         f.write("// Measured best tile and split count of the backward-weight kernel, one line per layer geometry\n"
                 "// (N, H, W, C, K, R, S, stride, pad of the plain NHWC problem).  Written by\n"
                 "// `python -m paper_1512_01274_amd.tune` from timings on an MI355X; other geometries are planned by the\n"
@@ -165,10 +168,13 @@ def write_tables(igemm_rows, wgrad_rows):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=8)
-    ap.add_argument("--workloads", default="alexnet_b128,inception3a_b128,vgg_a_b64,resnet_bottleneck_b256")
+    ap.add_argument("--workloads", default="alexnet_b128,inception3a_b128,vgg_a_b64,resnet_bottleneck_b256,alexnet_b32,vgg_a_b32")
     ap.add_argument("--log", default="")
+    ap.add_argument("--out-dir", default=os.path.join(HERE, "csrc"), help="where the two .inc tables are written")
     args = ap.parse_args()
     assert torch.cuda.is_available(), "tuning needs the GPU"
+    assert set(IGEMM_TILES) == set(mxc.mxc_tile_names(0)) and set(WGRAD_TILES) == set(mxc.mxc_tile_names(1)), \
+        "the tile tables of this script and of the library differ"
     out = open(args.log, "w") if args.log else sys.stdout
 
     def log(s):
@@ -181,7 +187,7 @@ def main():
         for L in cfg.layers:
             tune_layer(L, timer, igemm_rows, wgrad_rows, log)
             torch.cuda.empty_cache()
-    write_tables(igemm_rows, wgrad_rows)
+    write_tables(igemm_rows, wgrad_rows, args.out_dir)
     log(f"wrote {len(igemm_rows)} igemm and {len(wgrad_rows)} wgrad entries")
 
 

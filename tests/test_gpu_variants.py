@@ -124,6 +124,15 @@ def test_stream_kernel(mxc, oracle, dims):
         _check(mxc, oracle, dims, ("fwd", "bwd_data"), "igemm_stream")
 
 
+# every form the streaming kernel is built in (compute waves x ring stages), on problems whose filter tile
+# fits beside the deepest ring
+@pytest.mark.parametrize("form", ["4x4", "8x3", "4x3"])
+@pytest.mark.parametrize("dims", [STREAM_SHAPES[i] for i in (0, 5, 6, 7, 8)])
+def test_stream_kernel_forms(mxc, oracle, dims, form):
+    with forced("MXC_FORCE_VARIANT", "igemm_stream"), forced("MXC_STREAM_SHAPE", form):
+        _check(mxc, oracle, dims, ("fwd", "bwd_data"), "igemm_stream")
+
+
 def test_stream_kernel_epilogue(mxc, oracle):
     """bias + ReLU on the forward output and the ReLU-derivative mask on the backward-data output, both applied
     by the streaming kernel's epilogue."""
