@@ -7,7 +7,9 @@ backward-weight (with its split reduction) through the C ABI with activations re
 filters in KRSC.  Inputs are generated from a seed on the host and are resident in HBM before the timed
 region.  Backward-data reads filters prepared once per weight version (mxc_conv2d_bwd_data_prepare_filter,
 outside the timed region: the weights do not change between the steps of this benchmark; the cost of
-preparing them every step is reported in `filter_prepare_ms_per_step`).
+preparing them every step is reported in `filter_prepare_ms_per_step`).  A first layer (C = 3) packs its
+input once per step, inside the timed region, into a buffer that its forward and its backward-weight both
+read (mxc_conv2d_prepare_input); --raw-filter turns both kinds of prepared operands off.
 
 Two schedules of the same calls are timed:
   * "single_stream": every call in program order on one stream, launched eagerly.  This is the headline
@@ -93,6 +95,14 @@ class LayerState:
         self.w_prepared = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_BWD_DATA_FILTER, *self.dims, self.dt, self.lay))
         self.prepare_filter = lambda: mxc.mxc_conv2d_bwd_data_prepare_filter(*self.dims, self.dt, self.lay, self.w, self.w_prepared)
         self.prepare_filter()
+        # first layers (C = 3): forward packs x once into a buffer that backward-weight reads too
+        self.x_prepared = None
+        if layout == "nhwc":
+            nb = mxc.mxc_conv2d_workspace_bytes(mxc.MXC_INPUT_PREPARED, *self.dims, self.dt, self.lay)
+            if nb:
+                self.x_prepared = mxc.alloc_workspace(nb)
+                for op in (mxc.MXC_FWD_PREPARED_INPUT, mxc.MXC_BWD_WEIGHT_PREPARED_INPUT):
+                    self.ws[op] = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *self.dims, self.dt, self.lay))
 
 
 class Network:
@@ -110,6 +120,27 @@ class Network:
                                                           s.ws[m.MXC_BWD_DATA_PREPARED])
         return lambda: m.mxc_conv2d_bwd_data(*s.dims, s.dt, s.lay, s.dy, s.w, s.dx, s.ws[m.MXC_BWD_DATA])
 
+    def fwd_thunk(self, s, x, bias=None, relu=0):
+        """Forward of layer s on x; a layer with a prepared input form packs its own x here, once per step."""
+        m = self.mxc
+        if self.prepared and s.x_prepared is not None and x is s.x:
+            def fn():
+                m.mxc_conv2d_prepare_input(*s.dims, s.dt, s.lay, x, s.x_prepared)
+                m.mxc_conv2d_fwd_prepared_input(*s.dims, s.dt, s.lay, s.x_prepared, s.w, bias, relu, s.y,
+                                                s.ws[m.MXC_FWD_PREPARED_INPUT])
+            return fn
+        if bias is None and not relu:
+            return lambda: m.mxc_conv2d_fwd(*s.dims, s.dt, s.lay, x, s.w, s.y, s.ws[m.MXC_FWD])
+        return lambda: m.mxc_conv2d_fwd_bias_act(*s.dims, s.dt, s.lay, x, s.w, bias, relu, s.y, s.ws[m.MXC_FWD])
+
+    def wgrad_thunk(self, s, x, dy):
+        """Backward-weight of layer s; reads what fwd_thunk prepared when there is such a form."""
+        m = self.mxc
+        if self.prepared and s.x_prepared is not None and x is s.x:
+            return lambda: m.mxc_conv2d_bwd_weight_prepared_input(*s.dims, s.dt, s.lay, s.x_prepared, dy, s.dw, m.MXC_F32,
+                                                                  s.ws[m.MXC_BWD_WEIGHT_PREPARED_INPUT])
+        return lambda: m.mxc_conv2d_bwd_weight(*s.dims, s.dt, s.lay, x, dy, s.dw, s.ws[m.MXC_BWD_WEIGHT])
+
     def calls(self):
         """(label, op, layer, thunk) for every ABI call of one step, in program order."""
         m = self.mxc
@@ -120,11 +151,9 @@ class Network:
             out.append(("layout", "layout", s0, lambda: m.mxc_layout_convert(
                 L0.N, L0.C, L0.H, L0.W, s0.dt, m.MXC_NCHW, m.MXC_NHWC, s0.x_nchw, s0.x)))
         for s in self.layers:
-            out.append((s.L.name, "fwd", s, lambda s=s: m.mxc_conv2d_fwd(
-                *s.dims, s.dt, s.lay, s.x, s.w, s.y, s.ws[m.MXC_FWD])))
+            out.append((s.L.name, "fwd", s, self.fwd_thunk(s, s.x)))
             out.append((s.L.name, "bwd_data", s, self._bwd_data(s)))
-            out.append((s.L.name, "bwd_weight", s, lambda s=s: m.mxc_conv2d_bwd_weight(
-                *s.dims, s.dt, s.lay, s.x, s.dy, s.dw, s.ws[m.MXC_BWD_WEIGHT])))
+            out.append((s.L.name, "bwd_weight", s, self.wgrad_thunk(s, s.x, s.dy)))
         return out
 
     def grouped_calls(self):
@@ -135,8 +164,7 @@ class Network:
         for c in self.calls():
             label, op, s, fn = c
             if op == "fwd":
-                out.append((label, op, s, lambda s=s: m.mxc_conv2d_fwd_bias_act(
-                    *s.dims, s.dt, s.lay, s.x, s.w, s.bias, 1, s.y, s.ws[m.MXC_FWD])))
+                out.append((label, op, s, self.fwd_thunk(s, s.x, s.bias, 1)))
             elif op == "bwd_data":
                 out.append((label, op, s, lambda s=s: m.mxc_conv2d_bwd_data_relu(
                     *s.dims, s.dt, s.lay, s.dy, s.w, s.x, s.dx, s.ws[m.MXC_BWD_DATA_RELU])))
@@ -171,9 +199,9 @@ def chained_grouped_step(net):
     if net.layout == "nhwc":
         calls.append(lambda: m.mxc_layout_convert(s0.L.N, s0.L.C, s0.L.H, s0.L.W, s0.dt, m.MXC_NCHW, m.MXC_NHWC, s0.x_nchw, s0.x))
     for s in layers:
-        calls.append(lambda s=s: m.mxc_conv2d_fwd_bias_act(*s.dims, s.dt, s.lay, x_of[id(s)], s.w, s.bias, 1, s.y, s.ws[m.MXC_FWD]))
+        calls.append(net.fwd_thunk(s, x_of[id(s)], s.bias, 1))
     for s in reversed(layers):
-        calls.append(lambda s=s: m.mxc_conv2d_bwd_weight(*s.dims, s.dt, s.lay, x_of[id(s)], dy_of[id(s)], s.dw, s.ws[m.MXC_BWD_WEIGHT]))
+        calls.append(net.wgrad_thunk(s, x_of[id(s)], dy_of[id(s)]))
         calls.append(lambda s=s: m.mxc_bias_grad(s.L.N, s.L.K, s.L.P, s.L.Q, s.dt, s.lay, dy_of[id(s)], s.db, s.ws[m.MXC_BIAS_GRAD]))
         calls.append(lambda s=s: m.mxc_conv2d_bwd_data_relu(*s.dims, s.dt, s.lay, dy_of[id(s)], s.w, x_of[id(s)], s.dx,
                                                             s.ws[m.MXC_BWD_DATA_RELU]))

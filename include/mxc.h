@@ -65,7 +65,11 @@ enum { MXC_FWD = 0, MXC_BWD_DATA = 1, MXC_BWD_WEIGHT = 2,
        MXC_BWD_DATA_FILTER = 5,          /* bytes of the prepared filter of mxc_conv2d_bwd_data_prepare_filter */
        MXC_BWD_DATA_PREPARED = 6,        /* workspace of mxc_conv2d_bwd_data_prepared without x_mask           */
        MXC_BWD_DATA_PREPARED_RELU = 7,   /* ... with x_mask                                                     */
-       MXC_BWD_WEIGHT_BF16 = 8 };        /* workspace of mxc_conv2d_bwd_weight_bf16                             */
+       MXC_BWD_WEIGHT_BF16 = 8,          /* workspace of mxc_conv2d_bwd_weight_bf16                             */
+       MXC_INPUT_PREPARED = 9,           /* bytes of the prepared input of mxc_conv2d_prepare_input (0: none)   */
+       MXC_FWD_PREPARED_INPUT = 10,      /* workspace of mxc_conv2d_fwd_prepared_input                          */
+       MXC_BWD_WEIGHT_PREPARED_INPUT = 11,       /* workspace of mxc_conv2d_bwd_weight_prepared_input, fp32 dw  */
+       MXC_BWD_WEIGHT_PREPARED_INPUT_BF16 = 12 };/* ... bf16 dw                                                 */
 
 /*
  * Forward (the layer's "forward" evaluation, paper Section 2.1):
@@ -184,6 +188,36 @@ int mxc_conv2d_bwd_data_prepared(int N, int C, int H, int W, int K, int R, int S
                                  int dtype, int layout,
                                  const void *dy, const void *w_prepared, size_t prepared_bytes, const void *x_mask, void *dx,
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Forward and backward-weight on an input prepared once.  Layers whose channel count is not a multiple of 8
+ * (the first layer of every network of Section 4: C = 3) first bring x into the form their kernels read -
+ * space-to-depth packed for strided filters, zero-bordered with 4 channels per pixel, or channel-padded -
+ * and both passes of a training step (Section 2.1: forward, then the gradient of the weights) read the same
+ * form of the same x:
+ *   mxc_conv2d_prepare_input             writes that form into x_prepared (device memory of the caller, at least
+ *       mxc_conv2d_workspace_bytes(MXC_INPUT_PREPARED, ...) bytes, 16-byte aligned; opaque contents, valid for
+ *       exactly these N..pad, dtype and layout until x changes).  A layer that reads x as it is has 0 bytes:
+ *       the call does nothing (x_prepared may be NULL) and the two calls below take x itself as x_prepared;
+ *   mxc_conv2d_fwd_prepared_input        is mxc_conv2d_fwd_bias_act (bias may be NULL, relu 0 or 1) reading
+ *       x_prepared; same results bit for bit.  Workspace: query MXC_FWD_PREPARED_INPUT;
+ *   mxc_conv2d_bwd_weight_prepared_input is mxc_conv2d_bwd_weight (dw_dtype MXC_F32) or mxc_conv2d_bwd_weight_bf16
+ *       (dw_dtype MXC_BF16) reading x_prepared; same results bit for bit.  Workspace: query
+ *       MXC_BWD_WEIGHT_PREPARED_INPUT / MXC_BWD_WEIGHT_PREPARED_INPUT_BF16.
+ * layout must be MXC_NHWC (MXC_ERR_UNSUPPORTED otherwise: the NCHW boundary converts every operand per call).
+ * prepared_bytes: size of the x_prepared buffer (checked: MXC_ERR_WORKSPACE).  Everything else as the calls named.
+ */
+int mxc_conv2d_prepare_input(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             int dtype, int layout,
+                             const void *x, void *x_prepared, size_t prepared_bytes, void *hip_stream);
+int mxc_conv2d_fwd_prepared_input(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                  int dtype, int layout,
+                                  const void *x_prepared, size_t prepared_bytes, const void *w, const float *bias, int relu,
+                                  void *y, void *workspace, size_t workspace_bytes, void *hip_stream);
+int mxc_conv2d_bwd_weight_prepared_input(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                         int dtype, int layout,
+                                         const void *x_prepared, size_t prepared_bytes, const void *dy, void *dw, int dw_dtype,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Gradient of the bias of mxc_conv2d_fwd_bias_act (derivative of forward + bias[k] in bias):

@@ -78,14 +78,31 @@ ConvShape with_channels(const ConvShape &s, int C)
     return t;
 }
 
+// How forward and backward-weight get their input.  Layers whose channel count is not a multiple of 8 first
+// bring x into the form their GEMM reads (space-to-depth packed, zero-bordered with 4 channels per pixel, or
+// channel-padded), the same form for both passes; a caller that runs both on one x can have that done once
+// (INPUT_PREPARE_ONLY fills a buffer of the caller's, nothing else runs) and hand the buffer to both
+// (INPUT_PREPARED).  The form is carved from `xws` - the ordinary workspace in INPUT_RAW mode, the caller's
+// buffer in the other two.  Layers that read x as it is have an empty prepared form.
+enum InputMode { INPUT_RAW = 0, INPUT_PREPARE_ONLY = 1, INPUT_PREPARED = 2 };
+enum InputForm { FORM_AS_IS = 0, FORM_S2D = 1, FORM_SMALLC = 2, FORM_CHANPAD = 3 };
+struct InputPrep {
+    Carver *xws = nullptr;
+    InputMode mode = INPUT_RAW;
+    int *form = nullptr;       // out: the InputForm the pass reads (the two passes must agree before they share a buffer)
+};
+inline void note_form(const InputPrep &ip, int form) { if (ip.form) *ip.form = form; }
+
 int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *y, const PostOp &post, Carver &ws, hipStream_t st,
-             bool dry)
+             bool dry, const InputPrep &ip = InputPrep())
 {
     const char *v = "";
+    Carver &xws = ip.xws ? *ip.xws : ws;
+    const bool pack = ip.mode != INPUT_PREPARED, run = ip.mode != INPUT_PREPARE_ONLY;
     if (dtype == MXC_BF16 && s.C % 8 == 0 && igemm_fwd_supported(s)) {
-        const size_t split_bytes = igemm_fwd_split_bytes(s);
+        const size_t split_bytes = run ? igemm_fwd_split_bytes(s) : 0;
         void *split_ws = split_bytes ? ws.take(split_bytes) : nullptr;
-        if (dry) return MXC_OK;
+        if (dry || !run) return MXC_OK;
         const int rc = igemm_fwd(s, x, w, y, st, &v, post, split_ws);
         set_variant("fwd", v);
         return rc;
@@ -93,9 +110,12 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
     if (dtype == MXC_BF16 && s2d_applicable(s) && igemm_fwd_supported(s2d_shape(s))) {
         // strided first layer: space-to-depth turns it into a stride-1 problem with stride^2*C channels
         const ConvShape s2 = s2d_shape(s);
-        void *x2 = ws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2), *w2 = ws.take((size_t)s2.K * s2.R * s2.S * s2.C * 2);
+        note_form(ip, FORM_S2D);
+        void *x2 = xws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2);
+        void *w2 = run ? ws.take((size_t)s2.K * s2.R * s2.S * s2.C * 2) : nullptr;
         if (dry) return MXC_OK;
-        MXC_TRY(s2d_pack_x(s, x, x2, st));
+        if (pack) MXC_TRY(s2d_pack_x(s, x, x2, st));
+        if (!run) return MXC_OK;
         MXC_TRY(s2d_pack_w(s, w, w2, st));
         const int rc = igemm_fwd(s2, x2, w2, y, st, &v, post);
         set_variant("fwd", (std::string("s2d+") + v).c_str());
@@ -104,9 +124,12 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
     if (dtype == MXC_BF16 && s.C <= 4 && igemm_fwd_smallc_supported(s)) {
         // first-layer style: zero-bordered image with 4 or 8 channels per pixel, filter rows as runs
         const SmallCGeom g = smallc_geom(s);
-        void *xp = ws.take((size_t)s.N * g.Hp * g.Wp * g.pix * 2), *wp = ws.take((size_t)s.K * s.R * g.run * 2);
+        note_form(ip, FORM_SMALLC);
+        void *xp = xws.take((size_t)s.N * g.Hp * g.Wp * g.pix * 2);
+        void *wp = run ? ws.take((size_t)s.K * s.R * g.run * 2) : nullptr;
         if (dry) return MXC_OK;
-        MXC_TRY(smallc_pack_x(s, x, xp, st));
+        if (pack) MXC_TRY(smallc_pack_x(s, x, xp, st));
+        if (!run) return MXC_OK;
         MXC_TRY(smallc_pack_w(s, w, wp, st));
         const int rc = igemm_fwd_smallc(s, xp, wp, y, st, &v, post);
         set_variant("fwd", (std::string("smallc+") + v).c_str());
@@ -115,15 +138,18 @@ int fwd_nhwc(const ConvShape &s, int dtype, const void *x, const void *w, void *
     const int C8 = (s.C + 7) / 8 * 8;
     if (dtype == MXC_BF16 && s.C % 8 != 0 && igemm_fwd_supported(with_channels(s, C8))) {
         // other channel counts: zero-pad the channels of x and w to a multiple of 8
-        void *xp = ws.take((size_t)s.N * s.H * s.W * C8 * 2), *wp = ws.take((size_t)s.K * s.R * s.S * C8 * 2);
+        note_form(ip, FORM_CHANPAD);
+        void *xp = xws.take((size_t)s.N * s.H * s.W * C8 * 2);
+        void *wp = run ? ws.take((size_t)s.K * s.R * s.S * C8 * 2) : nullptr;
         if (dry) return MXC_OK;
-        MXC_TRY(pad_channels(x, xp, (long long)s.N * s.H * s.W, s.C, st));
+        if (pack) MXC_TRY(pad_channels(x, xp, (long long)s.N * s.H * s.W, s.C, st));
+        if (!run) return MXC_OK;
         MXC_TRY(pad_channels(w, wp, (long long)s.K * s.R * s.S, s.C, st));
         const int rc = igemm_fwd(with_channels(s, C8), xp, wp, y, st, &v, post);
         set_variant("fwd", (std::string("chanpad+") + v).c_str());
         return rc;
     }
-    if (dry) return MXC_OK;
+    if (dry || !run) return MXC_OK;
     set_variant("fwd", "direct");
     return direct_fwd(s, dtype, x, w, y, st, post);
 }
@@ -189,10 +215,14 @@ int bwd_data_nhwc(const ConvShape &s, int dtype, const void *dy, const void *w, 
     return direct_bwd_data(s, dtype, dy, mode == FILTER_PREPARED ? wc : w, dx, st, post);
 }
 
+// ip: see InputMode (the forms are those of fwd_nhwc, chosen by the same tests in the same order; only
+// INPUT_RAW and INPUT_PREPARED reach this function)
 int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy, void *dw, bool dw_bf16, Carver &ws,
-                    hipStream_t st, bool dry)
+                    hipStream_t st, bool dry, const InputPrep &ip = InputPrep())
 {
     const char *v = "";
+    Carver &xws = ip.xws ? *ip.xws : ws;
+    const bool pack = ip.mode != INPUT_PREPARED;
     if (dtype == MXC_BF16 && s.C % 8 == 0 && wgrad_supported(wgrad_geom_plain(s))) {
         const WgradGeom g = wgrad_geom_plain(s);
         float *partial = (float *)ws.take(wgrad_workspace(g));
@@ -204,10 +234,11 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
     if (dtype == MXC_BF16 && s2d_applicable(s) && wgrad_supported(wgrad_geom_s2d(s))) {
         const ConvShape s2 = s2d_shape(s);
         const WgradGeom g = wgrad_geom_s2d(s);
-        void *x2 = ws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2);
+        note_form(ip, FORM_S2D);
+        void *x2 = xws.take((size_t)s2.N * s2.H * s2.W * s2.C * 2);
         float *partial = (float *)ws.take(wgrad_workspace(g));
         if (dry) return MXC_OK;
-        MXC_TRY(s2d_pack_x(s, x, x2, st));
+        if (pack) MXC_TRY(s2d_pack_x(s, x, x2, st));
         const int rc = wgrad(g, x2, dy, dw, dw_bf16, partial, st, &v);
         set_variant("bwd_weight", (std::string("s2d+") + v).c_str());
         return rc;
@@ -215,20 +246,22 @@ int bwd_weight_nhwc(const ConvShape &s, int dtype, const void *x, const void *dy
     if (dtype == MXC_BF16 && s.C <= 4 && wgrad_supported(wgrad_geom_smallc(s))) {
         const SmallCGeom sg = smallc_geom(s);
         const WgradGeom g = wgrad_geom_smallc(s);
-        void *xp = ws.take((size_t)s.N * sg.Hp * sg.Wp * sg.pix * 2);
+        note_form(ip, FORM_SMALLC);
+        void *xp = xws.take((size_t)s.N * sg.Hp * sg.Wp * sg.pix * 2);
         float *partial = (float *)ws.take(wgrad_workspace(g));
         if (dry) return MXC_OK;
-        MXC_TRY(smallc_pack_x(s, x, xp, st));
+        if (pack) MXC_TRY(smallc_pack_x(s, x, xp, st));
         const int rc = wgrad(g, xp, dy, dw, dw_bf16, partial, st, &v);
         set_variant("bwd_weight", (std::string("smallc+") + v).c_str());
         return rc;
     }
     if (dtype == MXC_BF16 && s.C % 8 != 0 && wgrad_supported(wgrad_geom_chanpad(s))) {
         const WgradGeom g = wgrad_geom_chanpad(s);
-        void *xp = ws.take((size_t)s.N * s.H * s.W * g.pix * 2);
+        note_form(ip, FORM_CHANPAD);
+        void *xp = xws.take((size_t)s.N * s.H * s.W * g.pix * 2);
         float *partial = (float *)ws.take(wgrad_workspace(g));
         if (dry) return MXC_OK;
-        MXC_TRY(pad_channels(x, xp, (long long)s.N * s.H * s.W, s.C, st));
+        if (pack) MXC_TRY(pad_channels(x, xp, (long long)s.N * s.H * s.W, s.C, st));
         const int rc = wgrad(g, xp, dy, dw, dw_bf16, partial, st, &v);
         set_variant("bwd_weight", (std::string("chanpad+") + v).c_str());
         return rc;
@@ -475,6 +508,101 @@ int mxc_conv2d_bwd_data_prepared(int N, int C, int H, int W, int K, int R, int S
     return run_pass(MXC_BWD_DATA, s, dtype, layout, dy, nullptr, dx, post, ws, (hipStream_t)hip_stream, false, &fws, FILTER_PREPARED);
 }
 
+namespace mxc {
+namespace {
+
+// Size and kind of the prepared input of a layer.  Forward and backward-weight must read the same form to share
+// a buffer; for a shape where they would not (one of them falls back to another kernel family) the prepared
+// form is empty, like that of a layer that reads x as it is, and each pass packs for itself as usual.
+int prepared_input_plan(const ConvShape &s, int dtype, size_t *bytes, int *form)
+{
+    Carver none(nullptr), xf(nullptr), xw(nullptr);
+    int form_f = FORM_AS_IS, form_w = FORM_AS_IS;
+    InputPrep ipf, ipw;
+    ipf.xws = &xf; ipf.mode = INPUT_PREPARE_ONLY; ipf.form = &form_f;
+    ipw.xws = &xw; ipw.mode = INPUT_PREPARED; ipw.form = &form_w;
+    MXC_TRY(fwd_nhwc(s, dtype, nullptr, nullptr, nullptr, PostOp(), none, nullptr, true, ipf));
+    MXC_TRY(bwd_weight_nhwc(s, dtype, nullptr, nullptr, nullptr, false, none, nullptr, true, ipw));
+    const bool shared = form_f == form_w && xf.used == xw.used;
+    *bytes = shared ? xf.used : 0;
+    *form = shared ? form_f : FORM_AS_IS;
+    return MXC_OK;
+}
+
+}  // namespace
+}  // namespace mxc
+
+int mxc_conv2d_prepare_input(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                             const void *x, void *x_prepared, size_t prepared_bytes, void *hip_stream)
+{
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (layout != MXC_NHWC) return MXC_ERR_UNSUPPORTED;
+    if (!x) return MXC_ERR_NULL;
+    if (misaligned(x) || misaligned(x_prepared)) return MXC_ERR_ALIGN;
+    size_t need = 0;
+    int form = FORM_AS_IS;
+    MXC_TRY(prepared_input_plan(s, dtype, &need, &form));
+    if (need == 0) return MXC_OK;          // the layer reads x as it is
+    if (!x_prepared) return MXC_ERR_NULL;
+    if (prepared_bytes < need) return MXC_ERR_WORKSPACE;
+    Carver none(nullptr), xws(x_prepared);
+    InputPrep ip;
+    ip.xws = &xws; ip.mode = INPUT_PREPARE_ONLY;
+    return fwd_nhwc(s, dtype, x, nullptr, nullptr, PostOp(), none, (hipStream_t)hip_stream, false, ip);
+}
+
+int mxc_conv2d_fwd_prepared_input(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                                  const void *x_prepared, size_t prepared_bytes, const void *w, const float *bias, int relu,
+                                  void *y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (layout != MXC_NHWC || (relu != 0 && relu != 1)) return MXC_ERR_UNSUPPORTED;
+    if (!x_prepared || !w || !y) return MXC_ERR_NULL;
+    if (misaligned(x_prepared) || misaligned(w) || misaligned(y) || misaligned(workspace) || ((uintptr_t)bias & 3u)) return MXC_ERR_ALIGN;
+    size_t needx = 0;
+    int form = FORM_AS_IS;
+    MXC_TRY(prepared_input_plan(s, dtype, &needx, &form));
+    if (prepared_bytes < needx) return MXC_ERR_WORKSPACE;
+    PostOp post;
+    post.bias = bias;
+    post.relu = relu;
+    InputPrep ip;
+    Carver need(nullptr), nx(nullptr);
+    if (needx) { ip.xws = &nx; ip.mode = INPUT_PREPARED; }
+    MXC_TRY(fwd_nhwc(s, dtype, nullptr, nullptr, nullptr, PostOp(), need, nullptr, true, ip));
+    if (need.used > 0 && (!workspace || workspace_bytes < need.used)) return MXC_ERR_WORKSPACE;
+    Carver ws(workspace), xws(const_cast<void *>(x_prepared));
+    if (needx) ip.xws = &xws;
+    // an empty prepared form: x_prepared is x itself
+    return fwd_nhwc(s, dtype, needx ? nullptr : x_prepared, w, y, post, ws, (hipStream_t)hip_stream, false, ip);
+}
+
+int mxc_conv2d_bwd_weight_prepared_input(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype,
+                                         int layout, const void *x_prepared, size_t prepared_bytes, const void *dy, void *dw,
+                                         int dw_dtype, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (layout != MXC_NHWC || (dw_dtype != MXC_F32 && dw_dtype != MXC_BF16) || (dw_dtype == MXC_BF16 && dtype != MXC_BF16))
+        return MXC_ERR_UNSUPPORTED;
+    if (!x_prepared || !dy || !dw) return MXC_ERR_NULL;
+    if (misaligned(x_prepared) || misaligned(dy) || misaligned(dw) || misaligned(workspace)) return MXC_ERR_ALIGN;
+    size_t needx = 0;
+    int form = FORM_AS_IS;
+    MXC_TRY(prepared_input_plan(s, dtype, &needx, &form));
+    if (prepared_bytes < needx) return MXC_ERR_WORKSPACE;
+    InputPrep ip;
+    Carver need(nullptr), nx(nullptr);
+    if (needx) { ip.xws = &nx; ip.mode = INPUT_PREPARED; }
+    MXC_TRY(bwd_weight_nhwc(s, dtype, nullptr, nullptr, nullptr, dw_dtype == MXC_BF16, need, nullptr, true, ip));
+    if (need.used > 0 && (!workspace || workspace_bytes < need.used)) return MXC_ERR_WORKSPACE;
+    Carver ws(workspace), xws(const_cast<void *>(x_prepared));
+    if (needx) ip.xws = &xws;
+    return bwd_weight_nhwc(s, dtype, needx ? nullptr : x_prepared, dy, dw, dw_dtype == MXC_BF16, ws, (hipStream_t)hip_stream, false, ip);
+}
+
 int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout, const void *dy, float *db, void *workspace,
                   size_t workspace_bytes, void *hip_stream)
 {
@@ -541,13 +669,27 @@ int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int 
                                int dtype, int layout, size_t *out_bytes)
 {
     if (!out_bytes) return MXC_ERR_NULL;
-    if (pass < MXC_FWD || pass > MXC_BWD_WEIGHT_BF16) return MXC_ERR_UNSUPPORTED;
+    if (pass < MXC_FWD || pass > MXC_BWD_WEIGHT_PREPARED_INPUT_BF16) return MXC_ERR_UNSUPPORTED;
     if (pass == MXC_BWD_WEIGHT_BF16 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
     ConvShape s;
     const int rc = validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s);
     if (rc != MXC_OK) return rc;
     if (pass == MXC_BIAS_GRAD) {
         *out_bytes = align_up((size_t)bias_grad_parts(s.N, s.K, (long long)s.P * s.Q, layout) * s.K * sizeof(float), 256);
+        return MXC_OK;
+    }
+    if (pass >= MXC_INPUT_PREPARED) {
+        if (layout != MXC_NHWC || (pass == MXC_BWD_WEIGHT_PREPARED_INPUT_BF16 && dtype != MXC_BF16)) return MXC_ERR_UNSUPPORTED;
+        size_t needx = 0;
+        int form = FORM_AS_IS;
+        MXC_TRY(prepared_input_plan(s, dtype, &needx, &form));
+        if (pass == MXC_INPUT_PREPARED) { *out_bytes = needx; return MXC_OK; }
+        InputPrep ip;
+        Carver needw(nullptr), nx(nullptr);
+        if (needx) { ip.xws = &nx; ip.mode = INPUT_PREPARED; }
+        if (pass == MXC_FWD_PREPARED_INPUT) MXC_TRY(fwd_nhwc(s, dtype, nullptr, nullptr, nullptr, PostOp(), needw, nullptr, true, ip));
+        else MXC_TRY(bwd_weight_nhwc(s, dtype, nullptr, nullptr, nullptr, pass == MXC_BWD_WEIGHT_PREPARED_INPUT_BF16, needw, nullptr, true, ip));
+        *out_bytes = needw.used;
         return MXC_OK;
     }
     Carver need(nullptr), needf(nullptr);

@@ -17,6 +17,7 @@ MXC_F32, MXC_BF16 = 0, 1
 MXC_NCHW, MXC_NHWC = 0, 1
 MXC_FWD, MXC_BWD_DATA, MXC_BWD_WEIGHT, MXC_BWD_DATA_RELU, MXC_BIAS_GRAD = 0, 1, 2, 3, 4
 MXC_BWD_DATA_FILTER, MXC_BWD_DATA_PREPARED, MXC_BWD_DATA_PREPARED_RELU, MXC_BWD_WEIGHT_BF16 = 5, 6, 7, 8
+MXC_INPUT_PREPARED, MXC_FWD_PREPARED_INPUT, MXC_BWD_WEIGHT_PREPARED_INPUT, MXC_BWD_WEIGHT_PREPARED_INPUT_BF16 = 9, 10, 11, 12
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmxc.so")
 if not os.path.exists(LIB_PATH):
@@ -34,6 +35,12 @@ _lib.mxc_conv2d_bwd_data_prepare_filter.argtypes = [_I] * 11 + [_VP, _VP, _SZ, _
 _lib.mxc_conv2d_bwd_data_prepare_filter.restype = _I
 _lib.mxc_conv2d_bwd_data_prepared.argtypes = [_I] * 11 + [_VP, _VP, _SZ, _VP, _VP, _VP, _SZ, _VP]
 _lib.mxc_conv2d_bwd_data_prepared.restype = _I
+_lib.mxc_conv2d_prepare_input.argtypes = [_I] * 11 + [_VP, _VP, _SZ, _VP]
+_lib.mxc_conv2d_prepare_input.restype = _I
+_lib.mxc_conv2d_fwd_prepared_input.argtypes = [_I] * 11 + [_VP, _SZ, _VP, _VP, _I, _VP, _VP, _SZ, _VP]
+_lib.mxc_conv2d_fwd_prepared_input.restype = _I
+_lib.mxc_conv2d_bwd_weight_prepared_input.argtypes = [_I] * 11 + [_VP, _SZ, _VP, _VP, _I, _VP, _SZ, _VP]
+_lib.mxc_conv2d_bwd_weight_prepared_input.restype = _I
 _lib.mxc_conv2d_workspace_bytes.argtypes = [_I] * 12 + [ctypes.POINTER(_SZ)]
 _lib.mxc_conv2d_workspace_bytes.restype = _I
 _lib.mxc_layout_convert.argtypes = [_I] * 7 + [_VP, _VP, _VP]
@@ -199,6 +206,36 @@ def mxc_conv2d_bwd_data_prepared(N, C, H, W, K, R, S, stride, pad, dtype, layout
     rc = _lib.mxc_conv2d_bwd_data_prepared(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(dy), _ptr(w_prepared),
                                            w_prepared.numel() * w_prepared.element_size(), _ptr(x_mask), _ptr(dx), ws_ptr, ws_bytes,
                                            _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def mxc_conv2d_prepare_input(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, x_prepared, stream=None):
+    rc = _lib.mxc_conv2d_prepare_input(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(x), _ptr(x_prepared),
+                                       _nbytes(x_prepared), _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_conv2d_fwd_prepared_input(N, C, H, W, K, R, S, stride, pad, dtype, layout, x_prepared, w, bias, relu, y, workspace=None,
+                                  stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_conv2d_fwd_prepared_input(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(x_prepared), _nbytes(x_prepared),
+                                            _ptr(w), _ptr(bias), int(relu), _ptr(y), ws_ptr, ws_bytes, _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_conv2d_bwd_weight_prepared_input(N, C, H, W, K, R, S, stride, pad, dtype, layout, x_prepared, dy, dw, dw_dtype,
+                                         workspace=None, stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_conv2d_bwd_weight_prepared_input(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(x_prepared),
+                                                   _nbytes(x_prepared), _ptr(dy), _ptr(dw), dw_dtype, ws_ptr, ws_bytes,
+                                                   _stream(stream))
     if rc != MXC_OK:
         raise MxcError(rc)
 

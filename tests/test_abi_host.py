@@ -124,6 +124,41 @@ def test_workspace_query_over_random_shapes(mxc):
                     assert sizes[mxc.MXC_BWD_DATA_PREPARED] + sizes[mxc.MXC_BWD_DATA_FILTER] >= sizes[mxc.MXC_BWD_DATA], dims
 
 
+def test_prepared_input_sizes_and_validation(mxc):
+    """Host logic of the prepared-input calls: layers that read x as it is have an empty prepared form, first
+    layers (C = 3) have one in each packing, with it a call needs no more scratch than without (the packed copy
+    moved out of the workspace), NCHW is refused, and bad buffers are reported before any launch."""
+    import ctypes as ct
+    lib = mxc.raw()
+    out = ct.c_size_t(0)
+    q = lambda p, dims, dt=mxc.MXC_BF16, lay=mxc.MXC_NHWC: mxc.mxc_conv2d_workspace_bytes(p, *dims, dt, lay)
+    plain = (2, 64, 14, 14, 32, 3, 3, 1, 1)
+    assert q(mxc.MXC_INPUT_PREPARED, plain) == 0
+    assert q(mxc.MXC_FWD_PREPARED_INPUT, plain) == q(mxc.MXC_FWD, plain)
+    assert q(mxc.MXC_BWD_WEIGHT_PREPARED_INPUT, plain) == q(mxc.MXC_BWD_WEIGHT, plain)
+    assert q(mxc.MXC_INPUT_PREPARED, plain, mxc.MXC_F32) == 0
+    for dims in [(2, 3, 67, 67, 16, 11, 11, 4, 2), (2, 3, 30, 30, 16, 3, 3, 1, 1), (2, 20, 12, 12, 16, 3, 3, 1, 1)]:
+        px = q(mxc.MXC_INPUT_PREPARED, dims)
+        assert px > 0 and px % 256 == 0, dims
+        assert q(mxc.MXC_FWD_PREPARED_INPUT, dims) + px == q(mxc.MXC_FWD, dims), dims
+        assert q(mxc.MXC_BWD_WEIGHT_PREPARED_INPUT, dims) + px == q(mxc.MXC_BWD_WEIGHT, dims), dims
+        assert q(mxc.MXC_BWD_WEIGHT_PREPARED_INPUT_BF16, dims) + px == q(mxc.MXC_BWD_WEIGHT_BF16, dims), dims
+        for p in (mxc.MXC_INPUT_PREPARED, mxc.MXC_FWD_PREPARED_INPUT, mxc.MXC_BWD_WEIGHT_PREPARED_INPUT):
+            assert lib.mxc_conv2d_workspace_bytes(p, *dims, mxc.MXC_BF16, mxc.MXC_NCHW, ct.byref(out)) == mxc.MXC_ERR_UNSUPPORTED
+        big = 1 << 30
+        assert lib.mxc_conv2d_prepare_input(*dims, 1, 1, 4096, None, big, None) == mxc.MXC_ERR_NULL
+        assert lib.mxc_conv2d_prepare_input(*dims, 1, 1, 4096, 8192, px - 1, None) == mxc.MXC_ERR_WORKSPACE
+        assert lib.mxc_conv2d_prepare_input(*dims, 1, 0, 4096, 8192, big, None) == mxc.MXC_ERR_UNSUPPORTED
+        assert lib.mxc_conv2d_fwd_prepared_input(*dims, 1, 1, 4096, px - 1, 8192, None, 0, 16384, 32768, big, None) == mxc.MXC_ERR_WORKSPACE
+        assert lib.mxc_conv2d_fwd_prepared_input(*dims, 1, 1, 4096, px, 8192, None, 2, 16384, 32768, big, None) == mxc.MXC_ERR_UNSUPPORTED
+        assert lib.mxc_conv2d_bwd_weight_prepared_input(*dims, 1, 1, 4096, px - 1, 8192, 16384, 0, 32768, big, None) == mxc.MXC_ERR_WORKSPACE
+        assert lib.mxc_conv2d_bwd_weight_prepared_input(*dims, 1, 1, 4096, px, 8192, 16384, 7, 32768, big, None) == mxc.MXC_ERR_UNSUPPORTED
+        assert lib.mxc_conv2d_bwd_weight_prepared_input(*dims, 1, 1, None, px, 8192, 16384, 0, 32768, big, None) == mxc.MXC_ERR_NULL
+    # the bf16 weight gradient exists for bf16 operands only
+    assert lib.mxc_conv2d_workspace_bytes(mxc.MXC_BWD_WEIGHT_PREPARED_INPUT_BF16, *plain, mxc.MXC_F32, mxc.MXC_NHWC, ct.byref(out)) \
+        == mxc.MXC_ERR_UNSUPPORTED
+
+
 def test_nchw_limits_are_reported_before_any_launch(mxc):
     """NCHW operands go through batched transposes with int row/column counts: what those cannot run is refused by the
     shape check itself (the size query sees it too), while the same problem in NHWC is accepted; batch and filter

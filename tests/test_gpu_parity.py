@@ -334,6 +334,61 @@ def test_prepared_filter_backward_data(mxc, oracle, dims, dtype, layout):
     assert np.all(np.abs(a - ref) <= util.tight_bound(ref, den, dtype, dtype == "bf16")), dims
 
 
+PREPARED_INPUT_SHAPES = [
+    (2, 3, 67, 67, 16, 11, 11, 4, 2),      # space-to-depth packing (stride 4)
+    (2, 3, 33, 35, 24, 7, 7, 2, 3),        # space-to-depth packing (stride 2)
+    (2, 3, 30, 30, 16, 3, 3, 1, 1),        # zero-bordered, 4 channels per pixel
+    (2, 20, 12, 12, 16, 3, 3, 1, 1),       # channel padding
+    (2, 16, 12, 12, 24, 3, 3, 1, 1),       # read as it is: empty prepared form
+    (2, 5, 9, 9, 7, 3, 3, 1, 1),           # the two passes use different kernel families: nothing to share, empty form
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dims", PREPARED_INPUT_SHAPES)
+def test_prepared_input_forward_and_backward_weight(mxc, oracle, dims, dtype):
+    """Forward (+bias, ReLU) and backward-weight (fp32 and bf16 dw) from one prepared input: bit-identical to the
+    ordinary entry points on repeated use of the buffer, and within the parity bound of the oracle."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy, bias = _fused_case(dims, dtype, (hash(dims) & 0xFFFF) + 9)
+    run = util.Runner(mxc, dims, dtype, "nhwc")
+    P, Q = run.P, run.Q
+    d_x, d_w, d_dy, d_b = run._in(x), run._in(w), run._in(dy), torch.from_numpy(bias).cuda()
+    nbytes = mxc.mxc_conv2d_workspace_bytes(mxc.MXC_INPUT_PREPARED, *dims, run.dt, run.lay)
+    assert (nbytes == 0) == (dtype == "f32" or C % 8 == 0 or K % 8 != 0), dims
+    prepared = mxc.alloc_workspace(nbytes) if nbytes else None
+    mxc.mxc_conv2d_prepare_input(*dims, run.dt, run.lay, d_x, prepared)
+    xp = prepared if nbytes else d_x
+    as_bits = lambda t: t.view({2: torch.int16, 4: torch.int32}[t.element_size()])
+    want = torch.full((N * K * P * Q,), float("nan"), dtype=run.tdtype, device="cuda")
+    mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, d_x, d_w, d_b, 1, want, run._ws(mxc.MXC_FWD))
+    for _ in range(2):
+        got = torch.full_like(want, float("nan"))
+        mxc.mxc_conv2d_fwd_prepared_input(*dims, run.dt, run.lay, xp, d_w, d_b, 1, got, run._ws(mxc.MXC_FWD_PREPARED_INPUT))
+        torch.cuda.synchronize()
+        assert torch.equal(as_bits(got), as_bits(want)), (dims, dtype, mxc.mxc_last_variant())
+    ref, den = oracle.conv2d_fwd_bias_act(x, w, bias, True, st, pad)
+    a = run._out(got, (N, K, P, Q))
+    assert np.all(np.abs(a - ref) <= util.tight_bound(ref, den, dtype, dtype == "bf16")), dims
+    cases = [(mxc.MXC_F32, torch.float32, mxc.mxc_conv2d_bwd_weight, mxc.MXC_BWD_WEIGHT, mxc.MXC_BWD_WEIGHT_PREPARED_INPUT)]
+    if dtype == "bf16":
+        cases.append((mxc.MXC_BF16, torch.bfloat16, mxc.mxc_conv2d_bwd_weight_bf16, mxc.MXC_BWD_WEIGHT_BF16,
+                      mxc.MXC_BWD_WEIGHT_PREPARED_INPUT_BF16))
+    for dw_dt, tdt, plain_fn, op_plain, op_prep in cases:
+        want = torch.full((K * R * S * C,), float("nan"), dtype=tdt, device="cuda")
+        plain_fn(*dims, run.dt, run.lay, d_x, d_dy, want, run._ws(op_plain))
+        for _ in range(2):
+            got = torch.full_like(want, float("nan"))
+            mxc.mxc_conv2d_bwd_weight_prepared_input(*dims, run.dt, run.lay, xp, d_dy, got, dw_dt, run._ws(op_prep))
+            torch.cuda.synchronize()
+            assert torch.equal(as_bits(got), as_bits(want)), (dims, dtype, dw_dt, mxc.mxc_last_variant())
+        if dw_dt == mxc.MXC_F32:
+            ref = oracle.conv2d_bwd_weight(x, dy, w.shape, st, pad)
+            den = oracle.conv2d_bwd_weight(np.abs(x), np.abs(dy), w.shape, st, pad)
+            a = util.nhwc_to_nchw(got.cpu().numpy().astype(np.float64).reshape(K, R, S, C))
+            assert util.metric(a, ref, den) <= util.TOL[dtype], (dims, mxc.mxc_last_variant())
+
+
 @pytest.mark.parametrize("cfg_idx", [1, 3])
 def test_grouped_operations_network_layers(mxc, oracle, cfg_idx):
     """The bench's launch configuration (bf16, NHWC) on every layer of the AlexNet- and VGG-style stacks, batch 2."""
