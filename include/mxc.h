@@ -314,6 +314,12 @@ int mxc_version(void);
  * the tuning script and the tests walk the list.  Static host memory. */
 const char *mxc_tile_name(int family, int index);
 
+/* Tuning aid: the implicit GEMM (rows M, output columns Co, reduction length Kd) that the calling thread's last
+ * forward or backward-data call planned - for first layers that is the GEMM on the packed operands, whose
+ * dimensions the caller does not otherwise see.  The tuning script keys its table of measured plans on it.
+ * All three are 0 before any such call.  Host only. */
+void mxc_last_plan_key(long long *M, int *Co, int *Kd);
+
 /* Measurement aid (not part of the convolution path): enqueues one launch of a
  * register-resident loop of bf16 matrix instructions (v_mfma_f32_32x32x16_bf16, fp32
  * accumulate, no memory traffic) on `workgroups` workgroups of 256 threads, `iters`

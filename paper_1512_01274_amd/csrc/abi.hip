@@ -744,6 +744,16 @@ const char *mxc_status_string(int status)
 
 const char *mxc_last_variant(void) { return g_variant; }
 
+void mxc_last_plan_key(long long *M, int *Co, int *Kd)
+{
+    long long m = 0;
+    int co = 0, kd = 0;
+    igemm_last_plan_key(&m, &co, &kd);
+    if (M) *M = m;
+    if (Co) *Co = co;
+    if (Kd) *Kd = kd;
+}
+
 int mxc_version(void) { return 200; }
 
 const char *mxc_tile_name(int family, int index)

@@ -627,8 +627,12 @@ double model_time(const TileChoice &t, long long M, int Co, int KT, double fixed
 // measured best plans (tuned_igemm.inc, written by the tuning script from timings on the device) when it
 // holds this GEMM; else the least modelled time over single shapes and main+tail pairs.
 // allow_stream = false: callers that need a tile of this file's kernel (split reductions, in-place filters).
+thread_local long long g_key_M = 0;
+thread_local int g_key_Co = 0, g_key_Kd = 0;
+
 Plan choose_plan(long long M, int Co, int Kd, bool allow_stream = true)
 {
+    g_key_M = M; g_key_Co = Co; g_key_Kd = Kd;
     if (const char *f = getenv("MXC_FORCE_VARIANT")) {
         const char *plus = strchr(f, '+');
         const int a = tile_index(f, plus ? (size_t)(plus - f) : strlen(f));
@@ -829,6 +833,7 @@ int launch_split(int tc, IgemmParams p, long long M, int sp, void *split_ws, voi
 
 const char *igemm_tile_name(int index) { return index >= 0 && index < N_TILE_CHOICES ? kTiles[index].name : nullptr; }
 const char *igemm_stream_name(int index) { return index == 0 ? kStreamName : nullptr; }
+void igemm_last_plan_key(long long *M, int *Co, int *Kd) { *M = g_key_M; *Co = g_key_Co; *Kd = g_key_Kd; }
 
 size_t igemm_bwd_data_split_bytes(const ConvShape &s)
 {

@@ -143,6 +143,8 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w2, vo
 // names of the tile shapes the two MFMA kernel families are built in (nullptr past the last)
 const char *igemm_tile_name(int index);
 const char *igemm_stream_name(int index);   // names of the streaming kernel's plans (one)
+// key (rows, output columns, reduction length) of the calling thread's last implicit-GEMM plan lookup
+void igemm_last_plan_key(long long *M, int *Co, int *Kd);
 const char *wgrad_tile_name(int index);
 
 // ---- the implicit GEMM as its kernels see it (igemm.hip, stream.hip) ----------------------------------
@@ -219,6 +221,7 @@ int igemm_fwd_smallc(const ConvShape &s, const void *xp, const void *wp, void *y
 // (r/s2d, s/s2d) at channel ((r%s2d)*s2d + s%s2d)*Cq + c.
 struct WgradGeom {
     int N, H, W, pix, K, P, Q, stride, pad, TR, TS, run, R, S, C, col_r, col_s, s2d, Cq;
+    int oH, oW, ostride, opad;   // the caller's problem (with N, C, K, R, S: the key of the measured-plan table)
 };
 WgradGeom wgrad_geom_s2d(const ConvShape &s);       // x already packed by s2d_pack_x
 WgradGeom wgrad_geom_plain(const ConvShape &s);     // C % 8 == 0

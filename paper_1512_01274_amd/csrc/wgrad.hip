@@ -468,8 +468,8 @@ Plan make_plan(const WgradGeom &g)
         if (forced >= 0 && slash) forced_splits = atoi(slash + 1);
     } else {
         for (const TunedWgrad &e : kTunedWgrad)
-            if (e.N == g.N && e.H == g.H && e.W == g.W && e.C == g.pix && e.C == g.run && e.K == g.K && e.R == g.TR && e.S == g.TS &&
-                e.stride == g.stride && e.pad == g.pad && g.s2d == 1) {
+            if (e.N == g.N && e.H == g.oH && e.W == g.oW && e.C == g.C && e.K == g.K && e.R == g.R && e.S == g.S &&
+                e.stride == g.ostride && e.pad == g.opad) {
                 forced = tile_index(e.tile, strlen(e.tile));
                 forced_splits = forced >= 0 ? e.splits : 0;
                 break;
@@ -529,25 +529,25 @@ const char *wgrad_tile_name(int index) { return index >= 0 && index < N_TILES ? 
 
 WgradGeom wgrad_geom_plain(const ConvShape &s)
 {
-    return WgradGeom{s.N, s.H, s.W, s.C, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, s.C, s.R, s.S, s.C, s.S * s.C, s.C, 1, 0};
+    return WgradGeom{s.N, s.H, s.W, s.C, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, s.C, s.R, s.S, s.C, s.S * s.C, s.C, 1, 0, s.H, s.W, s.stride, s.pad};
 }
 
 WgradGeom wgrad_geom_chanpad(const ConvShape &s)
 {
     const int C8 = (s.C + 7) / 8 * 8;
-    return WgradGeom{s.N, s.H, s.W, C8, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, C8, s.R, s.S, s.C, s.S * C8, C8, 1, 0};
+    return WgradGeom{s.N, s.H, s.W, C8, s.K, s.P, s.Q, s.stride, s.pad, s.R, s.S, C8, s.R, s.S, s.C, s.S * C8, C8, 1, 0, s.H, s.W, s.stride, s.pad};
 }
 
 WgradGeom wgrad_geom_smallc(const ConvShape &s)
 {
     const SmallCGeom g = smallc_geom(s);
-    return WgradGeom{s.N, g.Hp, g.Wp, g.pix, s.K, s.P, s.Q, s.stride, 0, s.R, 1, g.run, s.R, s.S, s.C, g.run, g.pix, 1, 0};
+    return WgradGeom{s.N, g.Hp, g.Wp, g.pix, s.K, s.P, s.Q, s.stride, 0, s.R, 1, g.run, s.R, s.S, s.C, g.run, g.pix, 1, 0, s.H, s.W, s.stride, s.pad};
 }
 
 WgradGeom wgrad_geom_s2d(const ConvShape &s)
 {
     const S2DGeom g = s2d_geom(s);
-    return WgradGeom{s.N, g.H2, g.W2, g.C2, s.K, s.P, s.Q, 1, 0, g.R2, g.S2, g.C2, s.R, s.S, s.C, g.S2 * g.C2, g.C2, g.s, g.Cq};
+    return WgradGeom{s.N, g.H2, g.W2, g.C2, s.K, s.P, s.Q, 1, 0, g.R2, g.S2, g.C2, s.R, s.S, s.C, g.S2 * g.C2, g.C2, g.s, g.Cq, s.H, s.W, s.stride, s.pad};
 }
 
 bool wgrad_supported(const WgradGeom &g)

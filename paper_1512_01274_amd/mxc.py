@@ -99,8 +99,19 @@ def mxc_tile_name(family: int, index: int):
     return None if n is None else n.decode()
 
 
+_lib.mxc_last_plan_key.argtypes = [ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(_I), ctypes.POINTER(_I)]
+_lib.mxc_last_plan_key.restype = None
+
+
+def mxc_last_plan_key():
+    """(M, Co, Kd) of the implicit GEMM the last forward / backward-data call of this thread planned."""
+    m, co, kd = ctypes.c_longlong(0), _I(0), _I(0)
+    _lib.mxc_last_plan_key(ctypes.byref(m), ctypes.byref(co), ctypes.byref(kd))
+    return m.value, co.value, kd.value
+
+
 def mxc_tile_names(family: int):
-    """Names of the tile shapes of a kernel family (0: implicit GEMM, 1: backward-weight)."""
+    """Names of the tile shapes of a kernel family (0: implicit GEMM, 1: backward-weight, 2: streaming implicit GEMM)."""
     out, i = [], 0
     while True:
         n = _lib.mxc_tile_name(family, i)

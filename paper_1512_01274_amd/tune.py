@@ -116,30 +116,36 @@ def tune_layer(L, timer, igemm_rows, wgrad_rows, log):
             del os.environ[env]
         return t
 
-    plain = L.C % 8 == 0 and L.K % 8 == 0
-    if plain:
-        jobs = [("fwd", L.N * L.P * L.Q, L.K, L.R * L.S * L.C, mxc.MXC_FWD,
-                 lambda ws: mxc.mxc_conv2d_fwd(*dims, dt, lay, x, w, y, ws))]
-        if L.stride == 1:
-            jobs.append(("bwd_data", L.N * L.H * L.W, L.C, L.R * L.S * L.K, mxc.MXC_BWD_DATA,
-                         lambda ws: mxc.mxc_conv2d_bwd_data(*dims, dt, lay, dy, w, dx, ws)))
-        for name, M, Co, Kd, op, fn in jobs:
-            res = sorted((run("MXC_FORCE_VARIANT", c, op, fn), c) for c in igemm_candidates(M, Co))
-            base = timer.time(lambda: fn(mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *dims, dt, lay))))
-            log(f"{L.name:>22} {name:>9} M={M} Co={Co} Kd={Kd}: library default {base:7.1f} us; best " +
-                ", ".join(f"{c} {t:.1f}" for t, c in res[:4]))
-            t, c = res[0]
-            main, _, tail = c.partition("+")
-            igemm_rows[(M, Co, Kd)] = (main, tail, t)
-        M, RSC = L.N * L.P * L.Q, L.R * L.S * L.C
-        fn = lambda ws: mxc.mxc_conv2d_bwd_weight(*dims, dt, lay, x, dy, dw, ws)
+    # Forward and backward-data: the table is keyed on the GEMM the library plans (for first layers, the GEMM on
+    # the packed operands), which the library reports after a call.  Strided backward-data of a plain layer runs
+    # one GEMM per residue class and is planned by the model.
+    jobs = [("fwd", mxc.MXC_FWD, lambda ws: mxc.mxc_conv2d_fwd(*dims, dt, lay, x, w, y, ws))]
+    if L.stride == 1 or L.C <= 4:
+        jobs.append(("bwd_data", mxc.MXC_BWD_DATA, lambda ws: mxc.mxc_conv2d_bwd_data(*dims, dt, lay, dy, w, dx, ws)))
+    for name, op, fn in jobs:
+        base = timer.time(lambda: fn(mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *dims, dt, lay))))
+        if "igemm" not in mxc.mxc_last_variant():
+            continue
+        M, Co, Kd = mxc.mxc_last_plan_key()
+        res = sorted((run("MXC_FORCE_VARIANT", c, op, fn), c) for c in igemm_candidates(M, Co))
+        log(f"{L.name:>22} {name:>9} M={M} Co={Co} Kd={Kd}: library default {base:7.1f} us; best " +
+            ", ".join(f"{c} {t:.1f}" for t, c in res[:4]))
+        t, c = res[0]
+        if t == float("inf"):
+            continue
+        main, _, tail = c.partition("+")
+        igemm_rows[(M, Co, Kd)] = (main, tail, t)
+    M, RSC = L.N * L.P * L.Q, L.R * L.S * L.C
+    fn = lambda ws: mxc.mxc_conv2d_bwd_weight(*dims, dt, lay, x, dy, dw, ws)
+    base = timer.time(lambda: fn(mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_BWD_WEIGHT, *dims, dt, lay))))
+    if "wgrad" in mxc.mxc_last_variant():
         res = sorted((run("MXC_FORCE_WGRAD", c, mxc.MXC_BWD_WEIGHT, fn), c) for c in wgrad_candidates(L.K, RSC, M))
-        base = timer.time(lambda: fn(mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_BWD_WEIGHT, *dims, dt, lay))))
         log(f"{L.name:>22} {'wgrad':>9} K={L.K} RSC={RSC} M={M}: library default {base:7.1f} us; best " +
             ", ".join(f"{c} {t:.1f}" for t, c in res[:4]))
         t, c = res[0]
-        tile, _, sp = c.partition("/")
-        wgrad_rows[(L.N, L.H, L.W, L.C, L.K, L.R, L.S, L.stride, L.pad)] = (tile, int(sp), t)
+        if t != float("inf"):
+            tile, _, sp = c.partition("/")
+            wgrad_rows[(L.N, L.H, L.W, L.C, L.K, L.R, L.S, L.stride, L.pad)] = (tile, int(sp), t)
 
 
 def write_tables(igemm_rows, wgrad_rows, out_dir):
@@ -155,7 +161,7 @@ def write_tables(igemm_rows, wgrad_rows, out_dir):
         f.write("};\n")
     with open(os.path.join(out_dir, "tuned_wgrad.inc"), "w") as f:
         f.write("// Measured best tile and split count of the backward-weight kernel, one line per layer geometry\n"
-                "// (N, H, W, C, K, R, S, stride, pad of the plain NHWC problem).  Written by\n"
+                "// (N, H, W, C, K, R, S, stride, pad of the caller's problem).  Written by\n"
                 "// `python -m paper_1512_01274_amd.tune` from timings on an MI355X; other geometries are planned by the\n"
                 "// time model in wgrad.hip.\n"
                 "struct TunedWgrad { int N, H, W, C, K, R, S, stride, pad; const char *tile; int splits; };\n"
