@@ -26,6 +26,15 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
     return (bf16_t)(u >> 16);
 }
 
+// two values at once (v_cvt_pk_bf16_f32): `lo` in bits 0..15; the same rounding as f32_to_bf16 for finite inputs
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
+
 __device__ __forceinline__ float load_f32(const float *p) { return *p; }
 __device__ __forceinline__ float load_f32(const bf16_t *p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void store_f32(float *p, float v) { *p = v; }

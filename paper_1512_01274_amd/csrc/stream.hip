@@ -16,8 +16,8 @@
 //     tile end.
 // One workgroup barrier per stage hands a landed stage to the compute waves and a consumed slot back to the
 // loaders.  Compute wave v owns rows 32v..32v+31 of the row tile and all BN columns (v_mfma_f32_32x32x16_bf16,
-// fp32 accumulators); results leave through a per-wave LDS staging area as 16-byte stores, with the same
-// optional bias / ReLU / mask as the other kernel.
+// fp32 accumulators, which start from the bias); results leave through a per-wave LDS staging area as 16-byte
+// stores, with the same optional ReLU / mask as the other kernel.
 #include <type_traits>
 
 #include "mxc_internal.h"
@@ -54,7 +54,7 @@ struct StreamParams {
 };
 
 // NC compute waves (row tile BM = 32*NC), NL loader waves, column tile BN (32, 64 or 128), NS ring stages.
-// Dynamic LDS: [filter BN x KT*64][ring NS x BM x 64][staging NC x 32 x min(BN,64)][tap table].
+// Dynamic LDS: [filter BN x KT*64][ring NS x BM x 64][staging NC x 32 x min(BN,64)][tap table][bias BN].
 template <int NC, int NL, int BN, int NS>
 __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamParams sp)
 {
@@ -72,6 +72,7 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
     bf16_t *sA = reinterpret_cast<bf16_t *>(smem + sp.b_bytes);
     bf16_t *sE = sA + NS * STG_A;
     int2 *tap_tab = reinterpret_cast<int2 *>(sE + NC * 32 * EW);
+    float *sBias = reinterpret_cast<float *>(tap_tab + MAX_TAPS + 1);   // BN values: the bias of this column tile, or zeros
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -105,6 +106,8 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
         }
         tap_tab[t] = e;
     }
+
+    for (int c = tid; c < BN; c += 64 * NW) sBias[c] = (p.bias != nullptr && n0 + c < p.Co) ? p.bias[n0 + c] : 0.f;
 
     const buf_rsrc_t rs_in = make_buf_rsrc(p.in, p.in_bytes);
     const buf_rsrc_t rs_wm = make_buf_rsrc(p.wm, p.wm_bytes);
@@ -233,29 +236,53 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
     }
 
     // ================================= compute waves =======================================================
-    f32x16 acc[NI];
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
-
+    // The product is formed transposed, D[co][pixel] (filter fragment as the first MFMA operand): accumulator
+    // element e of a 32x32 block then belongs to pixel lane%32 and output column 8*(e/4) + 4*(lane/32) + e%4, so a
+    // lane holds runs of four neighbouring columns of one pixel - they convert two at a time
+    // (v_cvt_pk_bf16_f32) and go to the staging area eight bytes at a time.
     const int frag_row = lane & 31, frag_kg = lane >> 5;
     const int frag_swz = (frag_row >> 1) & 7;
     const bf16_t *a_base = sA + (wave * 32 + frag_row) * BK;
     const bf16_t *b_base = sB + frag_row * BK;
     bf16_t *stg = sE + wave * 32 * EW;
+    constexpr int CPR = EW / 8;                     // 16-byte chunks per staged row; chunk c of row r sits at c ^ (r % CPR)
+    constexpr int JN = EW / 32;                     // accumulator blocks per staging pass
 
-    float bias_j[NI];
+    f32x16 acc[NI];
+    // accumulators start from the bias (zeros without one): 4 columns per 16-byte read
+    auto reset_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        const int co = n0 + j * 32 + frag_row;
-        bias_j[j] = (p.bias != nullptr && co < p.Co) ? p.bias[co] : 0.f;
-    }
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const float4 b4 = *reinterpret_cast<const float4 *>(sBias + j * 32 + 8 * g4 + 4 * frag_kg);
+                acc[j][4 * g4 + 0] = b4.x; acc[j][4 * g4 + 1] = b4.y; acc[j][4 * g4 + 2] = b4.z; acc[j][4 * g4 + 3] = b4.w;
+            }
+    };
+    // fp32 -> bf16 (nearest even) of one pass of JN blocks into the staging area
+    auto stage_out = [&](int jc, auto relu_c) __attribute__((always_inline)) {
+        constexpr bool RELU = decltype(relu_c)::value;
+#pragma unroll
+        for (int jj = 0; jj < JN; ++jj) {
+            const int j = jc * JN + jj;
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                float v[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    v[t] = acc[j][4 * g4 + t];
+                    if (RELU) v[t] = fmaxf(v[t], 0.f);
+                }
+                const int c = jj * 4 + g4;
+                uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                *reinterpret_cast<uint2 *>(stg + frag_row * EW + ((c ^ (frag_row & (CPR - 1))) << 3) + 4 * frag_kg) = pk;
+            }
+        }
+    };
 
     wait_vmcnt<0>();                                // this wave's share of the filter
-#pragma unroll
-    for (int j = 0; j < NI; ++j) asm volatile("" : "+v"(bias_j[j]));   // the bias loads are awaited here, not in the loop
     wg_barrier();                                   // filter and stage 0 complete
+    reset_acc();
     int slot = 0, kt = 0, tile = 0;
     for (int g = 0; g < total; ++g) {
         const bf16_t *a_st = a_base + slot * STG_A;
@@ -268,41 +295,29 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
 #pragma unroll
             for (int j = 0; j < NI; ++j) b[j] = *reinterpret_cast<const bf16x8 *>(b_st + j * 32 * BK + pos);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[j], acc[j], 0, 0, 0);
+            for (int j = 0; j < NI; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a, acc[j], 0, 0, 0);
         }
         wait_lgkmcnt0();                            // operand reads of this slot have returned
         wg_barrier();
         slot = slot + 1 == NS ? 0 : slot + 1;
         if (++kt < KT) continue;
         kt = 0;
-        // ---- tile finished: fp32 -> bf16 (nearest even), bias / ReLU / mask, 16-byte stores -------------------
-        // accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+        // ---- tile finished: ReLU, conversion, staging, mask, 16-byte stores ---------------------------------
         const int m0 = wg_lo + tile * BM + wave * 32;
         ++tile;
 #pragma unroll
         for (int jc = 0; jc < (BN + 63) / 64; ++jc) {
-            constexpr int JN = EW / 32;             // accumulator blocks per staging pass
-#pragma unroll
-            for (int jj = 0; jj < JN; ++jj) {
-                const int j = jc * JN + jj;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float v = acc[j][e] + bias_j[j];
-                    if (p.relu) v = fmaxf(v, 0.f);
-                    stg[(8 * (e >> 2) + 4 * frag_kg + (e & 3)) * EW + jj * 32 + frag_row] = f32_to_bf16(v);
-                    acc[j][e] = 0.f;
-                }
-            }
+            if (p.relu) stage_out(jc, std::true_type{});
+            else stage_out(jc, std::false_type{});
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            constexpr int CPR = EW / 8;             // 16-byte chunks per staged row
 #pragma unroll
             for (int k = 0; k < 32 * CPR / 64; ++k) {
                 const int idx = k * 64 + lane;
                 const int r = idx / CPR, c = idx % CPR;
                 const int m = m0 + r, co = n0 + jc * 64 + c * 8;
-                uint4 v = *reinterpret_cast<const uint4 *>(stg + r * EW + c * 8);
+                uint4 v = *reinterpret_cast<const uint4 *>(stg + r * EW + ((c ^ (r & (CPR - 1))) << 3));
                 if (m < wg_hi && co < p.Co) {
                     long long pix = m;
                     if (!p.linear_out) {
@@ -322,6 +337,7 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
+        reset_acc();
     }
 }
 
@@ -331,7 +347,7 @@ struct StreamConfig { int nc, ns, bn, lds; bool ok; };
 long long stream_lds(int nc, int ns, int bn, int KT)
 {
     const int ew = bn < 64 ? bn : 64;
-    return (long long)bn * KT * BK * 2 + (long long)ns * 32 * nc * BK * 2 + (long long)nc * 32 * ew * 2 + (MAX_TAPS + 1) * 8;
+    return (long long)bn * KT * BK * 2 + (long long)ns * 32 * nc * BK * 2 + (long long)nc * 32 * ew * 2 + (MAX_TAPS + 1) * 8 + bn * 4;
 }
 
 // The forms the kernel is built in, (compute waves, ring stages), in the order of preference measured on 1x1
