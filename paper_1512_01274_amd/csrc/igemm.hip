@@ -466,7 +466,10 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
                         const uint4 mk = *reinterpret_cast<const uint4 *>(p.mask + off);
                         v = make_uint4(mask_bf16x2(v.x, mk.x), mask_bf16x2(v.y, mk.y), mask_bf16x2(v.z, mk.z), mask_bf16x2(v.w, mk.w));
                     }
-                    *reinterpret_cast<uint4 *>(p.out + off) = v;
+                    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+                    const u32x4 vv = {v.x, v.y, v.z, v.w};
+                    if (p.nt_out) __builtin_nontemporal_store(vv, reinterpret_cast<u32x4 *>(p.out + off));
+                    else *reinterpret_cast<u32x4 *>(p.out + off) = vv;
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -514,6 +517,9 @@ int launch(IgemmParams p, hipStream_t st, long long m_begin = 0, long long m_end
     // MXC_TAP_OUTER=1 (tuning only) keeps the filter's own order, all channels of a tap before the next tap
     p.tap_inner = (!BT && p.Ci % BKT == 0 && p.TR * p.TS > 1 && !tap_outer_forced) ? 1 : 0;
     p.linear_out = (p.out_mul_h == 1 && p.out_mul_w == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
+    // results of a large layer leave as non-temporal stores: the caches keep serving this kernel's operand reads
+    static const char *nt_forced = getenv("MXC_NT_OUT");                      // tuning sweeps only; read once
+    p.nt_out = nt_forced ? atoi(nt_forced) : ((long long)p.N * p.Ho * p.Wo * p.Co * 2 >= (128ll << 20) ? 1 : 0);
     if (p.splits > 1) {
         // even stage ranges; the last split may be shorter, none is empty
         const int KT = (p.TR * p.TS * p.Ci + BKT - 1) / BKT;

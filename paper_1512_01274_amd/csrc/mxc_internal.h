@@ -91,6 +91,33 @@ __device__ __forceinline__ void lds_dma16(buf_rsrc_t rsrc, unsigned byte_off, co
                  : "memory");
 }
 
+// lds_dma16 marked non-temporal: a streaming read that the caches need not keep
+__device__ __forceinline__ void lds_dma16_nt(buf_rsrc_t rsrc, unsigned byte_off, const void *lds_base_uniform)
+{
+    typedef __attribute__((address_space(3))) const void *lds_cvptr;
+    const unsigned lds_addr = (unsigned)(uintptr_t)(lds_cvptr)lds_base_uniform;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen nt lds"
+                 :
+                 : "s"(lds_addr), "v"(byte_off), "s"(rsrc)
+                 : "memory");
+}
+__device__ __forceinline__ void buffer_store16_nt(buf_rsrc_t rsrc, unsigned byte_off, uint4 v)
+{
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 d = {v.x, v.y, v.z, v.w};
+    asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen nt\n\ts_nop 0" : : "v"(d), "v"(byte_off), "s"(rsrc) : "memory");
+}
+
+// 16-byte store through a buffer resource: a lane whose byte_off lies beyond the resource's size writes nothing,
+// which takes the place of a bounds branch.  (The wait state after it covers the rule that the data registers
+// of a store wider than 8 bytes are not overwritten by the very next instruction.)
+__device__ __forceinline__ void buffer_store16(buf_rsrc_t rsrc, unsigned byte_off, uint4 v)
+{
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 d = {v.x, v.y, v.z, v.w};
+    asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen\n\ts_nop 0" : : "v"(d), "v"(byte_off), "s"(rsrc) : "memory");
+}
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline size_t elem_size(int dtype) { return dtype == MXC_BF16 ? 2 : 4; }
 
@@ -188,6 +215,7 @@ struct IgemmParams {
     float *partial;
     int splits, split_stages;
     int tap_row_inner;   // tap t = (column step)*TR + (row step) instead of (row step)*TS + (column step)
+    int nt_out;          // the 16-byte result stores are non-temporal
     int tap_inner;       // reduction order (Ci % BKT == 0 only): 1 = all taps of a channel block before the next block
     // applied to the accumulators before the store (all optional)
     const float *bias;   // + bias[co]

@@ -50,6 +50,8 @@ struct StreamParams {
     int units;       // n_wg_m * n_tiles (the grid is rounded up to whole XCD rounds)
     int per_xcd;     // units per XCD, a multiple of n_tiles
     int b_bytes;     // LDS bytes of the resident filter tile: BN * KT * 128
+    int nt;          // bit 0: results leave as non-temporal stores, bit 1: activations arrive as non-temporal loads
+    unsigned out_bytes;   // size of the output tensor (< 2^31)
     int d_n, d_a, d_b;   // one row tile further = d_n images + d_a rows + d_b columns of the output grid (d_a < Mh, d_b < Mw)
 };
 
@@ -205,7 +207,8 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
                 const s16x2 d = __builtin_bit_cast(s16x2, lim_hw) - hw;
                 const int bad = (__builtin_bit_cast(int, hw) | __builtin_bit_cast(int, d)) & (int)0x80008000;
                 const unsigned va = bad == 0 ? (unsigned)(a_off[i] + te.x + ci2) : OOB;
-                lds_dma16(rs_in, va, dst + (l + NL * i) * 8 * BK);
+                if (sp.nt & 2) lds_dma16_nt(rs_in, va, dst + (l + NL * i) * 8 * BK);
+                else lds_dma16(rs_in, va, dst + (l + NL * i) * 8 * BK);
             }
             if (++pf_kt == KT) {
                 pf_kt = 0;
@@ -267,41 +270,69 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
             const int j = jc * JN + jj;
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                float v[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    v[t] = acc[j][4 * g4 + t];
-                    if (RELU) v[t] = fmaxf(v[t], 0.f);
-                }
                 const int c = jj * 4 + g4;
-                uint2 pk = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                uint2 pk = make_uint2(pack_bf16x2(acc[j][4 * g4], acc[j][4 * g4 + 1]), pack_bf16x2(acc[j][4 * g4 + 2], acc[j][4 * g4 + 3]));
+                if (RELU) {                         // max(0, .) on the bf16 pairs: as 16-bit integers, negative values are < 0
+                    pk.x = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pk.x), s16x2{0, 0}));
+                    pk.y = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pk.y), s16x2{0, 0}));
+                }
                 *reinterpret_cast<uint2 *>(stg + frag_row * EW + ((c ^ (frag_row & (CPR - 1))) << 3) + 4 * frag_kg) = pk;
             }
         }
     };
 
+    // Operand fetch.  The filter is resident, so its fragments for the coming stage are requested BEFORE the
+    // barrier that publishes the stage (HB k-steps of them: all four while that fits the register budget) and
+    // arrive while the wave waits there; after the barrier only the activation fragments are fetched, all four
+    // k-steps at once, and the MFMAs run as they arrive.
+    constexpr int KS = BK / 16;
+    constexpr int HB = NI <= 2 ? KS : KS / 2;       // k-steps of filter fragments held at a time
+    bf16x8 bq[HB][NI];
+    auto fetch_b = [&](int kt_of, int ks0) __attribute__((always_inline)) {
+        const bf16_t *b_st = b_base + (size_t)kt_of * BN * BK;
+#pragma unroll
+        for (int h = 0; h < HB; ++h) {
+            const int pos = (((ks0 + h) * 2 + frag_kg) ^ frag_swz) << 3;
+#pragma unroll
+            for (int j = 0; j < NI; ++j) bq[h][j] = *reinterpret_cast<const bf16x8 *>(b_st + j * 32 * BK + pos);
+        }
+    };
+
+    // Stores of the common case (output pixel index == GEMM row, no mask): one buffer store per 8 staged rows;
+    // rows past the end of this workgroup's range and columns past Co get an offset the resource rejects.
+    const buf_rsrc_t rs_out = make_buf_rsrc(p.out, sp.out_bytes);
+    const bool fast_store = p.linear_out && p.mask == nullptr;
+    constexpr int RPI = 64 / CPR;                   // staged rows per store instruction
+    const int st_r = lane / CPR, st_c = lane % CPR;
+    const unsigned st_lane_off = (unsigned)((st_r * p.Co + n0 + st_c * 8) * 2);
+    const bf16_t *st_src = stg + st_r * EW + ((st_c ^ (st_r & (CPR - 1))) << 3);   // RPI is a multiple of CPR: same swizzle for every k
+
     wait_vmcnt<0>();                                // this wave's share of the filter
     wg_barrier();                                   // filter and stage 0 complete
     reset_acc();
     int slot = 0, kt = 0, tile = 0;
+    if (total > 0) fetch_b(0, 0);
     for (int g = 0; g < total; ++g) {
         const bf16_t *a_st = a_base + slot * STG_A;
-        const bf16_t *b_st = b_base + (size_t)kt * BN * BK;
+        bf16x8 a[KS];
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            const int pos = ((ks * 2 + frag_kg) ^ frag_swz) << 3;
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(a_st + pos);
-            bf16x8 b[NI];
+        for (int ks = 0; ks < KS; ++ks) a[ks] = *reinterpret_cast<const bf16x8 *>(a_st + (((ks * 2 + frag_kg) ^ frag_swz) << 3));
 #pragma unroll
-            for (int j = 0; j < NI; ++j) b[j] = *reinterpret_cast<const bf16x8 *>(b_st + j * 32 * BK + pos);
+        for (int h0 = 0; h0 < KS; h0 += HB) {
+            if (h0 > 0) fetch_b(kt, h0);            // second half of the stage into the same registers
 #pragma unroll
-            for (int j = 0; j < NI; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a, acc[j], 0, 0, 0);
+            for (int h = 0; h < HB; ++h)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[h][j], a[h0 + h], acc[j], 0, 0, 0);
         }
-        wait_lgkmcnt0();                            // operand reads of this slot have returned
+        // every activation fragment of this slot has been consumed by an MFMA, so its read has returned: the
+        // slot can be handed back.  The filter fragments of the next stage are requested first.
+        const int kt_next = kt + 1 == KT ? 0 : kt + 1;
+        if (g + 1 < total) fetch_b(kt_next, 0);
         wg_barrier();
         slot = slot + 1 == NS ? 0 : slot + 1;
-        if (++kt < KT) continue;
-        kt = 0;
+        kt = kt_next;
+        if (kt != 0) continue;
         // ---- tile finished: ReLU, conversion, staging, mask, 16-byte stores ---------------------------------
         const int m0 = wg_lo + tile * BM + wave * 32;
         ++tile;
@@ -312,6 +343,18 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (fast_store) {
+                const bool col_ok = n0 + jc * 64 + st_c * 8 < p.Co;
+                const unsigned tile_off = (unsigned)(m0 * p.Co * 2 + jc * 128);     // < 2^31 with the whole output
+                const int rows_left = wg_hi - m0;
+#pragma unroll
+                for (int k = 0; k < 32 / RPI; ++k) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(st_src + k * RPI * EW);
+                    const bool ok = col_ok && st_r + k * RPI < rows_left;
+                    if (sp.nt & 1) buffer_store16_nt(rs_out, ok ? st_lane_off + tile_off + (unsigned)(k * RPI * p.Co * 2) : OOB, v);
+                    else buffer_store16(rs_out, ok ? st_lane_off + tile_off + (unsigned)(k * RPI * p.Co * 2) : OOB, v);
+                }
+            } else
 #pragma unroll
             for (int k = 0; k < 32 * CPR / 64; ++k) {
                 const int idx = k * 64 + lane;
@@ -354,7 +397,7 @@ long long stream_lds(int nc, int ns, int bn, int KT)
 // layers of 56x56 and 28x28 images: eight compute waves where the filter tile leaves room for their ring (the
 // epilogue of a tile - conversion, staging, stores - is shared by more waves), else four with a deeper ring.
 // MXC_STREAM_SHAPE=<compute waves>x<stages> (tuning sweeps only) picks one.
-const int kForms[][2] = {{8, 3}, {4, 4}, {4, 3}};
+const int kForms[][2] = {{8, 3}, {4, 4}, {4, 3}, {4, 6}};
 
 // Column tile: the smallest of 32 / 64 / 128 that holds min(Co, 128).
 StreamConfig stream_config(const IgemmParams &p)
@@ -399,6 +442,14 @@ int launch_stream(StreamParams sp, int lds, hipStream_t st)
     sp.n_wg_m = n_wg_m;
     sp.units = n_wg_m * p.n_tiles;
     sp.per_xcd = ((sp.units + 7) / 8 + p.n_tiles - 1) / p.n_tiles * p.n_tiles;
+    // Cache policy, measured on 1x1 layers of 56x56 images: results of a large layer leave as non-temporal stores
+    // (the next reader finds them in HBM whatever the policy, and the caches keep serving this kernel's reads);
+    // activations that no second workgroup and no second tap will ask for arrive as non-temporal loads.
+    // MXC_STREAM_NT=<bits> (tuning sweeps only) overrides.
+    const long long in_bytes = (long long)p.N * p.Hi * p.Wi * p.pix * 2, out_bytes = (long long)p.N * p.Ho * p.Wo * p.Co * 2;
+    sp.nt = (out_bytes >= (32ll << 20) ? 1 : 0) | ((in_bytes >= (64ll << 20) && p.n_tiles == 1 && p.TR * p.TS == 1) ? 2 : 0);
+    if (const char *f = getenv("MXC_STREAM_NT")) sp.nt = atoi(f);
+    sp.out_bytes = (unsigned)((long long)p.N * p.Ho * p.Wo * p.Co * 2);
     sp.d_n = BM / (p.Mh * p.Mw);
     sp.d_a = BM % (p.Mh * p.Mw) / p.Mw;
     sp.d_b = BM % p.Mw;
@@ -421,6 +472,7 @@ bool stream_applicable(const IgemmParams &p)
     if (p.splits > 1 || p.partial != nullptr) return false;
     const int Kd = p.TR * p.TS * p.Ci;
     if ((long long)p.N * p.Mh * p.Mw >= 0x7FFF0000ll) return false;          // row indices plus a tile stay in 31 bits
+    if ((long long)p.N * p.Ho * p.Wo * p.Co * 2 >= 0x7FFF0000ll) return false;   // 32-bit byte offsets into the output
     if (Kd % 8 != 0 || p.Ci % 8 != 0 || (p.Co & 7) != 0) return false;      // 16-byte chunks within a tap's run; 16-byte stores
     if (p.TR * p.TS > MAX_TAPS) return false;
     return stream_config(p).ok;
@@ -446,6 +498,7 @@ int stream_launch(const IgemmParams &p, hipStream_t st)
     sp.KT = (Kd + BK - 1) / BK;
     sp.b_bytes = c.bn * sp.KT * BK * 2;
     if (c.nc == 8) return launch_stream_bn<8, 4, 3>(sp, c, st);
+    if (c.ns == 6) return launch_stream_bn<4, 2, 6>(sp, c, st);
     if (c.ns == 4) return launch_stream_bn<4, 2, 4>(sp, c, st);
     return launch_stream_bn<4, 2, 3>(sp, c, st);
 }
