@@ -328,7 +328,19 @@ def measure_ceilings(torch, mxc):
 
 
 def smi_clock():
-    """Shader clock as the SMI tool reports it right now (None when the tool is absent or not permitted)."""
+    """Shader clock right now: the current level of the driver's sclk table (sysfs), else what the SMI tool prints;
+    None when neither is readable.  Under a profiler no tool is spawned (its preloaded library would make the
+    child a GPU process before it starts the tool)."""
+    import glob
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        try:
+            cur = [ln.strip() for ln in open(path) if ln.strip().endswith("*")]
+            if cur:
+                return "pp_dpm_sclk " + cur[0]
+        except OSError:
+            pass
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
+        return None
     for cmd in (["rocm-smi", "--showclocks", "--json"], ["amd-smi", "metric", "--clock", "--json"]):
         try:
             r = subprocess.run(cmd, capture_output=True, text=True, timeout=10)
