@@ -277,6 +277,10 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         else lds_dma16(rs_wm, vb[Tk - A_LD], dst_b + (wave + NW * (Tk - A_LD)) * (BT ? RPLB * BN : RPL * BKT));
     };
 
+    // this thread's share of the tile's bias vector (column n0 + tid), requested now, used after the loop
+    static_assert(NT >= BN, "one bias value per thread");
+    const float bias_t = (p.bias != nullptr && tid < BN && n0 + tid < p.Co) ? p.bias[n0 + tid] : 0.f;
+
     f32x16 acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -327,7 +331,8 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         constexpr int H1 = NMF > 1 ? NMF / 2 : 1, H2 = NMF - H1 > 0 ? NMF - H1 : 1;
         static_for<NMF>([&](auto s) __attribute__((always_inline)) {
             constexpr int S = decltype(s)::value;
-            acc[S / NI][S % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[S / NI], f.b[S % NI], acc[S / NI][S % NI], 0, 0, 0);
+            // filter fragment first: the product is formed transposed, D[co][pixel] (see the epilogue)
+            acc[S / NI][S % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[S % NI], f.a[S / NI], acc[S / NI][S % NI], 0, 0, 0);
             static_for<NTASK>([&](auto t) __attribute__((always_inline)) {
                 constexpr int Tk = decltype(t)::value;
                 constexpr int slot = Tk < NFRONT ? Tk * H1 / NFRONT
@@ -394,7 +399,9 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     wait_vmcnt<0>();   // drain the zero-fill loads of the stages past the end before the tile's LDS is abandoned
 
     // ---- epilogue: fp32 -> bf16 (RNE), to the output pixels ------------------------------------
-    // accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+    // The product was formed transposed (filter fragment as the first MFMA operand): accumulator element e of a
+    // 32x32 block belongs to tile row lane%32 and column 8*(e/4) + 4*(lane/32) + e%4, so a lane holds runs of four
+    // neighbouring output columns of one pixel.
     auto out_pixel = [&](int m) __attribute__((always_inline)) -> long long {
         if (p.linear_out) return m;
         const unsigned b = (unsigned)m % (unsigned)p.Mw, t2 = (unsigned)m / (unsigned)p.Mw;
@@ -402,74 +409,114 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         return ((long long)n * p.Ho + ((int)a * p.out_mul_h + p.out_off_h)) * p.Wo + ((int)b * p.out_mul_w + p.out_off_w);
     };
     if (p.splits > 1) {
-        // split reduction: fp32 accumulators to partial[z][m][co] (row-major like the output)
+        // split reduction: fp32 accumulators to partial[z][m][co] (row-major like the output; Co % 8 == 0), 16 bytes at a time
         float *part = p.partial + (size_t)split_z * p.M * p.Co;
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i) {
+            const int m = m0 + wave_m + i * 32 + frag_row;
+            if (m >= p.m_end) continue;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
-                if (m >= p.m_end) continue;
+            for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    const int co = n0 + wave_n + j * 32 + frag_row;
-                    if (co < p.Co) part[(size_t)m * p.Co + co] = acc[i][j][e];
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int co = n0 + wave_n + j * 32 + 8 * g4 + 4 * frag_kg;
+                    if (co < p.Co)
+                        *reinterpret_cast<float4 *>(part + (size_t)m * p.Co + co) =
+                            make_float4(acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]);
                 }
-            }
+        }
         return;
     }
-    // bias of this lane's NI output columns (accumulator block j holds column j*32 + lane%32)
-    float bias_j[NI];
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        const int co = n0 + wave_n + j * 32 + frag_row;
-        bias_j[j] = (p.bias != nullptr && co < p.Co) ? p.bias[co] : 0.f;
-    }
-    auto finish = [&](float v, int j) __attribute__((always_inline)) -> bf16_t {
-        v += bias_j[j];
-        if (p.relu) v = fmaxf(v, 0.f);
-        return f32_to_bf16(v);
-    };
     if ((p.Co & 7) == 0) {
-        // Through LDS, one 32-row block of the wave tile at a time, so that global stores are 16 bytes
-        // per lane and a row's WN channels leave as one contiguous run.
+        // Through LDS, one 32-row block of the wave tile at a time, so that global stores are 16 bytes per lane and
+        // a row's WN channels leave as one contiguous run.  Staged rows are padded by 16 bytes: the 8-byte writes of
+        // 32 rows then spread over the banks.
         constexpr int CPR = WN / 8;                   // 16-byte chunks per staged row
-        constexpr int RS = 32 * WN;                   // staging elements per wave
+        constexpr int PW = WN + 8;                    // staged row pitch, elements
+        constexpr int RS = 32 * PW;                   // staging elements per wave
         constexpr bool USE_A = SZA >= SZB;
         constexpr int SZ = USE_A ? SZA : SZB;
         constexpr int WPB = SZ / RS;                  // waves whose staging fits one stage buffer
         static_assert(WPB >= 1 && NW <= WPB * NS, "epilogue staging must fit the stage buffers of one operand");
+        static_assert((USE_A ? SZB : SZA) * 2 >= BN * 4, "the bias vector must fit a stage buffer of the other operand");
         wait_lgkmcnt0();
         __syncthreads();                              // every wave is done reading operands: LDS is free
         const int bi = wave / WPB;
         bf16_t *stg = bi == 0 ? (USE_A ? sa0 : sb0) : bi == 1 ? (USE_A ? sa1 : sb1) : bi == 2 ? (USE_A ? sa2 : sb2) : (USE_A ? sa3 : sb3);
         stg += (wave % WPB) * RS;
+        float *s_bias = reinterpret_cast<float *>(USE_A ? sb0 : sa0);
+        const bool has_bias = p.bias != nullptr;
+        if (has_bias) {                               // uniform
+            if (tid < BN) s_bias[tid] = bias_t;
+            __syncthreads();
+        }
+        // conversion and staging of block (i, *): + bias, ReLU as a 16-bit integer maximum on the rounded pair
+        auto stage_block = [&](int i, auto bias_c, auto relu_c) __attribute__((always_inline)) {
+            constexpr bool BIAS = decltype(bias_c)::value, RELU = decltype(relu_c)::value;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    float v0 = acc[i][j][4 * g4], v1 = acc[i][j][4 * g4 + 1], v2 = acc[i][j][4 * g4 + 2], v3 = acc[i][j][4 * g4 + 3];
+                    if (BIAS) {
+                        const float4 b4 = *reinterpret_cast<const float4 *>(s_bias + wave_n + j * 32 + 8 * g4 + 4 * frag_kg);
+                        v0 += b4.x; v1 += b4.y; v2 += b4.z; v3 += b4.w;
+                    }
+                    uint2 pk = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+                    if (RELU) {
+                        pk.x = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pk.x), s16x2{0, 0}));
+                        pk.y = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pk.y), s16x2{0, 0}));
+                    }
+                    *reinterpret_cast<uint2 *>(stg + frag_row * PW + j * 32 + 8 * g4 + 4 * frag_kg) = pk;
+                }
+        };
+        // Common case (output pixel index == GEMM row, no mask, output below 2 GiB, a store instruction covers whole
+        // staged rows): one buffer store per 64/CPR rows; rows past the end and columns past Co get an offset the
+        // resource rejects, which takes the place of a bounds branch.
+        constexpr bool ROWS_PER_STORE_OK = 64 % CPR == 0;
+        constexpr int RPI = ROWS_PER_STORE_OK ? 64 / CPR : 1;
+        const bool fast_store = ROWS_PER_STORE_OK && p.linear_out && p.mask == nullptr && p.out_bytes != 0;
+        const buf_rsrc_t rs_out = make_buf_rsrc(p.out, p.out_bytes);
+        const int st_r = lane / CPR, st_c = lane % CPR;
+        const bool st_col_ok = n0 + wave_n + st_c * 8 < p.Co;
+        const unsigned st_lane_off = (unsigned)((st_r * p.Co + n0 + wave_n + st_c * 8) * 2);
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    stg[(8 * (e >> 2) + 4 * frag_kg + (e & 3)) * WN + j * 32 + frag_row] = finish(acc[i][j][e], j);
+            if (has_bias) { if (p.relu) stage_block(i, std::true_type{}, std::true_type{}); else stage_block(i, std::true_type{}, std::false_type{}); }
+            else { if (p.relu) stage_block(i, std::false_type{}, std::true_type{}); else stage_block(i, std::false_type{}, std::false_type{}); }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (fast_store) {
+                const int mb = m0 + wave_m + i * 32;
+                const unsigned blk_off = (unsigned)mb * (unsigned)(p.Co * 2);   // below 2^32: the output is below 2^31 and a tile adds little
+                const int rows_left = p.m_end - mb;
 #pragma unroll
-            for (int k = 0; k < 32 * CPR / 64; ++k) {
-                const int idx = k * 64 + lane;
-                const int r = idx / CPR, c = idx % CPR;
-                const int m = m0 + wave_m + i * 32 + r, co = n0 + wave_n + c * 8;
-                uint4 v = *reinterpret_cast<const uint4 *>(stg + r * WN + c * 8);
-                if (m < p.m_end && co < p.Co) {
-                    const long long off = out_pixel(m) * p.Co + co;
-                    if (p.mask != nullptr) {
-                        const uint4 mk = *reinterpret_cast<const uint4 *>(p.mask + off);
-                        v = make_uint4(mask_bf16x2(v.x, mk.x), mask_bf16x2(v.y, mk.y), mask_bf16x2(v.z, mk.z), mask_bf16x2(v.w, mk.w));
+                for (int k = 0; k < 32 / RPI; ++k) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + (st_r + k * RPI) * PW + st_c * 8);
+                    const bool ok = st_col_ok && st_r + k * RPI < rows_left;
+                    const unsigned off = ok ? st_lane_off + blk_off + (unsigned)(k * RPI * p.Co * 2) : OOB;
+                    if (p.nt_out) buffer_store16_nt(rs_out, off, v);
+                    else buffer_store16(rs_out, off, v);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 32 * CPR / 64; ++k) {
+                    const int idx = k * 64 + lane;
+                    const int r = idx / CPR, c = idx % CPR;
+                    const int m = m0 + wave_m + i * 32 + r, co = n0 + wave_n + c * 8;
+                    uint4 v = *reinterpret_cast<const uint4 *>(stg + r * PW + c * 8);
+                    if (m < p.m_end && co < p.Co) {
+                        const long long off = out_pixel(m) * p.Co + co;
+                        if (p.mask != nullptr) {
+                            const uint4 mk = *reinterpret_cast<const uint4 *>(p.mask + off);
+                            v = make_uint4(mask_bf16x2(v.x, mk.x), mask_bf16x2(v.y, mk.y), mask_bf16x2(v.z, mk.z), mask_bf16x2(v.w, mk.w));
+                        }
+                        typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+                        const u32x4 vv = {v.x, v.y, v.z, v.w};
+                        if (p.nt_out) __builtin_nontemporal_store(vv, reinterpret_cast<u32x4 *>(p.out + off));
+                        else *reinterpret_cast<u32x4 *>(p.out + off) = vv;
                     }
-                    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-                    const u32x4 vv = {v.x, v.y, v.z, v.w};
-                    if (p.nt_out) __builtin_nontemporal_store(vv, reinterpret_cast<u32x4 *>(p.out + off));
-                    else *reinterpret_cast<u32x4 *>(p.out + off) = vv;
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -477,22 +524,24 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     } else {
+        // output channel counts that are not a multiple of 8: element by element
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
+            const int m = m0 + wave_m + i * 32 + frag_row;
+            if (m >= p.m_end) continue;
+            const long long orow = out_pixel(m) * p.Co;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wave_m + i * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
-                if (m >= p.m_end) continue;
-                const long long orow = out_pixel(m) * p.Co;
+            for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    const int co = n0 + wave_n + j * 32 + frag_row;
+                for (int e = 0; e < 16; ++e) {
+                    const int co = n0 + wave_n + j * 32 + 8 * (e >> 2) + 4 * frag_kg + (e & 3);
                     if (co < p.Co) {
+                        float v = acc[i][j][e] + (p.bias != nullptr ? p.bias[co] : 0.f);
+                        if (p.relu) v = fmaxf(v, 0.f);
                         const bool keep = p.mask == nullptr || mask_keeps(p.mask + orow + co);
-                        p.out[orow + co] = keep ? finish(acc[i][j][e], j) : (bf16_t)0;
+                        p.out[orow + co] = keep ? f32_to_bf16(v) : (bf16_t)0;
                     }
                 }
-            }
         }
     }
 }
@@ -519,6 +568,8 @@ int launch(IgemmParams p, hipStream_t st, long long m_begin = 0, long long m_end
     p.linear_out = (p.out_mul_h == 1 && p.out_mul_w == 1 && p.out_off_h == 0 && p.out_off_w == 0 && p.Mh == p.Ho && p.Mw == p.Wo) ? 1 : 0;
     // results of a large layer leave as non-temporal stores: the caches keep serving this kernel's operand reads
     static const char *nt_forced = getenv("MXC_NT_OUT");                      // tuning sweeps only; read once
+    const long long out_bytes = (long long)p.N * p.Ho * p.Wo * p.Co * 2;
+    p.out_bytes = out_bytes < 0x7FFF0000ll ? (unsigned)out_bytes : 0u;
     p.nt_out = nt_forced ? atoi(nt_forced) : ((long long)p.N * p.Ho * p.Wo * p.Co * 2 >= (128ll << 20) ? 1 : 0);
     if (p.splits > 1) {
         // even stage ranges; the last split may be shorter, none is empty

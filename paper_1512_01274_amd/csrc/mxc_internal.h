@@ -216,6 +216,7 @@ struct IgemmParams {
     int splits, split_stages;
     int tap_row_inner;   // tap t = (column step)*TR + (row step) instead of (row step)*TS + (column step)
     int nt_out;          // the 16-byte result stores are non-temporal
+    unsigned out_bytes;  // size of the output tensor when below 2 GiB (buffer stores with range-checked offsets), else 0
     int tap_inner;       // reduction order (Ci % BKT == 0 only): 1 = all taps of a channel block before the next block
     // applied to the accumulators before the store (all optional)
     const float *bias;   // + bias[co]

@@ -345,7 +345,7 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             if (fast_store) {
                 const bool col_ok = n0 + jc * 64 + st_c * 8 < p.Co;
-                const unsigned tile_off = (unsigned)(m0 * p.Co * 2 + jc * 128);     // < 2^31 with the whole output
+                const unsigned tile_off = (unsigned)m0 * (unsigned)(p.Co * 2) + (unsigned)(jc * 128);   // below 2^32: the output is below 2^31
                 const int rows_left = wg_hi - m0;
 #pragma unroll
                 for (int k = 0; k < 32 / RPI; ++k) {
