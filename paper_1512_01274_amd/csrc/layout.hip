@@ -136,31 +136,51 @@ __global__ __launch_bounds__(256) void small_c_kernel(const T *__restrict__ src,
     }
 }
 
-// Same permutation for 2-byte elements, C channels, 8 pixels per thread: C 16-byte loads, a register
-// shuffle, C 16-byte stores.  Needs pixels % 8 == 0 (keeps every access 16-byte aligned).
+// Same permutation for 2-byte elements, C channels, 8 pixels per thread: C 16-byte accesses on the planar side, a
+// register shuffle, and C 16-byte accesses on the interleaved side.  A thread's C interleaved chunks are
+// neighbours in memory (a wave-wide access of "my i-th chunk" would touch 16 bytes of every 16*C), so they pass
+// through LDS and each instruction of the interleaved side covers one contiguous span of the workgroup's pixels.
+// Needs pixels % 8 == 0 (keeps every access 16-byte aligned).
 template <int C, bool TO_INTERLEAVED>
 __global__ __launch_bounds__(256) void small_c_vec_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
                                                           long long pixels)
 {
-    const long long pix0 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 8;
-    if (pix0 >= pixels) return;
+    __shared__ uint4 chunks[256 * C];
+    const int t = threadIdx.x;
+    const long long blk_pix0 = (long long)blockIdx.x * 2048;           // first pixel of this workgroup
+    const long long pix0 = blk_pix0 + (long long)t * 8;
+    const bool mine = pix0 < pixels;
     const size_t base = (size_t)blockIdx.y * C * pixels;
+    const long long blk_chunks = (min(pixels - blk_pix0, 2048ll) / 8) * C;   // 16-byte chunks of this workgroup's span
+    uint16_t *inter = const_cast<uint16_t *>(TO_INTERLEAVED ? dst : src) + base + (size_t)blk_pix0 * C;
     union V { uint4 v; uint16_t e[8]; };
     V in[C], out[C];
     if (TO_INTERLEAVED) {
+        if (mine) {
 #pragma unroll
-        for (int ch = 0; ch < C; ++ch) in[ch].v = *reinterpret_cast<const uint4 *>(src + base + (size_t)ch * pixels + pix0);
+            for (int ch = 0; ch < C; ++ch) in[ch].v = *reinterpret_cast<const uint4 *>(src + base + (size_t)ch * pixels + pix0);
 #pragma unroll
-        for (int j = 0; j < 8 * C; ++j) out[j / 8].e[j % 8] = in[j % C].e[j / C];
+            for (int j = 0; j < 8 * C; ++j) out[j / 8].e[j % 8] = in[j % C].e[j / C];
 #pragma unroll
-        for (int i = 0; i < C; ++i) *reinterpret_cast<uint4 *>(dst + base + (size_t)pix0 * C + i * 8) = out[i].v;
+            for (int i = 0; i < C; ++i) chunks[t * C + i] = out[i].v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < C; ++i)
+            if (i * 256 + t < blk_chunks) reinterpret_cast<uint4 *>(inter)[i * 256 + t] = chunks[i * 256 + t];
     } else {
 #pragma unroll
-        for (int i = 0; i < C; ++i) in[i].v = *reinterpret_cast<const uint4 *>(src + base + (size_t)pix0 * C + i * 8);
+        for (int i = 0; i < C; ++i)
+            if (i * 256 + t < blk_chunks) chunks[i * 256 + t] = reinterpret_cast<const uint4 *>(inter)[i * 256 + t];
+        __syncthreads();
+        if (mine) {
 #pragma unroll
-        for (int j = 0; j < 8 * C; ++j) out[j % C].e[j / C] = in[j / 8].e[j % 8];
+            for (int i = 0; i < C; ++i) in[i].v = chunks[t * C + i];
 #pragma unroll
-        for (int ch = 0; ch < C; ++ch) *reinterpret_cast<uint4 *>(dst + base + (size_t)ch * pixels + pix0) = out[ch].v;
+            for (int j = 0; j < 8 * C; ++j) out[j % C].e[j / C] = in[j / 8].e[j % 8];
+#pragma unroll
+            for (int ch = 0; ch < C; ++ch) *reinterpret_cast<uint4 *>(dst + base + (size_t)ch * pixels + pix0) = out[ch].v;
+        }
     }
 }
 

@@ -349,7 +349,7 @@ __device__ __forceinline__ void store4(bf16_t *dw, int i4, const float4 v)
 }
 
 template <int G, typename OUT>
-__global__ __launch_bounds__(256) void wgrad_reduce_vec4_kernel(const float4 *__restrict__ partial, OUT *__restrict__ dw,
+__global__ __launch_bounds__(256) void wgrad_reduce_vec4_kernel(const float4 *partial, OUT *dw,
                                                                 int total4, int splits)
 {
     constexpr int LPG = 64 / G;                       // lanes per group
@@ -565,11 +565,25 @@ size_t wgrad_workspace(const WgradGeom &g)
 }
 
 template <typename OUT>
-static int launch_reduce(const WgradGeom &g, const float *partial, OUT *dw, int splits, int ncols, bool identity, hipStream_t st)
+static int launch_reduce(const WgradGeom &g, float *partial, OUT *dw, int splits, int ncols, bool identity, hipStream_t st)
 {
     const int total = g.K * g.R * g.S * g.C;
     // many splits of a small dw: 16 lane groups keep enough loads in flight; otherwise 4
     const bool wide = splits >= 32 && total < 256 * 1024;
+    if (!identity && splits > 1) {
+        // Packed geometries (first layers): the column remap reads single floats, so first add the splits with the
+        // 16-byte kernel - in place, into the first split's partial tensor: every element is read and then written
+        // by the same lane group - and remap that one tensor afterwards.
+        const int cols4 = g.K * ncols / 4;            // ncols is a multiple of 8
+        if (wide)
+            hipLaunchKernelGGL((wgrad_reduce_vec4_kernel<16, float>), dim3((unsigned)((cols4 + 15) / 16)), dim3(256), 0, st,
+                               (const float4 *)partial, partial, cols4, splits);
+        else
+            hipLaunchKernelGGL((wgrad_reduce_vec4_kernel<4, float>), dim3((unsigned)((cols4 + 63) / 64)), dim3(256), 0, st,
+                               (const float4 *)partial, partial, cols4, splits);
+        if (hipGetLastError() != hipSuccess) return MXC_ERR_LAUNCH;
+        splits = 1;
+    }
     if (identity && total % 4 == 0) {
         const int total4 = total / 4;
         if (wide)
@@ -618,8 +632,8 @@ int wgrad(const WgradGeom &g, const void *x, const void *dy, void *dw, bool dw_b
     if (rc != MXC_OK) return rc;
     *variant = tc.name;
     if (direct) return MXC_OK;
-    return dw_bf16 ? launch_reduce(g, partial, (bf16_t *)dw, p.splits, p.ncols, identity, st)
-                   : launch_reduce(g, partial, (float *)dw, p.splits, p.ncols, identity, st);
+    return dw_bf16 ? launch_reduce(g, p.partial, (bf16_t *)dw, p.splits, p.ncols, identity, st)
+                   : launch_reduce(g, p.partial, (float *)dw, p.splits, p.ncols, identity, st);
 }
 
 }  // namespace mxc
