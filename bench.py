@@ -514,6 +514,39 @@ def layout_entry(torch, mxc):
     return res
 
 
+def transform_entry(torch, mxc, gen):
+    """The other algorithm for 3x3 stride-1 layers (transform domain, 2x2 blocks from 4x4 patches) beside the direct
+    implicit GEMM, forward of two VGG-style layers: microseconds per call and the workspace the transform needs."""
+    cfg = gen.config_by_name("vgg_a_b64")
+    out = []
+    for L in cfg.layers:
+        if L.name not in ("conv4_2", "conv5_2"):
+            continue
+        d = L.dims()
+        x = torch.randn(L.N * L.C * L.H * L.W, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+        w = (torch.randn(L.K * L.C * L.R * L.S, dtype=torch.float32, device="cuda") * 0.05).to(torch.bfloat16)
+        y = torch.empty(L.N * L.K * L.P * L.Q, dtype=torch.bfloat16, device="cuda")
+        ws_d = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_FWD, *d, mxc.MXC_BF16, mxc.MXC_NHWC))
+        nb = mxc.mxc_conv2d_workspace_bytes(mxc.MXC_FWD_TRANSFORM, *d, mxc.MXC_BF16, mxc.MXC_NHWC)
+        ws_t = mxc.alloc_workspace(nb)
+        us = {}
+        for name, f in (("direct_us", lambda: mxc.mxc_conv2d_fwd(*d, mxc.MXC_BF16, mxc.MXC_NHWC, x, w, y, ws_d)),
+                        ("transform_us", lambda: mxc.mxc_conv2d_fwd_transform(*d, mxc.MXC_BF16, mxc.MXC_NHWC, x, w, None, 0, y, ws_t))):
+            f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            us[name] = round(e0.elapsed_time(e1) * 100.0, 1)
+        out.append({"layer": L.name, **us, "transform_workspace_MiB": nb >> 20})
+        del x, w, y, ws_d, ws_t
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -656,6 +689,8 @@ def main():
     del net, per_call
     torch.cuda.empty_cache()
     result["layout_a1"] = layout_entry(torch, mxc)
+    if not args.no_all:
+        result["alt_algorithm_3x3_fwd"] = transform_entry(torch, mxc, gen)
     if not args.no_all:
         nets = {}
         for other in gen.CONFIGS:

@@ -69,7 +69,8 @@ enum { MXC_FWD = 0, MXC_BWD_DATA = 1, MXC_BWD_WEIGHT = 2,
        MXC_INPUT_PREPARED = 9,           /* bytes of the prepared input of mxc_conv2d_prepare_input (0: none)   */
        MXC_FWD_PREPARED_INPUT = 10,      /* workspace of mxc_conv2d_fwd_prepared_input                          */
        MXC_BWD_WEIGHT_PREPARED_INPUT = 11,       /* workspace of mxc_conv2d_bwd_weight_prepared_input, fp32 dw  */
-       MXC_BWD_WEIGHT_PREPARED_INPUT_BF16 = 12 };/* ... bf16 dw                                                 */
+       MXC_BWD_WEIGHT_PREPARED_INPUT_BF16 = 12,  /* ... bf16 dw                                                 */
+       MXC_FWD_TRANSFORM = 13 };         /* workspace of mxc_conv2d_fwd_transform                               */
 
 /*
  * Forward (the layer's "forward" evaluation, paper Section 2.1):
@@ -218,6 +219,25 @@ int mxc_conv2d_bwd_weight_prepared_input(int N, int C, int H, int W, int K, int 
                                          int dtype, int layout,
                                          const void *x_prepared, size_t prepared_bytes, const void *dy, void *dw, int dw_dtype,
                                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Forward by another algorithm: the 3x3 stride-1 convolution evaluated in a transform domain (minimal filtering,
+ * 2x2 output blocks from 4x4 input patches: 16 multiplications per channel and block instead of 36), the same
+ * y = act(conv(x, w) + bias) as mxc_conv2d_fwd_bias_act (Section 2.1; one of the hand-optimised "big" operators
+ * of Section 3.1).  Filter and input are transformed, rounded once to bf16 and multiplied on the matrix cores as
+ * 16 independent GEMMs with fp32 sums; the result is transformed back and rounded once.  Its error is therefore
+ * not that of the direct form: |y - exact| <= 2^-8 * W + 2^-8 * |exact|, W = the sum, over the transform-domain
+ * entries a result combines, of sum_c |U||V| (U, V the transformed filter and input); for the layers of the
+ * benchmark stacks that is well inside 1e-2 of sum |x||w|.
+ * Only R = S = 3, stride = 1, dtype MXC_BF16, layout MXC_NHWC, C % 8 == 0 and K % 8 == 0 (MXC_ERR_UNSUPPORTED
+ * otherwise; callers fall back to mxc_conv2d_fwd_bias_act).  bias may be NULL, relu is 0 or 1.  Workspace: query
+ * MXC_FWD_TRANSFORM (16 transformed copies of the tiled input in bf16 and of the output in fp32: large).
+ * Everything else as mxc_conv2d_fwd.
+ */
+int mxc_conv2d_fwd_transform(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             int dtype, int layout,
+                             const void *x, const void *w, const float *bias, int relu, void *y,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Gradient of the bias of mxc_conv2d_fwd_bias_act (derivative of forward + bias[k] in bias):

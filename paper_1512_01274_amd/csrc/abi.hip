@@ -603,6 +603,31 @@ int mxc_conv2d_bwd_weight_prepared_input(int N, int C, int H, int W, int K, int 
     return bwd_weight_nhwc(s, dtype, needx ? nullptr : x_prepared, dy, dw, dw_dtype == MXC_BF16, ws, (hipStream_t)hip_stream, false, ip);
 }
 
+int mxc_conv2d_fwd_transform(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype, int layout,
+                             const void *x, const void *w, const float *bias, int relu, void *y, void *workspace,
+                             size_t workspace_bytes, void *hip_stream)
+{
+    ConvShape s;
+    MXC_TRY(validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s));
+    if (dtype != MXC_BF16 || layout != MXC_NHWC || (relu != 0 && relu != 1) || !winograd_supported(s)) return MXC_ERR_UNSUPPORTED;
+    if (!x || !w || !y) return MXC_ERR_NULL;
+    if (misaligned(x) || misaligned(w) || misaligned(y) || misaligned(workspace) || ((uintptr_t)bias & 3u)) return MXC_ERR_ALIGN;
+    size_t ub, vb, mb;
+    winograd_workspace(s, &ub, &vb, &mb);
+    Carver need(nullptr);
+    need.take(ub); need.take(vb); need.take(mb);
+    if (!workspace || workspace_bytes < need.used) return MXC_ERR_WORKSPACE;
+    Carver ws(workspace);
+    void *u = ws.take(ub), *v = ws.take(vb), *m = ws.take(mb);
+    PostOp post;
+    post.bias = bias;
+    post.relu = relu;
+    const char *vname = "";
+    const int rc = winograd_fwd(s, x, w, y, u, v, m, (hipStream_t)hip_stream, &vname, post);
+    if (rc == MXC_OK) set_variant("fwd", vname);
+    return rc;
+}
+
 int mxc_bias_grad(int N, int K, int P, int Q, int dtype, int layout, const void *dy, float *db, void *workspace,
                   size_t workspace_bytes, void *hip_stream)
 {
@@ -669,13 +694,22 @@ int mxc_conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int 
                                int dtype, int layout, size_t *out_bytes)
 {
     if (!out_bytes) return MXC_ERR_NULL;
-    if (pass < MXC_FWD || pass > MXC_BWD_WEIGHT_PREPARED_INPUT_BF16) return MXC_ERR_UNSUPPORTED;
+    if (pass < MXC_FWD || pass > MXC_FWD_TRANSFORM) return MXC_ERR_UNSUPPORTED;
     if (pass == MXC_BWD_WEIGHT_BF16 && dtype != MXC_BF16) return MXC_ERR_UNSUPPORTED;
     ConvShape s;
     const int rc = validate_shape(N, C, H, W, K, R, S, stride, pad, dtype, layout, &s);
     if (rc != MXC_OK) return rc;
     if (pass == MXC_BIAS_GRAD) {
         *out_bytes = align_up((size_t)bias_grad_parts(s.N, s.K, (long long)s.P * s.Q, layout) * s.K * sizeof(float), 256);
+        return MXC_OK;
+    }
+    if (pass == MXC_FWD_TRANSFORM) {
+        if (dtype != MXC_BF16 || layout != MXC_NHWC || !winograd_supported(s)) return MXC_ERR_UNSUPPORTED;
+        size_t ub, vb, mb;
+        winograd_workspace(s, &ub, &vb, &mb);
+        Carver need(nullptr);
+        need.take(ub); need.take(vb); need.take(mb);
+        *out_bytes = need.used;
         return MXC_OK;
     }
     if (pass >= MXC_INPUT_PREPARED) {

@@ -408,8 +408,9 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         const unsigned a = t2 % (unsigned)p.Mh, n = t2 / (unsigned)p.Mh;
         return ((long long)n * p.Ho + ((int)a * p.out_mul_h + p.out_off_h)) * p.Wo + ((int)b * p.out_mul_w + p.out_off_w);
     };
-    if (p.splits > 1) {
-        // split reduction: fp32 accumulators to partial[z][m][co] (row-major like the output; Co % 8 == 0), 16 bytes at a time
+    if (p.splits > 1 || p.f32_out) {
+        // split reduction, or a caller that wants the fp32 sums themselves: accumulators to partial[z][m][co]
+        // (row-major like the output; Co % 8 == 0), 16 bytes at a time
         float *part = p.partial + (size_t)split_z * p.M * p.Co;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
@@ -930,6 +931,29 @@ int igemm_fwd(const ConvShape &s, const void *x, const void *w, void *y, hipStre
     const Plan pl = plan_for(p, M, s.K, s.R * s.S * s.C, sp > 1);
     *variant = plan_name(pl);
     if (sp > 1) return launch_split(pl.main, p, M, sp, split_ws, y, post, st, variant);
+    return launch_plan(pl, p, st);
+}
+
+// Plain GEMM on the same kernels: out[m][n] = sum_k a[m][k] * b[n][k], a and b bf16 (row-major, k contiguous, k % 8 == 0),
+// out fp32, n % 8 == 0.  It is the 1x1 convolution of an M-image batch of 1x1 images whose fp32 accumulators are
+// stored unrounded (the transform-domain convolution multiplies its 16 planes with it).
+bool igemm_gemm_f32_supported(long long M, int Kd, int Nn)
+{
+    return Kd % 8 == 0 && Nn % 8 == 0 && igemm_dims_ok(M * Kd, (long long)Nn * Kd, M, 1, 1, 4, 1) && M * Nn * 4 < (1ll << 40);
+}
+
+int igemm_gemm_f32(long long M, int Kd, int Nn, const void *a, const void *b, float *out, hipStream_t st, const char **variant)
+{
+    IgemmParams p{};
+    p.in = (const bf16_t *)a; p.wm = (const bf16_t *)b; p.out = nullptr;
+    p.partial = out; p.f32_out = 1;
+    p.N = (int)M; p.Hi = 1; p.Wi = 1; p.Ci = Kd; p.pix = Kd; p.Co = Nn;
+    p.TR = 1; p.TS = 1; p.tstep_h = 1; p.tstep_w = 1;
+    p.Mh = 1; p.Mw = 1;
+    p.in_mul_h = 1; p.in_mul_w = 1; p.in_off_h = 0; p.in_off_w = 0;
+    p.Ho = 1; p.Wo = 1; p.out_mul_h = 1; p.out_mul_w = 1; p.out_off_h = 0; p.out_off_w = 0;
+    const Plan pl = choose_plan(M, Nn, Kd, false);
+    *variant = plan_name(pl);
     return launch_plan(pl, p, st);
 }
 

@@ -215,6 +215,7 @@ struct IgemmParams {
     float *partial;
     int splits, split_stages;
     int tap_row_inner;   // tap t = (column step)*TR + (row step) instead of (row step)*TS + (column step)
+    int f32_out;         // store the fp32 accumulators to `partial` ([m][co], one split) instead of a rounded result to `out`
     int nt_out;          // the 16-byte result stores are non-temporal
     unsigned out_bytes;  // size of the output tensor when below 2 GiB (buffer stores with range-checked offsets), else 0
     int tap_inner;       // reduction order (Ci % BKT == 0 only): 1 = all taps of a channel block before the next block
@@ -223,6 +224,18 @@ struct IgemmParams {
     int relu;            // max(0, .)
     const bf16_t *mask;  // indexed like `out`: the stored value is 0 where mask <= 0
 };
+
+// out[m][n] = sum_k a[m][k] * b[n][k] in fp32 from bf16 operands (k contiguous in both), on the tiled kernel
+bool igemm_gemm_f32_supported(long long M, int Kd, int Nn);
+int igemm_gemm_f32(long long M, int Kd, int Nn, const void *a, const void *b, float *out, hipStream_t st, const char **variant);
+
+// ---- winograd.hip: 3x3 stride-1 forward in the transform domain, F(2x2, 3x3) ----------------------------
+bool winograd_supported(const ConvShape &s);
+// bytes of the three workspace parts: transformed filter U [16][K][C] bf16, transformed input V [16][tiles][C] bf16,
+// products M [16][tiles][K] fp32
+void winograd_workspace(const ConvShape &s, size_t *u_bytes, size_t *v_bytes, size_t *m_bytes);
+int winograd_fwd(const ConvShape &s, const void *x, const void *w, void *y, void *u, void *v, void *m, hipStream_t st,
+                 const char **variant, const PostOp &post);
 
 // stream.hip: the same GEMM for short reductions and few output columns (see there); whether it can run p,
 // and the launch over all rows (both take p as a launch site fills it: the fields the launcher derives -

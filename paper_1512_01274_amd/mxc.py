@@ -18,6 +18,7 @@ MXC_NCHW, MXC_NHWC = 0, 1
 MXC_FWD, MXC_BWD_DATA, MXC_BWD_WEIGHT, MXC_BWD_DATA_RELU, MXC_BIAS_GRAD = 0, 1, 2, 3, 4
 MXC_BWD_DATA_FILTER, MXC_BWD_DATA_PREPARED, MXC_BWD_DATA_PREPARED_RELU, MXC_BWD_WEIGHT_BF16 = 5, 6, 7, 8
 MXC_INPUT_PREPARED, MXC_FWD_PREPARED_INPUT, MXC_BWD_WEIGHT_PREPARED_INPUT, MXC_BWD_WEIGHT_PREPARED_INPUT_BF16 = 9, 10, 11, 12
+MXC_FWD_TRANSFORM = 13
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmxc.so")
 if not os.path.exists(LIB_PATH):
@@ -41,6 +42,8 @@ _lib.mxc_conv2d_fwd_prepared_input.argtypes = [_I] * 11 + [_VP, _SZ, _VP, _VP, _
 _lib.mxc_conv2d_fwd_prepared_input.restype = _I
 _lib.mxc_conv2d_bwd_weight_prepared_input.argtypes = [_I] * 11 + [_VP, _SZ, _VP, _VP, _I, _VP, _SZ, _VP]
 _lib.mxc_conv2d_bwd_weight_prepared_input.restype = _I
+_lib.mxc_conv2d_fwd_transform.argtypes = [_I] * 11 + [_VP, _VP, _VP, _I, _VP, _VP, _SZ, _VP]
+_lib.mxc_conv2d_fwd_transform.restype = _I
 _lib.mxc_conv2d_workspace_bytes.argtypes = [_I] * 12 + [ctypes.POINTER(_SZ)]
 _lib.mxc_conv2d_workspace_bytes.restype = _I
 _lib.mxc_layout_convert.argtypes = [_I] * 7 + [_VP, _VP, _VP]
@@ -217,6 +220,14 @@ def mxc_conv2d_bwd_data_prepared(N, C, H, W, K, R, S, stride, pad, dtype, layout
     rc = _lib.mxc_conv2d_bwd_data_prepared(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(dy), _ptr(w_prepared),
                                            w_prepared.numel() * w_prepared.element_size(), _ptr(x_mask), _ptr(dx), ws_ptr, ws_bytes,
                                            _stream(stream))
+    if rc != MXC_OK:
+        raise MxcError(rc)
+
+
+def mxc_conv2d_fwd_transform(N, C, H, W, K, R, S, stride, pad, dtype, layout, x, w, bias, relu, y, workspace=None, stream=None):
+    ws_ptr, ws_bytes = _ws(workspace)
+    rc = _lib.mxc_conv2d_fwd_transform(N, C, H, W, K, R, S, stride, pad, dtype, layout, _ptr(x), _ptr(w), _ptr(bias), int(relu),
+                                       _ptr(y), ws_ptr, ws_bytes, _stream(stream))
     if rc != MXC_OK:
         raise MxcError(rc)
 

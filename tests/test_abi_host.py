@@ -159,6 +159,29 @@ def test_prepared_input_sizes_and_validation(mxc):
         == mxc.MXC_ERR_UNSUPPORTED
 
 
+def test_transform_domain_forward_validation(mxc):
+    """Host logic of the transform-domain forward: it exists for 3x3 stride-1 bf16 NHWC layers with channel counts
+    that are multiples of 8, reports everything else as unsupported, and sizes its three workspace parts."""
+    import ctypes as ct
+    lib = mxc.raw()
+    out = ct.c_size_t(0)
+    ok = (2, 64, 14, 14, 32, 3, 3, 1, 1)
+    T = 2 * 7 * 7
+    need = mxc.mxc_conv2d_workspace_bytes(mxc.MXC_FWD_TRANSFORM, *ok, mxc.MXC_BF16, mxc.MXC_NHWC)
+    assert need == 16 * 32 * 64 * 2 + 16 * T * 64 * 2 + 16 * T * 32 * 4       # U, V, M (each a multiple of 256 here)
+    for bad in [(2, 64, 14, 14, 32, 5, 5, 1, 2), (2, 64, 14, 14, 32, 3, 3, 2, 1), (2, 60, 14, 14, 32, 3, 3, 1, 1),
+                (2, 64, 14, 14, 36, 3, 3, 1, 1), (2, 64, 14, 14, 32, 1, 1, 1, 0)]:
+        assert lib.mxc_conv2d_workspace_bytes(mxc.MXC_FWD_TRANSFORM, *bad, mxc.MXC_BF16, mxc.MXC_NHWC, ct.byref(out)) == mxc.MXC_ERR_UNSUPPORTED
+        assert lib.mxc_conv2d_fwd_transform(*bad, mxc.MXC_BF16, mxc.MXC_NHWC, 4096, 8192, None, 0, 16384, 32768, 1 << 30, None) \
+            == mxc.MXC_ERR_UNSUPPORTED
+    for dt, lay in ((mxc.MXC_F32, mxc.MXC_NHWC), (mxc.MXC_BF16, mxc.MXC_NCHW)):
+        assert lib.mxc_conv2d_workspace_bytes(mxc.MXC_FWD_TRANSFORM, *ok, dt, lay, ct.byref(out)) == mxc.MXC_ERR_UNSUPPORTED
+    assert lib.mxc_conv2d_fwd_transform(*ok, 1, 1, 4096, 8192, None, 2, 16384, 32768, 1 << 30, None) == mxc.MXC_ERR_UNSUPPORTED
+    assert lib.mxc_conv2d_fwd_transform(*ok, 1, 1, None, 8192, None, 0, 16384, 32768, 1 << 30, None) == mxc.MXC_ERR_NULL
+    assert lib.mxc_conv2d_fwd_transform(*ok, 1, 1, 4096, 8192, 4098, 0, 16384, 32768, 1 << 30, None) == mxc.MXC_ERR_ALIGN
+    assert lib.mxc_conv2d_fwd_transform(*ok, 1, 1, 4096, 8192, None, 0, 16384, 32768, need - 1, None) == mxc.MXC_ERR_WORKSPACE
+
+
 def test_nchw_limits_are_reported_before_any_launch(mxc):
     """NCHW operands go through batched transposes with int row/column counts: what those cannot run is refused by the
     shape check itself (the size query sees it too), while the same problem in NHWC is accepted; batch and filter

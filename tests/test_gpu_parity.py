@@ -389,6 +389,47 @@ def test_prepared_input_forward_and_backward_weight(mxc, oracle, dims, dtype):
             assert util.metric(a, ref, den) <= util.TOL[dtype], (dims, mxc.mxc_last_variant())
 
 
+TRANSFORM_SHAPES = [
+    (2, 16, 12, 12, 24, 3, 3, 1, 1),
+    (1, 64, 13, 15, 72, 3, 3, 1, 1),       # odd output sizes: half-filled blocks at the right and bottom edges
+    (2, 8, 9, 10, 16, 3, 3, 1, 0),         # no padding
+    (1, 16, 6, 6, 8, 3, 3, 1, 2),          # output larger than the input
+    (2, 128, 28, 28, 128, 3, 3, 1, 1),     # several row and column tiles of the GEMMs
+]
+
+
+@pytest.mark.parametrize("dims", TRANSFORM_SHAPES)
+def test_transform_domain_forward(mxc, oracle, dims):
+    """The 3x3 stride-1 forward evaluated in the transform domain, against the plain definition: inside the
+    spec tolerance, and inside its own budget - 2^-8 times the worst-case weight of its two bf16 roundings
+    (evaluated on the host from the transform's definition), plus the rounding of the result."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy, bias = _fused_case(dims, "bf16", (hash(dims) & 0xFFFF) + 13)
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    P, Q = run.P, run.Q
+    d_x, d_w, d_b = run._in(x), run._in(w), torch.from_numpy(bias).cuda()
+    ws = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_FWD_TRANSFORM, *dims, run.dt, run.lay))
+    budget = util.transform_domain_budget(x, w, pad)
+    for b, relu in ((None, 0), (d_b, 1)):
+        y = torch.full((N * K * P * Q,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_fwd_transform(*dims, run.dt, run.lay, d_x, d_w, b, relu, y, ws)
+        torch.cuda.synchronize()
+        assert mxc.mxc_last_variant().startswith("fwd:winograd"), mxc.mxc_last_variant()
+        got = run._out(y, (N, K, P, Q))
+        if b is None:
+            ref, den = oracle.conv2d_fwd(x, w, st, pad), oracle.conv2d_fwd(np.abs(x), np.abs(w), st, pad)
+        else:
+            ref, den = oracle.conv2d_fwd_bias_act(x, w, bias, True, st, pad)
+        assert util.metric(got, ref, den) <= util.TOL["bf16"], dims
+        bound = 2.0 ** -8 * 1.05 * budget + 2.0 ** -8 * np.abs(ref) + 64 * 2.0 ** -24 * den
+        assert np.all(np.abs(got - ref) <= bound), (dims, float(np.max(np.abs(got - ref) / np.maximum(bound, 1e-30))))
+    # the direct form on the same inputs, for the record of how much wider the budget is used
+    yd = torch.empty_like(y)
+    mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, d_x, d_w, d_b, 1, yd, run._ws(mxc.MXC_FWD))
+    torch.cuda.synchronize()
+    assert util.metric(run._out(yd, (N, K, P, Q)), ref, den) <= util.metric(got, ref, den) + 1e-3
+
+
 @pytest.mark.parametrize("cfg_idx", [1, 3])
 def test_grouped_operations_network_layers(mxc, oracle, cfg_idx):
     """The bench's launch configuration (bf16, NHWC) on every layer of the AlexNet- and VGG-style stacks, batch 2."""

@@ -482,3 +482,31 @@ def test_softmax_closed_forms_and_torch(oracle):
     torch.nn.functional.cross_entropy(tz, torch.tensor(labels), reduction="sum").backward()
     np.testing.assert_allclose(oracle.softmax_xent_bwd(p, labels), tz.grad.numpy(), rtol=1e-12, atol=1e-15)
     np.testing.assert_allclose(oracle.softmax_xent_bwd(p, labels, 0.25).sum(axis=1), 0.0, atol=1e-15)   # rows of the gradient sum to 0
+
+
+def test_transform_domain_identity_and_budget(oracle):
+    """The matrices the transform-domain forward (and the tests' error budget for it) are built on reproduce the
+    plain definition exactly: At[(G g Gt) .* (Bt d B)]A summed over channels equals the oracle's forward, and the
+    budget (the same expression on absolute values) bounds it."""
+    from tests import util
+    rng = np.random.Generator(np.random.Philox(key=99))
+    x = rng.standard_normal((2, 3, 7, 8)).astype(np.float32)
+    w = rng.standard_normal((4, 3, 3, 3)).astype(np.float32)
+    G = np.array([[1, 0, 0], [.5, .5, .5], [.5, -.5, .5], [0, 0, 1]])
+    Bt = np.array([[1, 0, -1, 0], [0, 1, 1, 0], [0, -1, 1, 0], [0, 1, 0, -1]], dtype=np.float64)
+    At = np.array([[1, 1, 1, 0], [0, 1, -1, -1]], dtype=np.float64)
+    for pad in (0, 1, 2):
+        ref = oracle.conv2d_fwd(x, w, 1, pad)
+        P, Q = ref.shape[2], ref.shape[3]
+        TP, TQ = (P + 1) // 2, (Q + 1) // 2
+        xp = np.zeros((2, 3, 2 * TP + 2, 2 * TQ + 2))
+        xp[:, :, pad:pad + 7, pad:pad + 8] = x
+        U = np.einsum("ir,kcrs,js->kcij", G, w.astype(np.float64), G)
+        out = np.zeros((2, 4, 2 * TP, 2 * TQ))
+        for tp in range(TP):
+            for tq in range(TQ):
+                V = np.einsum("ia,ncab,jb->ncij", Bt, xp[:, :, 2 * tp:2 * tp + 4, 2 * tq:2 * tq + 4], Bt)
+                out[:, :, 2 * tp:2 * tp + 2, 2 * tq:2 * tq + 2] = np.einsum("ai,nkij,bj->nkab", At, np.einsum("kcij,ncij->nkij", U, V), At)
+        assert np.max(np.abs(out[:, :, :P, :Q] - ref)) < 1e-12
+        budget = util.transform_domain_budget(x, w, pad)
+        assert budget.shape == ref.shape and np.all(budget + 1e-12 >= np.abs(ref))

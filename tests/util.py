@@ -95,3 +95,29 @@ def tight_bound(ref: np.ndarray, den: np.ndarray, dtype: str, out_is_bf16: bool)
     if out_is_bf16:
         b = b + 2.0 ** -8 * np.abs(ref)
     return b + 1e-30
+
+
+def transform_domain_budget(x: np.ndarray, w: np.ndarray, pad: int) -> np.ndarray:
+    """Worst-case effect of the two bf16 roundings of the transform-domain 3x3 forward (2x2 output blocks from 4x4
+    patches), per output element: W[n,k,p,q] = (|At| (sum_c |G g Gt| * |Bt d B|) |A|), the quantity its error bound
+    multiplies by 2^-8.  x is NCHW, w is KCRS, float64 arithmetic."""
+    G = np.array([[1, 0, 0], [.5, .5, .5], [.5, -.5, .5], [0, 0, 1]], dtype=np.float64)
+    Bt = np.array([[1, 0, -1, 0], [0, 1, 1, 0], [0, -1, 1, 0], [0, 1, 0, -1]], dtype=np.float64)
+    At = np.array([[1, 1, 1, 0], [0, 1, -1, -1]], dtype=np.float64)
+    N, C, H, W_ = x.shape
+    K = w.shape[0]
+    P, Q = H + 2 * pad - 2, W_ + 2 * pad - 2
+    TP, TQ = (P + 1) // 2, (Q + 1) // 2
+    xp = np.zeros((N, C, 2 * TP + 2, 2 * TQ + 2), dtype=np.float64)
+    hh, ww = min(H, xp.shape[2] - pad), min(W_, xp.shape[3] - pad)
+    xp[:, :, pad:pad + hh, pad:pad + ww] = x[:, :, :hh, :ww]
+    U = np.abs(np.einsum("ir,kcrs,js->kcij", G, w.astype(np.float64), G))
+    out = np.zeros((N, K, 2 * TP, 2 * TQ), dtype=np.float64)
+    aAt = np.abs(At)
+    for tp in range(TP):
+        for tq in range(TQ):
+            d = xp[:, :, 2 * tp:2 * tp + 4, 2 * tq:2 * tq + 4]
+            V = np.abs(np.einsum("ia,ncab,jb->ncij", Bt, d, Bt))
+            Wm = np.einsum("kcij,ncij->nkij", U, V)
+            out[:, :, 2 * tp:2 * tp + 2, 2 * tq:2 * tq + 2] = np.einsum("ai,nkij,bj->nkab", aAt, Wm, aAt)
+    return out[:, :, :P, :Q]
