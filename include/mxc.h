@@ -11,7 +11,7 @@
  * Notation.  x[N,C,H,W] input, w[K,C,R,S] filter, y/dy[N,K,P,Q] output and its
  * gradient, with
  *     P = floor((H + 2*pad - R)/stride) + 1,  Q = floor((W + 2*pad - S)/stride) + 1.
- * One stride and one pad serve both axes; dilation 1, groups 1, no bias;
+ * One stride and one pad serve both axes; dilation 1, groups 1, no bias in the three plain calls;
  * cross-correlation (no filter flip); x outside the image reads as 0.
  *
  * Common rules for every call.
@@ -22,7 +22,8 @@
  *     the default stream).  Calls return as soon as the launches are queued.
  *   - `dtype` is the element type of x, w, y, dy, dx: MXC_F32, or MXC_BF16
  *     (bf16 storage, fp32 accumulation, results rounded to nearest-even).
- *     dw is ALWAYS fp32, for both dtypes.
+ *     dw is fp32 for both dtypes (mxc_conv2d_bwd_weight_bf16 and the prepared-input
+ *     form with dw_dtype MXC_BF16 round that fp32 sum once to bf16).
  *   - `layout` says how the caller's tensors are stored:
  *       MXC_NCHW: x[N][C][H][W], w/dw[K][C][R][S], y/dy[N][K][P][Q]
  *       MXC_NHWC: x[N][H][W][C], w/dw[K][R][S][C], y/dy[N][P][Q][K]
