@@ -78,6 +78,32 @@ def test_every_igemm_tile(mxc, oracle, tile, dims):
         _check(mxc, oracle, dims, ("fwd", "bwd_data"), tile)
 
 
+@pytest.mark.parametrize("dims", [(2, 64, 19, 17, 104, 3, 3, 1, 1), (3, 72, 13, 15, 200, 3, 3, 1, 1)])
+@pytest.mark.parametrize("tile", _names(0))
+def test_every_igemm_tile_fused_epilogue(mxc, oracle, tile, dims):
+    """bias + ReLU in the forward epilogue and the ReLU-derivative mask in the backward-data epilogue of every tile
+    shape (the bias travels through LDS, ReLU acts on the packed pair, masked stores take the general store path)."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy = gen.random_case((hash(dims) + 3) & 0xFFFF, *dims, dtype="bf16", dist="normal")
+    bias = np.linspace(-2.0, 2.0, K).astype(np.float32)
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    with forced("MXC_FORCE_VARIANT", tile):
+        y = torch.full((N * K * run.P * run.Q,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, run._in(x), run._in(w), torch.from_numpy(bias).cuda(), 1, y, run._ws(mxc.MXC_FWD))
+        assert mxc.mxc_last_variant().split(":")[-1].startswith(tile)
+        ref, den = oracle.conv2d_fwd_bias_act(x, w, bias, True, st, pad)
+        got = run._out(y, (N, K, run.P, run.Q))
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), (tile, dims)
+        assert np.all(got >= 0)
+        dx = torch.full((N * C * H * W,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_bwd_data_relu(*dims, run.dt, run.lay, run._in(dy), run._in(w), run._in(x), dx, run._ws(mxc.MXC_BWD_DATA_RELU))
+        assert mxc.mxc_last_variant().split(":")[-1].startswith(tile)
+        ref, den = oracle.conv2d_bwd_data_relu(dy, w, x, st, pad)
+        got = run._out(dx, (N, C, H, W))
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), (tile, dims)
+        assert np.all(got[x <= 0] == 0)
+
+
 @pytest.mark.parametrize("splits", [1, 3, 0])
 @pytest.mark.parametrize("dims", IGEMM_SHAPES[:3])
 @pytest.mark.parametrize("tile", _names(1))
@@ -131,6 +157,43 @@ def test_stream_kernel(mxc, oracle, dims):
 def test_stream_kernel_forms(mxc, oracle, dims, form):
     with forced("MXC_FORCE_VARIANT", "igemm_stream"), forced("MXC_STREAM_SHAPE", form):
         _check(mxc, oracle, dims, ("fwd", "bwd_data"), "igemm_stream")
+
+
+def _random_stream_shapes(count):
+    """Short-reduction problems drawn at random (fixed seed): 1x1 to 3x3 filters, strides 1-2, every padding up to
+    the filter size, channel counts from 8 to 136 in steps of 8, images from 1 to 40 pixels a side, batches 1-70."""
+    rng = np.random.Generator(np.random.Philox(key=20240))
+    out = []
+    while len(out) < count:
+        R, S = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        st = int(rng.integers(1, 3))
+        pad = int(rng.integers(0, max(R, S)))
+        H, W = int(rng.integers(1, 41)), int(rng.integers(1, 41))
+        C, K = 8 * int(rng.integers(1, 18)), 8 * int(rng.integers(1, 18))
+        N = int(rng.choice([1, 2, 3, 5, 70]))
+        if H + 2 * pad < R or W + 2 * pad < S or N * H * W > 60000 or R * S * max(C, K) > 640:
+            continue
+        out.append((N, C, H, W, K, R, S, st, pad))
+    return out
+
+
+@pytest.mark.parametrize("dims", _random_stream_shapes(40))
+def test_stream_kernel_random_shapes(mxc, oracle, dims):
+    """The streaming kernel asked for on random short-reduction problems (where it declines, the tiled kernel runs:
+    either way the result must match the oracle)."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy = gen.random_case(hash(dims) & 0xFFFF, *dims, dtype="bf16", dist="normal")
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    with forced("MXC_FORCE_VARIANT", "igemm_stream"):
+        got = run.fwd(x, w)
+        v1 = mxc.mxc_last_variant()
+        ref, den = oracle.conv2d_fwd(x, w, st, pad), oracle.conv2d_fwd(np.abs(x), np.abs(w), st, pad)
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), (dims, v1)
+        got = run.bwd_data(dy, w)
+        v2 = mxc.mxc_last_variant()
+        ref = oracle.conv2d_bwd_data(dy, w, x.shape, st, pad)
+        den = oracle.conv2d_bwd_data(np.abs(dy), np.abs(w), x.shape, st, pad)
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), (dims, v2)
 
 
 def test_stream_kernel_epilogue(mxc, oracle):
