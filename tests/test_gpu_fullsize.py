@@ -115,6 +115,61 @@ def test_full_size_sampled(mxc, oracle, ci, li):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("ci,li", [(1, 0), (3, 0)])
+def test_full_size_prepared_input(mxc, oracle, ci, li):
+    """First layers at full size (AlexNet conv1: space-to-depth form; VGG conv1_1: zero-bordered form) from an input
+    prepared once: forward and backward-weight bit-identical to the plain calls, and forward inside the oracle bound on
+    sampled outputs."""
+    cfg = gen.CONFIGS[ci]
+    L, t = gen.layer_inputs(cfg, li)
+    x, w, dy = t["x"], t["w"], t["dy"]
+    N, C, H, W, K, R, S, st, pad = dims = L.dims()
+    dt, lay = mxc.MXC_BF16, mxc.MXC_NHWC
+    nhwc = lambda a: gen.to_device(a, "bf16").view(*a.shape).permute(0, 2, 3, 1).contiguous().view(-1)
+    d_x, d_w, d_dy = nhwc(x), nhwc(w), nhwc(dy)
+    q = lambda op: mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(op, *dims, dt, lay))
+    nb = mxc.mxc_conv2d_workspace_bytes(mxc.MXC_INPUT_PREPARED, *dims, dt, lay)
+    assert nb > 0
+    xp = mxc.alloc_workspace(nb)
+    mxc.mxc_conv2d_prepare_input(*dims, dt, lay, d_x, xp)
+    y0 = torch.empty(N * K * L.P * L.Q, dtype=torch.bfloat16, device="cuda")
+    y1 = torch.full_like(y0, float("nan"))
+    mxc.mxc_conv2d_fwd(*dims, dt, lay, d_x, d_w, y0, q(mxc.MXC_FWD))
+    mxc.mxc_conv2d_fwd_prepared_input(*dims, dt, lay, xp, d_w, None, 0, y1, q(mxc.MXC_FWD_PREPARED_INPUT))
+    assert torch.equal(y0.view(torch.int16), y1.view(torch.int16)), mxc.mxc_last_variant()
+    rng = np.random.Generator(np.random.Philox(key=gen.SEED + 5000 + ci))
+    idx = _sample(rng, (N, K, L.P, L.Q), ([0, N - 1], [0, K - 1], _edge(L.P), _edge(L.Q)), 2048)
+    ref, den = oracle.conv2d_fwd_at(x, w, st, pad, idx)
+    _check("fwd", _gather(y1, _nchw_to_nhwc_index(idx, (N, K, L.P, L.Q))), ref, den, True, L)
+    dw0 = torch.empty(K * C * R * S, dtype=torch.float32, device="cuda")
+    dw1 = torch.full_like(dw0, float("nan"))
+    mxc.mxc_conv2d_bwd_weight(*dims, dt, lay, d_x, d_dy, dw0, q(mxc.MXC_BWD_WEIGHT))
+    mxc.mxc_conv2d_bwd_weight_prepared_input(*dims, dt, lay, xp, d_dy, dw1, mxc.MXC_F32, q(mxc.MXC_BWD_WEIGHT_PREPARED_INPUT))
+    torch.cuda.synchronize()
+    assert torch.equal(dw0.view(torch.int32), dw1.view(torch.int32)), mxc.mxc_last_variant()
+
+
+@pytest.mark.parametrize("li", [6, 7])
+def test_full_size_transform_domain_forward(mxc, oracle, li):
+    """The transform-domain 3x3 forward on VGG conv5_1 / conv5_2 at full size: sampled outputs against the oracle
+    (spec tolerance; its per-element budget is checked on whole small tensors elsewhere)."""
+    cfg = gen.CONFIGS[3]
+    L, t = gen.layer_inputs(cfg, li)
+    x, w = t["x"], t["w"]
+    N, C, H, W, K, R, S, st, pad = dims = L.dims()
+    dt, lay = mxc.MXC_BF16, mxc.MXC_NHWC
+    nhwc = lambda a: gen.to_device(a, "bf16").view(*a.shape).permute(0, 2, 3, 1).contiguous().view(-1)
+    y = torch.full((N * K * L.P * L.Q,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = mxc.alloc_workspace(mxc.mxc_conv2d_workspace_bytes(mxc.MXC_FWD_TRANSFORM, *dims, dt, lay))
+    mxc.mxc_conv2d_fwd_transform(*dims, dt, lay, nhwc(x), nhwc(w), None, 0, y, ws)
+    rng = np.random.Generator(np.random.Philox(key=gen.SEED + 6000 + li))
+    idx = _sample(rng, (N, K, L.P, L.Q), ([0, N - 1], [0, K // 2, K - 1], _edge(L.P), _edge(L.Q)), 4096)
+    ref, den = oracle.conv2d_fwd_at(x, w, st, pad, idx)
+    got = _gather(y, _nchw_to_nhwc_index(idx, (N, K, L.P, L.Q)))
+    assert not np.any(np.isnan(got))
+    assert util.metric(got, ref, den) <= util.TOL["bf16"], L.name
+
+
 def test_tensors_beyond_2gib(mxc, oracle):
     """Maximum sizes: activation tensors of more than 2^31 bytes.  The matrix-core kernels address
     operands with signed 32-bit byte offsets and decline such tensors; the call must then run on the
