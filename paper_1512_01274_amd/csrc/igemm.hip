@@ -430,8 +430,10 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
     }
     if ((p.Co & 7) == 0) {
         // Through LDS, one 32-row block of the wave tile at a time, so that global stores are 16 bytes per lane and
-        // a row's WN channels leave as one contiguous run.  Staged rows are padded by 16 bytes: the 8-byte writes of
-        // 32 rows then spread over the banks.
+        // a row's WN channels leave as one contiguous run.  Staged rows are padded by 16 bytes, and 8-byte unit u of
+        // row r sits at u ^ ((r >> 3) % 4): the 32 rows that one 8-byte write instruction covers then fall on 16
+        // different bank pairs (two rows each: the least 256 bytes over 128 bytes of banks allow).  A 16-byte chunk c
+        // of row r is therefore found at chunk c ^ ((r >> 4) % 2), its halves exchanged when bit 3 of r is set.
         constexpr int CPR = WN / 8;                   // 16-byte chunks per staged row
         constexpr int PW = WN + 8;                    // staged row pitch, elements
         constexpr int RS = 32 * PW;                   // staging elements per wave
@@ -468,7 +470,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
                         pk.x = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pk.x), s16x2{0, 0}));
                         pk.y = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pk.y), s16x2{0, 0}));
                     }
-                    *reinterpret_cast<uint2 *>(stg + frag_row * PW + j * 32 + 8 * g4 + 4 * frag_kg) = pk;
+                    *reinterpret_cast<uint2 *>(stg + frag_row * PW + 4 * ((j * 8 + 2 * g4 + frag_kg) ^ ((frag_row >> 3) & 3))) = pk;
                 }
         };
         // Common case (output pixel index == GEMM row, no mask, output below 2 GiB, a store instruction covers whole
@@ -477,8 +479,12 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
         constexpr bool ROWS_PER_STORE_OK = 64 % CPR == 0;
         constexpr int RPI = ROWS_PER_STORE_OK ? 64 / CPR : 1;
         const bool fast_store = ROWS_PER_STORE_OK && p.linear_out && p.mask == nullptr && p.out_bytes != 0;
-        const buf_rsrc_t rs_out = make_buf_rsrc(p.out, p.out_bytes);
+        const out_rsrc_t rs_out = make_out_rsrc(p.out, p.out_bytes);
         const int st_r = lane / CPR, st_c = lane % CPR;
+        auto staged_chunk = [&](int r, int c) __attribute__((always_inline)) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * PW + ((c ^ ((r >> 4) & 1)) << 3));
+            return ((r >> 3) & 1) ? make_uint4(v.z, v.w, v.x, v.y) : v;
+        };
         const bool st_col_ok = n0 + wave_n + st_c * 8 < p.Co;
         const unsigned st_lane_off = (unsigned)((st_r * p.Co + n0 + wave_n + st_c * 8) * 2);
 #pragma unroll
@@ -494,7 +500,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
                 const int rows_left = p.m_end - mb;
 #pragma unroll
                 for (int k = 0; k < 32 / RPI; ++k) {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + (st_r + k * RPI) * PW + st_c * 8);
+                    const uint4 v = staged_chunk(st_r + k * RPI, st_c);
                     const bool ok = st_col_ok && st_r + k * RPI < rows_left;
                     const unsigned off = ok ? st_lane_off + blk_off + (unsigned)(k * RPI * p.Co * 2) : OOB;
                     if (p.nt_out) buffer_store16_nt(rs_out, off, v);
@@ -506,7 +512,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC == 4 && NS * (BM + BN) * BKT
                     const int idx = k * 64 + lane;
                     const int r = idx / CPR, c = idx % CPR;
                     const int m = m0 + wave_m + i * 32 + r, co = n0 + wave_n + c * 8;
-                    uint4 v = *reinterpret_cast<const uint4 *>(stg + r * PW + c * 8);
+                    uint4 v = staged_chunk(r, c);
                     if (m < p.m_end && co < p.Co) {
                         const long long off = out_pixel(m) * p.Co + co;
                         if (p.mask != nullptr) {

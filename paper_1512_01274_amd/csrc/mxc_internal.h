@@ -101,21 +101,23 @@ __device__ __forceinline__ void lds_dma16_nt(buf_rsrc_t rsrc, unsigned byte_off,
                  : "s"(lds_addr), "v"(byte_off), "s"(rsrc)
                  : "memory");
 }
-__device__ __forceinline__ void buffer_store16_nt(buf_rsrc_t rsrc, unsigned byte_off, uint4 v)
-{
-    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 d = {v.x, v.y, v.z, v.w};
-    asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen nt\n\ts_nop 0" : : "v"(d), "v"(byte_off), "s"(rsrc) : "memory");
-}
-
 // 16-byte store through a buffer resource: a lane whose byte_off lies beyond the resource's size writes nothing,
-// which takes the place of a bounds branch.  (The wait state after it covers the rule that the data registers
-// of a store wider than 8 bytes are not overwritten by the very next instruction.)
-__device__ __forceinline__ void buffer_store16(buf_rsrc_t rsrc, unsigned byte_off, uint4 v)
+// which takes the place of a bounds branch.  These are compiler builtins, not inline assembly, so that the compiler
+// itself keeps the wait states between a store wider than 8 bytes and the next write of its data registers.
+typedef __amdgpu_buffer_rsrc_t out_rsrc_t;
+__device__ __forceinline__ out_rsrc_t make_out_rsrc(void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);     // stride 0: raw buffer
+}
+__device__ __forceinline__ void buffer_store16(out_rsrc_t rsrc, unsigned byte_off, uint4 v)
 {
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 d = {v.x, v.y, v.z, v.w};
-    asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen\n\ts_nop 0" : : "v"(d), "v"(byte_off), "s"(rsrc) : "memory");
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4{v.x, v.y, v.z, v.w}, rsrc, (int)byte_off, 0, 0);
+}
+__device__ __forceinline__ void buffer_store16_nt(out_rsrc_t rsrc, unsigned byte_off, uint4 v)
+{
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4{v.x, v.y, v.z, v.w}, rsrc, (int)byte_off, 0, 2);   // 2: non-temporal
 }
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

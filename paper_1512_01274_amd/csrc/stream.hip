@@ -248,7 +248,13 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
     const bf16_t *a_base = sA + (wave * 32 + frag_row) * BK;
     const bf16_t *b_base = sB + frag_row * BK;
     bf16_t *stg = sE + wave * 32 * EW;
-    constexpr int CPR = EW / 8;                     // 16-byte chunks per staged row; chunk c of row r sits at c ^ (r % CPR)
+    // Staging layout: a row holds CPR 16-byte chunks; chunk c of row r sits at position c ^ ((r >> LB) % CPR) and
+    // its two 8-byte halves change places when bit 3 of r is set.  The 32 rows that one 8-byte write instruction
+    // covers then fall on 16 different bank pairs (two rows each: the least 256 bytes over 128 bytes of banks allow).
+    constexpr int CPR = EW / 8;
+    constexpr int LB = EW == 64 ? 0 : 1;            // log2 of the rows that share one 128-byte line of banks
+    auto stg_chunk = [](int r, int c) __attribute__((always_inline)) { return (c ^ ((r >> LB) & (CPR - 1))) << 3; };
+    auto swap_halves = [](uint4 v, bool sw) __attribute__((always_inline)) { return sw ? make_uint4(v.z, v.w, v.x, v.y) : v; };
     constexpr int JN = EW / 32;                     // accumulator blocks per staging pass
 
     f32x16 acc[NI];
@@ -276,7 +282,7 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
                     pk.x = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pk.x), s16x2{0, 0}));
                     pk.y = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pk.y), s16x2{0, 0}));
                 }
-                *reinterpret_cast<uint2 *>(stg + frag_row * EW + ((c ^ (frag_row & (CPR - 1))) << 3) + 4 * frag_kg) = pk;
+                *reinterpret_cast<uint2 *>(stg + frag_row * EW + stg_chunk(frag_row, c) + 4 * (frag_kg ^ ((frag_row >> 3) & 1))) = pk;
             }
         }
     };
@@ -300,12 +306,12 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
 
     // Stores of the common case (output pixel index == GEMM row, no mask): one buffer store per 8 staged rows;
     // rows past the end of this workgroup's range and columns past Co get an offset the resource rejects.
-    const buf_rsrc_t rs_out = make_buf_rsrc(p.out, sp.out_bytes);
+    const out_rsrc_t rs_out = make_out_rsrc(p.out, sp.out_bytes);
     const bool fast_store = p.linear_out && p.mask == nullptr;
     constexpr int RPI = 64 / CPR;                   // staged rows per store instruction
     const int st_r = lane / CPR, st_c = lane % CPR;
     const unsigned st_lane_off = (unsigned)((st_r * p.Co + n0 + st_c * 8) * 2);
-    const bf16_t *st_src = stg + st_r * EW + ((st_c ^ (st_r & (CPR - 1))) << 3);   // RPI is a multiple of CPR: same swizzle for every k
+    const bf16_t *st_src = stg + st_r * EW + stg_chunk(st_r, st_c);   // RPI is a multiple of CPR << LB: same chunk position for every k
 
     wait_vmcnt<0>();                                // this wave's share of the filter
     wg_barrier();                                   // filter and stage 0 complete
@@ -349,7 +355,7 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
                 const int rows_left = wg_hi - m0;
 #pragma unroll
                 for (int k = 0; k < 32 / RPI; ++k) {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(st_src + k * RPI * EW);
+                    const uint4 v = swap_halves(*reinterpret_cast<const uint4 *>(st_src + k * RPI * EW), ((st_r + k * RPI) >> 3) & 1);
                     const bool ok = col_ok && st_r + k * RPI < rows_left;
                     if (sp.nt & 1) buffer_store16_nt(rs_out, ok ? st_lane_off + tile_off + (unsigned)(k * RPI * p.Co * 2) : OOB, v);
                     else buffer_store16(rs_out, ok ? st_lane_off + tile_off + (unsigned)(k * RPI * p.Co * 2) : OOB, v);
@@ -360,7 +366,7 @@ __global__ __launch_bounds__(64 * (NC + NL)) void stream_kernel(const StreamPara
                 const int idx = k * 64 + lane;
                 const int r = idx / CPR, c = idx % CPR;
                 const int m = m0 + r, co = n0 + jc * 64 + c * 8;
-                uint4 v = *reinterpret_cast<const uint4 *>(stg + r * EW + ((c ^ (r & (CPR - 1))) << 3));
+                uint4 v = swap_halves(*reinterpret_cast<const uint4 *>(stg + r * EW + stg_chunk(r, c)), (r >> 3) & 1);
                 if (m < wg_hi && co < p.Co) {
                     long long pix = m;
                     if (!p.linear_out) {
