@@ -615,6 +615,7 @@ const TileChoice kTiles[] = {
     {192, 256, 64, 1, 1.05f, "igemm_192x256_k64s2_w8"},
     {64, 256, 64, 1, 0.55f, "igemm_64x256_k64s3_w8"},
     {64, 128, 64, 2, 0.45f, "igemm_64x128_k64s3_w4"},
+    {192, 128, 64, 1, 0.90f, "igemm_192x128_k64s3_w8"},
 };
 constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
 // plan index of the streaming kernel (stream.hip): not a tile of this file's kernel, one launch for all rows
@@ -646,7 +647,8 @@ int launch_choice(int idx, const IgemmParams &p, hipStream_t st, bool bt = false
     case 8: return launch<256, 192, 64, 2, 4, 2>(p, st, m_begin, m_end);
     case 9: return launch<192, 256, 64, 2, 2, 4>(p, st, m_begin, m_end);
     case 10: return launch<64, 256, 64, 3, 2, 4>(p, st, m_begin, m_end);
-    default: return launch<64, 128, 64, 3, 2, 2>(p, st, m_begin, m_end);
+    case 11: return launch<64, 128, 64, 3, 2, 2>(p, st, m_begin, m_end);
+    default: return launch<192, 128, 64, 3, 2, 4>(p, st, m_begin, m_end);
     }
 }
 

@@ -14,6 +14,8 @@
 //     R*S*C scattered triples, and no bounds test can fail.  The filter is laid out to match:
 //     [K][R][run], run = S*pix rounded up to 8, zeros where s >= S or c >= C.
 // Pure data movement (bf16 bit patterns).
+#include <type_traits>
+
 #include "mxc_internal.h"
 
 namespace mxc {
@@ -208,16 +210,31 @@ __global__ __launch_bounds__(256) void s2d_stage_pack_kernel(const bf16_t *__res
     const int row_dw = W * C / 2;                    // dwords per image row
     const int pitch = (row_dw + 3) & ~3;
     const int run_dw = s * C / 2;
-    for (int dh = 0; dh < s; ++dh) {
-        const int h = h2 * s + dh - pad;
-        if (h < 0 || h >= H) continue;               // uniform over the workgroup
-        const uint32_t *src = reinterpret_cast<const uint32_t *>(x + ((n * H + h) * W) * (long long)C);
-        uint32_t *l = s2d_lds + dh * pitch;
-        if (V16) {
-            for (int i = threadIdx.x; i < row_dw / 4; i += 256)
-                reinterpret_cast<uint4 *>(l)[i] = reinterpret_cast<const uint4 *>(src)[i];
-        } else {
-            for (int i = threadIdx.x; i < row_dw; i += 256) l[i] = src[i];
+    // all s image rows as one index space, up to NU loads in flight per thread before the first LDS write
+    using T = std::conditional_t<V16, uint4, uint32_t>;
+    const int per_row = V16 ? row_dw / 4 : row_dw;   // load units per image row
+    const int lds_row = V16 ? pitch / 4 : pitch;
+    const int total = s * per_row;
+    constexpr int NU = 4;
+    for (int base = threadIdx.x; base < total; base += 256 * NU) {
+        T v[NU];
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int idx = base + u * 256;
+            v[u] = T{};
+            if (idx < total) {
+                const int dh = idx / per_row, i = idx - dh * per_row;
+                const int h = h2 * s + dh - pad;
+                if (h >= 0 && h < H) v[u] = reinterpret_cast<const T *>(x + ((n * H + h) * W) * (long long)C)[i];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int idx = base + u * 256;
+            if (idx < total) {
+                const int dh = idx / per_row, i = idx - dh * per_row;
+                reinterpret_cast<T *>(s2d_lds)[dh * lds_row + i] = v[u];
+            }
         }
     }
     __syncthreads();

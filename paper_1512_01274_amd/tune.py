@@ -29,6 +29,7 @@ IGEMM_TILES = {  # name -> (bm, bn, workgroups per CU)
     "igemm_128x32_k64s2_w4": (128, 32, 4), "igemm_256x32_k64s2_w4": (256, 32, 2),
     "igemm_256x192_k64s2_w8": (256, 192, 1), "igemm_192x256_k64s2_w8": (192, 256, 1),
     "igemm_64x256_k64s3_w8": (64, 256, 1), "igemm_64x128_k64s3_w4": (64, 128, 2),
+    "igemm_192x128_k64s3_w8": (192, 128, 1),
 }
 WGRAD_TILES = {  # name -> (bm, bn, bp, workgroups per CU)
     "wgrad_128x128_p64s2_w4": (128, 128, 64, 2), "wgrad_256x256_p32s4_w8": (256, 256, 32, 1),
