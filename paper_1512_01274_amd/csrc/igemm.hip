@@ -621,6 +621,10 @@ constexpr int N_TILE_CHOICES = sizeof(kTiles) / sizeof(kTiles[0]);
 // plan index of the streaming kernel (stream.hip): not a tile of this file's kernel, one launch for all rows
 constexpr int STREAM_TILE = N_TILE_CHOICES;
 const char *const kStreamName = "igemm_stream";
+// ... and of the window kernel (window.hip), likewise
+constexpr int WINDOW_TILE = N_TILE_CHOICES + 1;
+const char *const kWindowName = "igemm_window";
+inline bool whole_launch(int idx) { return idx == STREAM_TILE || idx == WINDOW_TILE; }
 
 // the tiles that also exist reading a 1x1 filter in place (transposed tiles)
 bool has_bt(int idx) { return idx == 0 || idx == 1 || idx == 4; }
@@ -662,6 +666,7 @@ int tile_index(const char *name, size_t len)
     for (int i = 0; i < N_TILE_CHOICES; ++i)
         if (strlen(kTiles[i].name) == len && !strncmp(name, kTiles[i].name, len)) return i;
     if (strlen(kStreamName) == len && !strncmp(name, kStreamName, len)) return STREAM_TILE;
+    if (strlen(kWindowName) == len && !strncmp(name, kWindowName, len)) return WINDOW_TILE;
     return -1;
 }
 
@@ -703,8 +708,8 @@ Plan choose_plan(long long M, int Co, int Kd, bool allow_stream = true)
         const char *plus = strchr(f, '+');
         const int a = tile_index(f, plus ? (size_t)(plus - f) : strlen(f));
         const int b = plus ? tile_index(plus + 1, strlen(plus + 1)) : -1;
-        if (a == STREAM_TILE && !plus && allow_stream) return Plan{STREAM_TILE, -1, M};
-        if (a >= 0 && a != STREAM_TILE && b != STREAM_TILE && (!plus || b >= 0)) {
+        if (a >= 0 && whole_launch(a) && !plus && allow_stream) return Plan{a, -1, M};
+        if (a >= 0 && !whole_launch(a) && !whole_launch(b) && (!plus || b >= 0)) {
             const long long rows = b >= 0 ? whole_round_rows(kTiles[a], M, Co) : M;
             return (b >= 0 && rows > 0 && rows < M) ? Plan{a, b, rows} : Plan{a, -1, M};
         }
@@ -712,8 +717,8 @@ Plan choose_plan(long long M, int Co, int Kd, bool allow_stream = true)
     for (const TunedIgemm &e : kTunedIgemm)
         if (e.M == M && e.Co == Co && e.Kd == Kd) {
             const int a = tile_index(e.main, strlen(e.main)), b = e.tail[0] ? tile_index(e.tail, strlen(e.tail)) : -1;
-            if (a < 0 || b == STREAM_TILE || (a == STREAM_TILE && !allow_stream)) break;
-            if (a == STREAM_TILE) return Plan{STREAM_TILE, -1, M};
+            if (a < 0 || whole_launch(b) || (whole_launch(a) && !allow_stream)) break;
+            if (whole_launch(a)) return Plan{a, -1, M};
             const long long rows = b >= 0 ? whole_round_rows(kTiles[a], M, Co) : M;
             return (b >= 0 && rows > 0 && rows < M) ? Plan{a, b, rows} : Plan{a, -1, M};
         }
@@ -746,13 +751,16 @@ int choose_tile(long long M, int Co, int Kd) { return choose_plan(M, Co, Kd, fal
 Plan plan_for(const IgemmParams &p, long long M, int Co, int Kd, bool tiles_only = false)
 {
     const Plan pl = choose_plan(M, Co, Kd, !tiles_only);
-    return (pl.main == STREAM_TILE && !stream_applicable(p)) ? choose_plan(M, Co, Kd, false) : pl;
+    if (pl.main == STREAM_TILE && !stream_applicable(p)) return choose_plan(M, Co, Kd, false);
+    if (pl.main == WINDOW_TILE && !window_applicable(p)) return choose_plan(M, Co, Kd, false);
+    return pl;
 }
 
 // runs the plan: one or two launches on the stream
 int launch_plan(const Plan &pl, const IgemmParams &p, hipStream_t st, bool bt = false)
 {
     if (pl.main == STREAM_TILE) return stream_launch(p, st);
+    if (pl.main == WINDOW_TILE) return window_launch(p, st);
     if (pl.tail < 0) return launch_choice(pl.main, p, st, bt);
     const int rc = launch_choice(pl.main, p, st, bt, 0, pl.rows_main);
     if (rc != MXC_OK) return rc;
@@ -764,6 +772,7 @@ const char *plan_name(const Plan &pl)
 {
     static thread_local char name[96];
     if (pl.main == STREAM_TILE) return kStreamName;
+    if (pl.main == WINDOW_TILE) return kWindowName;
     if (pl.tail < 0) return kTiles[pl.main].name;
     snprintf(name, sizeof(name), "%s+%s", kTiles[pl.main].name, kTiles[pl.tail].name);
     return name;
@@ -898,7 +907,7 @@ int launch_split(int tc, IgemmParams p, long long M, int sp, void *split_ws, voi
 }  // namespace
 
 const char *igemm_tile_name(int index) { return index >= 0 && index < N_TILE_CHOICES ? kTiles[index].name : nullptr; }
-const char *igemm_stream_name(int index) { return index == 0 ? kStreamName : nullptr; }
+const char *igemm_stream_name(int index) { return index == 0 ? kStreamName : index == 1 ? kWindowName : nullptr; }
 void igemm_last_plan_key(long long *M, int *Co, int *Kd) { *M = g_key_M; *Co = g_key_Co; *Kd = g_key_Kd; }
 
 size_t igemm_bwd_data_split_bytes(const ConvShape &s)

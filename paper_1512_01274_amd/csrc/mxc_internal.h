@@ -180,7 +180,7 @@ int igemm_bwd_data_smallc(const ConvShape &s, const void *dy, const void *w2, vo
 
 // names of the tile shapes the two MFMA kernel families are built in (nullptr past the last)
 const char *igemm_tile_name(int index);
-const char *igemm_stream_name(int index);   // names of the streaming kernel's plans (one)
+const char *igemm_stream_name(int index);   // names of the whole-launch kernels' plans (streaming kernel, window kernel)
 // key (rows, output columns, reduction length) of the calling thread's last implicit-GEMM plan lookup
 void igemm_last_plan_key(long long *M, int *Co, int *Kd);
 const char *wgrad_tile_name(int index);
@@ -244,6 +244,10 @@ int winograd_fwd(const ConvShape &s, const void *x, const void *w, void *y, void
 // M, row range, tile counts, byte sizes, linear_out, tap_inner - are ignored and recomputed).
 bool stream_applicable(const IgemmParams &p);
 int stream_launch(const IgemmParams &p, hipStream_t st);
+// window.hip: the same GEMM for multi-tap stride-1 layers of at most 64 input channels, from an LDS-resident input
+// window and filter (see there); same conventions as the streaming kernel.
+bool window_applicable(const IgemmParams &p);
+int window_launch(const IgemmParams &p, hipStream_t st);
 
 // ---- prep.hip: re-packing for channel counts that are not a multiple of 8 ---------
 // [rows][C] -> [rows][C8] (C8 = C rounded up to 8, new channels zero); bf16 only.

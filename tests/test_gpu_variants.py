@@ -230,3 +230,73 @@ def test_stream_kernel_declines_long_reductions(mxc, oracle):
     assert "stream" not in mxc.mxc_last_variant()
     ref, den = oracle.conv2d_fwd(x, w, 1, 1), oracle.conv2d_fwd(np.abs(x), np.abs(w), 1, 1)
     assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True))
+
+
+# the window kernel (multi-tap stride-1 layers of at most 64 channels, input window and filter resident in LDS):
+# filters 1x2 to 3x5, every padding up to the filter size, 16 to 64 channels, one and several column tiles, images
+# narrower and wider than a patch row, ragged patches on both axes
+WINDOW_SHAPES = [
+    ((2, 64, 19, 17, 64, 3, 3, 1, 1), ("fwd", "bwd_data")),
+    ((3, 48, 13, 40, 96, 3, 3, 1, 1), ("fwd",)),            # three k-steps, two column tiles (the second ragged)
+    ((3, 96, 13, 40, 48, 3, 3, 1, 1), ("bwd_data",)),       # ... and its mirror image for backward-data
+    ((2, 32, 27, 27, 32, 3, 5, 1, 1), ("fwd", "bwd_data")), # 15 taps, two k-steps, 32-column tile
+    ((1, 16, 40, 36, 16, 3, 3, 1, 1), ("fwd", "bwd_data")), # one k-step
+    ((2, 48, 21, 70, 64, 3, 3, 1, 0), ("fwd", "bwd_data")), # no padding: the output grid is smaller than the input
+    ((2, 64, 21, 23, 48, 3, 3, 1, 2), ("fwd", "bwd_data")), # padding 2: larger
+    ((1, 64, 70, 45, 16, 3, 3, 1, 1), ("fwd", "bwd_data")), # several patches per image, 16 output channels
+    ((5, 64, 9, 11, 64, 3, 3, 1, 1), ("fwd", "bwd_data")),  # images smaller than a patch
+    ((2, 32, 18, 18, 48, 1, 2, 1, 0), ("fwd", "bwd_data")), # two taps: the fewest the kernel takes
+    ((1, 64, 1, 50, 64, 3, 3, 1, 1), ("fwd", "bwd_data")),  # one-row image
+    ((16, 64, 56, 56, 64, 3, 3, 1, 1), ("fwd", "bwd_data")),  # every workgroup walks several patches
+]
+
+
+@pytest.mark.parametrize("dims,passes", WINDOW_SHAPES)
+def test_window_kernel(mxc, oracle, dims, passes):
+    with forced("MXC_FORCE_VARIANT", "igemm_window"):
+        _check(mxc, oracle, dims, passes, "igemm_window")
+
+
+@pytest.mark.parametrize("patch", ["8x32", "4x64", "2x64", "3x32"])
+def test_window_kernel_patch_shapes(mxc, oracle, patch):
+    """Patch shapes forced through the tuning hook (32 output columns: the filter tile leaves room for the wider
+    windows): the result does not depend on how the output grid is cut."""
+    dims = (2, 64, 30, 141, 32, 3, 3, 1, 1)
+    with forced("MXC_FORCE_VARIANT", "igemm_window"), forced("MXC_WINDOW_PATCH", patch):
+        _check(mxc, oracle, dims, ("fwd",), "igemm_window")
+
+
+def test_window_kernel_epilogue(mxc, oracle):
+    """bias + ReLU applied by the window kernel's epilogue; the masked backward-data form is not its to run."""
+    dims = (3, 64, 20, 22, 64, 3, 3, 1, 1)
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy = gen.random_case(78, *dims, dtype="bf16", dist="normal")
+    bias = np.linspace(-1.0, 1.0, K).astype(np.float32)
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    with forced("MXC_FORCE_VARIANT", "igemm_window"):
+        y = torch.empty(N * K * H * W, dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_fwd_bias_act(*dims, run.dt, run.lay, run._in(x), run._in(w), torch.from_numpy(bias).cuda(), 1, y, run._ws(mxc.MXC_FWD))
+        assert mxc.mxc_last_variant().split(":")[-1] == "igemm_window"
+        ref, den = oracle.conv2d_fwd_bias_act(x, w, bias, True, st, pad)
+        got = run._out(y, (N, K, H, W))
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True))
+        dx = torch.empty(N * C * H * W, dtype=torch.bfloat16, device="cuda")
+        mxc.mxc_conv2d_bwd_data_relu(*dims, run.dt, run.lay, run._in(dy), run._in(w), run._in(x), dx, run._ws(mxc.MXC_BWD_DATA_RELU))
+        assert "window" not in mxc.mxc_last_variant()
+        ref, den = oracle.conv2d_bwd_data_relu(dy, w, x, st, pad)
+        got = run._out(dx, (N, C, H, W))
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True))
+
+
+def test_window_kernel_declines(mxc, oracle):
+    """1x1 filters, strided layers, more than 64 channels and channel counts that are not a multiple of 16: the
+    forced name is ignored and a tile of the other kernel runs."""
+    for dims in [(2, 64, 12, 12, 64, 1, 1, 1, 0), (2, 64, 12, 12, 64, 3, 3, 2, 1), (2, 40, 12, 12, 64, 3, 3, 1, 1), (2, 80, 12, 12, 64, 3, 3, 1, 1)]:
+        N, C, H, W, K, R, S, st, pad = dims
+        x, w, dy = gen.random_case(6, *dims, dtype="bf16", dist="normal")
+        run = util.Runner(mxc, dims, "bf16", "nhwc")
+        with forced("MXC_FORCE_VARIANT", "igemm_window"):
+            got = run.fwd(x, w)
+        assert "window" not in mxc.mxc_last_variant()
+        ref, den = oracle.conv2d_fwd(x, w, st, pad), oracle.conv2d_fwd(np.abs(x), np.abs(w), st, pad)
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), dims
