@@ -328,8 +328,9 @@ const char *mxc_last_variant(void);
 int mxc_version(void);
 
 /* Tuning aid: name of the index-th tile shape the matrix-core kernels are built in (family 0: forward /
- * backward-data implicit GEMM, family 1: backward-weight, family 2: the streaming implicit GEMM for short
- * reductions, which has one plan and runs only where the filter tile fits on chip), NULL past the last.  These are the names that
+ * backward-data implicit GEMM, family 1: backward-weight, family 2: the whole-launch implicit GEMMs - "igemm_stream"
+ * for short reductions and "igemm_window" for multi-tap stride-1 layers of at most 64 channels, each one plan that
+ * runs only where its filter tile fits on chip), NULL past the last.  These are the names that
  * mxc_last_variant() reports and that the tuning hooks MXC_FORCE_VARIANT=<name>[+<name of the shape for the
  * rows the last whole round leaves>] and MXC_FORCE_WGRAD=<name>[/<splits>] (environment, read per call) accept;
  * the tuning script and the tests walk the list.  Static host memory. */

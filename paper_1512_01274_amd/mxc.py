@@ -114,7 +114,7 @@ def mxc_last_plan_key():
 
 
 def mxc_tile_names(family: int):
-    """Names of the tile shapes of a kernel family (0: implicit GEMM, 1: backward-weight, 2: streaming implicit GEMM)."""
+    """Names of the tile shapes of a kernel family (0: implicit GEMM, 1: backward-weight, 2: the streaming and the window implicit GEMM)."""
     out, i = [], 0
     while True:
         n = _lib.mxc_tile_name(family, i)
