@@ -300,3 +300,43 @@ def test_window_kernel_declines(mxc, oracle):
         assert "window" not in mxc.mxc_last_variant()
         ref, den = oracle.conv2d_fwd(x, w, st, pad), oracle.conv2d_fwd(np.abs(x), np.abs(w), st, pad)
         assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), dims
+
+
+def _random_window_shapes(count):
+    """Multi-tap stride-1 problems drawn at random (fixed seed): 1x2 to 3x3 filters, every padding up to the filter
+    size, 16 to 64 channels in steps of 16 on the reduction side, 8 to 136 output channels, images from 1 to 90
+    pixels a side, batches 1-9."""
+    rng = np.random.Generator(np.random.Philox(key=20251))
+    out = []
+    while len(out) < count:
+        R, S = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        pad = int(rng.integers(0, max(R, S)))
+        H, W = int(rng.integers(1, 91)), int(rng.integers(1, 91))
+        C, K = 16 * int(rng.integers(1, 5)), 8 * int(rng.integers(1, 18))
+        N = int(rng.choice([1, 2, 3, 9]))
+        if R * S < 2 or H + 2 * pad < R or W + 2 * pad < S or N * H * W > 40000:
+            continue
+        out.append((N, C, H, W, K, R, S, 1, pad))
+    return out
+
+
+@pytest.mark.parametrize("dims", _random_window_shapes(30))
+def test_window_kernel_random_shapes(mxc, oracle, dims):
+    """The window kernel asked for on random problems; forward always fits it (at most 64 input channels), backward-
+    data where K is a multiple of 16 up to 64 - elsewhere the tiled kernel runs; either way the result must match
+    the oracle."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x, w, dy = gen.random_case(hash(dims) & 0xFFFF, *dims, dtype="bf16", dist="normal")
+    run = util.Runner(mxc, dims, "bf16", "nhwc")
+    with forced("MXC_FORCE_VARIANT", "igemm_window"):
+        got = run.fwd(x, w)
+        v1 = mxc.mxc_last_variant()
+        assert v1.endswith("igemm_window"), (dims, v1)
+        ref, den = oracle.conv2d_fwd(x, w, st, pad), oracle.conv2d_fwd(np.abs(x), np.abs(w), st, pad)
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), (dims, v1)
+        got = run.bwd_data(dy, w)
+        v2 = mxc.mxc_last_variant()
+        assert v2.endswith("igemm_window") == (K % 16 == 0 and K <= 64 and C % 8 == 0), (dims, v2)
+        ref = oracle.conv2d_bwd_data(dy, w, x.shape, st, pad)
+        den = oracle.conv2d_bwd_data(np.abs(dy), np.abs(w), x.shape, st, pad)
+        assert np.all(np.abs(got - ref) <= util.tight_bound(ref, den, "bf16", True)), (dims, v2)
