@@ -697,7 +697,8 @@ double model_time(const TileChoice &t, long long M, int Co, int KT, double fixed
 // Plan choice, in this order: MXC_FORCE_VARIANT=<name> or <main>+<tail> (tuning sweeps only); the table of
 // measured best plans (tuned_igemm.inc, written by the tuning script from timings on the device) when it
 // holds this GEMM; else the least modelled time over single shapes and main+tail pairs.
-// allow_stream = false: callers that need a tile of this file's kernel (split reductions, in-place filters).
+// allow_stream = false: callers that need a tile of this file's kernel, not one of the whole-launch kernels (split
+// reductions, in-place filters).
 thread_local long long g_key_M = 0;
 thread_local int g_key_Co = 0, g_key_Kd = 0;
 
@@ -747,7 +748,7 @@ Plan choose_plan(long long M, int Co, int Kd, bool allow_stream = true)
 
 int choose_tile(long long M, int Co, int Kd) { return choose_plan(M, Co, Kd, false).main; }
 
-// the plan for one launch site: the streaming kernel only where it can run the problem
+// the plan for one launch site: the streaming or the window kernel only where it can run the problem
 Plan plan_for(const IgemmParams &p, long long M, int Co, int Kd, bool tiles_only = false)
 {
     const Plan pl = choose_plan(M, Co, Kd, !tiles_only);

@@ -46,7 +46,7 @@ def ceil_div(a, b):
 
 def igemm_candidates(M, Co):
     """Single shapes whose column tile is not mostly padding, main+tail pairs where the main shape has
-    at least one whole round and leaves rows over, and the streaming kernel (the library declines it where
+    at least one whole round and leaves rows over, and the streaming and the window kernel (the library declines one where
     the filter tile does not fit on chip; such a timing is discarded)."""
     ok = [n for n, (bm, bn, _) in IGEMM_TILES.items() if bn <= 2 * max(Co, 32) and (bn <= 64 or bn * 3 <= Co * 4 or bn <= Co)]
     out = list(ok) + mxc.mxc_tile_names(2)
