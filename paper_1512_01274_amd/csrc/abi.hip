@@ -788,7 +788,7 @@ void mxc_last_plan_key(long long *M, int *Co, int *Kd)
     if (Kd) *Kd = kd;
 }
 
-int mxc_version(void) { return 300; }
+int mxc_version(void) { return 400; }
 
 const char *mxc_tile_name(int family, int index)
 {
